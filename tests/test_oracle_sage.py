@@ -1,0 +1,94 @@
+"""Pins for the oracle's GraphSAGE-mean forward pass."""
+import numpy as np
+
+import oracle
+
+
+def _dense_forward(blk, x, w_self, w_neigh, bias):
+    """Independent formulation: per layer build the row-normalised sampled adjacency D^-1 A_s
+    as a dense matrix and use matrix products (numpy, fp64)."""
+    L = len(w_self)
+    x = x.astype(np.float64)
+    for l in range(L):
+        h = L - 1 - l
+        n_dst, n_src = int(blk.n_nodes[h]), int(blk.n_nodes[h + 1])
+        A = np.zeros((n_dst, n_src))
+        rows = np.repeat(np.arange(n_dst), np.diff(blk.blk_indptr[h]))
+        np.add.at(A, (rows, blk.blk_src[h]), 1.0)
+        d = A.sum(axis=1, keepdims=True)
+        A = np.divide(A, d, out=np.zeros_like(A), where=d > 0)
+        y = x[:n_dst] @ w_self[l].astype(np.float64) + (A @ x[:n_src]) @ w_neigh[l].astype(np.float64) + bias[l]
+        x = np.maximum(y, 0.0) if l != L - 1 else y
+    return x
+
+
+def test_matches_dense_formulation(tiny):
+    w = tiny["w"]
+    blk = oracle.sample_khop(tiny["indptr"], tiny["indices"], tiny["seeds"][:64], 0, w.fanouts, w.rng_seed)
+    x = tiny["feat"][blk.nodes]
+    got = oracle.sage_forward(blk, x, tiny["w_self"], tiny["w_neigh"], tiny["bias"])
+    want = _dense_forward(blk, x, tiny["w_self"], tiny["w_neigh"], tiny["bias"])
+    assert got.shape == (64, w.classes)
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-12)
+    assert np.abs(got).max() > 0.1
+
+
+def test_three_layers_with_empty_rows(small_graphs):
+    indptr, indices = small_graphs[3]              # has nodes without in-neighbours
+    rng = np.random.default_rng(5)
+    seeds = np.array([0, 1, 3, 4], dtype=np.int64)
+    blk = oracle.sample_khop(indptr, indices, seeds, 1, (2, 2, 2), 4)
+    dims = [6, 5, 4, 3]
+    x = rng.standard_normal((len(blk.nodes), dims[0])).astype(np.float32)
+    ws = [rng.standard_normal((dims[i], dims[i + 1])).astype(np.float32) for i in range(3)]
+    wn = [rng.standard_normal((dims[i], dims[i + 1])).astype(np.float32) for i in range(3)]
+    bs = [rng.standard_normal(dims[i + 1]).astype(np.float32) for i in range(3)]
+    got = oracle.sage_forward(blk, x, ws, wn, bs)
+    assert np.allclose(got, _dense_forward(blk, x, ws, wn, bs), rtol=1e-12, atol=1e-12)
+
+
+def test_identity_self_weight_returns_input_rows(tiny):
+    w = tiny["w"]
+    blk = oracle.sample_khop(tiny["indptr"], tiny["indices"], tiny["seeds"][:32], 0, (5,), w.rng_seed)
+    x = tiny["feat"][blk.nodes]
+    F = w.feat_dim
+    got = oracle.sage_forward(blk, x, [np.eye(F, dtype=np.float32)], [np.zeros((F, F), dtype=np.float32)],
+                              [np.zeros(F, dtype=np.float32)])
+    assert np.array_equal(got, x[:32].astype(np.float64))      # no ReLU after the last layer
+    # identity on the neighbour side instead: logits are the sampled neighbours' mean
+    got = oracle.sage_forward(blk, x, [np.zeros((F, F), dtype=np.float32)], [np.eye(F, dtype=np.float32)],
+                              [np.zeros(F, dtype=np.float32)])
+    for i in range(32):
+        e0, e1 = blk.blk_indptr[0][i], blk.blk_indptr[0][i + 1]
+        want = x[blk.blk_src[0][e0:e1]].astype(np.float64).mean(axis=0) if e1 > e0 else np.zeros(F)
+        assert np.allclose(got[i], want, rtol=1e-13, atol=1e-13)
+
+
+def test_all_ones_features(tiny):
+    w = tiny["w"]
+    blk = oracle.sample_khop(tiny["indptr"], tiny["indices"], tiny["seeds"][:32], 0, (5,), w.rng_seed)
+    x = np.ones((len(blk.nodes), w.feat_dim), dtype=np.float32)
+    ws, wn, b = tiny["w_self"][0], tiny["w_neigh"][0], tiny["bias"][0]
+    got = oracle.sage_forward(blk, x, [ws], [wn], [b])
+    has = np.diff(blk.blk_indptr[0]) > 0
+    want_full = ws.astype(np.float64).sum(0) + wn.astype(np.float64).sum(0) + b
+    want_empty = ws.astype(np.float64).sum(0) + b
+    assert has.any()
+    assert np.allclose(got[has], want_full, rtol=1e-12)
+    if (~has).any():
+        assert np.allclose(got[~has], want_empty, rtol=1e-12)
+
+
+def test_relu_between_layers_only():
+    # one destination, one neighbour; weights chosen so the hidden value is negative
+    from oracle import Blocks
+    blk = Blocks(n_nodes=np.array([1, 1, 2]), n_edges=np.array([0, 1]), nodes=np.array([0, 1]),
+                 blk_indptr=[np.array([0, 0]), np.array([0, 1])], blk_src=[np.array([], dtype=np.int32),
+                                                                          np.array([1], dtype=np.int32)],
+                 src_global=[], src_pos=[])
+    x = np.array([[1.0], [3.0]], dtype=np.float32)
+    one, neg, zero = (np.array([[v]], dtype=np.float32) for v in (1.0, -1.0, 0.0))
+    b0 = np.zeros(1, dtype=np.float32)
+    # layer 0 on block 1: y = 1*(-1) + 3*(-1) = -4 -> ReLU -> 0 ; layer 1 on block 0: 0*1 + 0 - 2 = -2 (kept)
+    got = oracle.sage_forward(blk, x, [neg, one], [neg, zero], [b0, np.array([-2.0], dtype=np.float32)])
+    assert got.tolist() == [[-2.0]]
