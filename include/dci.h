@@ -1,0 +1,229 @@
+/*
+ * dci.h - C boundary of the MI355X (gfx950) implementation of the dual-cache GNN inference
+ * hot path of DCI (arXiv 2503.01281): pre-sampling access counting, the workload-aware
+ * dual-cache fill, cache-aware multi-hop neighbour sampling, cache-aware feature gathering
+ * and a GraphSAGE-mean forward pass.
+ *
+ * General rules
+ *  - C linkage, plain pointers and sizes.  Every call returns a status (0 = DCI_OK, negative =
+ *    error) and never throws or aborts; dci_last_error() gives the message of the last failure
+ *    on that context.
+ *  - The caller owns every buffer.  "device" pointers are HBM allocations on the context's GPU.
+ *    "mapped" pointers may be HBM or pinned host memory that the GPU can dereference
+ *    (hipHostMalloc / a pinned PyTorch tensor): the graph and the feature matrix normally live
+ *    there and are read by zero-copy on a cache miss (Section IV, framework paragraph).
+ *  - The library allocates nothing.  Temporary device memory comes from the workspace handed to
+ *    dci_create(); the dci_*_workspace_bytes() queries say how much each call needs.
+ *  - Calls enqueue work on the context's HIP stream and return without waiting, except
+ *    dci_fill_caches(), which waits for completion because the cache sizes it reports are
+ *    computed on the GPU.  Device outputs, and host outputs marked "valid after dci_sync", may be
+ *    read after dci_sync() (or any synchronisation of that stream).  Calls on one context must
+ *    not overlap in time on different host threads.
+ *  - Node ids are int64 (global) or int32 (local to a mini-batch), counters are uint32,
+ *    features and weights are fp32, row-major.
+ *  - Fan-outs are given in execution order, from the seed nodes outward (the paper prints them
+ *    in layer order, e.g. "15,10,5" = fan-outs {5,10,15} here).
+ */
+#ifndef DCI_H_
+#define DCI_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DCI_MAX_HOPS 8
+#define DCI_MAX_FANOUT 64
+
+#define DCI_OK 0
+#define DCI_ERR_INVALID_ARG (-1) /* NULL pointer, negative size, fan-out out of range, ...          */
+#define DCI_ERR_CAPACITY (-2)    /* a caller buffer or the workspace is too small (see message)      */
+#define DCI_ERR_HIP (-3)         /* a HIP runtime call failed                                        */
+#define DCI_ERR_UNSUPPORTED (-4) /* a size beyond what the kernels index (e.g. more than 2^31 nodes) */
+
+#define DCI_FEAT_POLICY_PAPER_MEAN 0 /* above-average nodes first, then the rest (Section IV-B)     */
+#define DCI_FEAT_POLICY_TOPK 1       /* nodes by visit count, descending                            */
+
+typedef struct dci_ctx dci_ctx;
+
+/* The graph and its features (Section II-C).  The adjacency structure is the compressed
+ * sparse column form of the paper with the target node as the column: the in-neighbours of
+ * node v are indices[indptr[v] .. indptr[v+1]).  Unweighted, so there is no Values array. */
+typedef struct {
+  int64_t num_nodes;      /* N, 1 .. 2^31-1                                   */
+  int64_t num_edges;      /* E = indptr[N]                                    */
+  int32_t feat_dim;       /* F >= 1                                           */
+  const int64_t* indptr;  /* [N+1] mapped, borrowed                           */
+  const int64_t* indices; /* [E]   mapped, borrowed                           */
+  const float* feat;      /* [N,F] mapped, borrowed (may be NULL for sampling-only calls) */
+} dci_graph;
+
+/* The dual cache (Section IV).  Filled by dci_fill_caches(); all pointers are device memory.
+ * A NULL dci_cache* argument means "no cache": every access takes the miss path. */
+typedef struct {
+  int64_t adj_nodes;      /* K: nodes whose neighbour lists are cached                  */
+  int64_t adj_edges;      /* M: cached list elements                                    */
+  int64_t feat_rows;      /* k: cached feature rows                                     */
+  uint64_t adj_bytes;     /* 8*(K+1) + 8*M                                              */
+  uint64_t feat_bytes;    /* 4*F*k                                                      */
+  uint64_t cap_adj_bytes; /* C_adj of Eq. (1) after spill-over                          */
+  uint64_t cap_feat_bytes;/* C_feat of Eq. (1) after spill-over                         */
+  const int32_t* adj_remap;  /* [N] slot in the adjacency cache, or -1                  */
+  const int64_t* c_indptr;   /* [K+1]                                                   */
+  const int64_t* c_indices;  /* [M] the cached lists, each in its original order        */
+  const int32_t* feat_remap; /* [N] row in the feature cache, or -1                     */
+  const float* feat_cache;   /* [k,F]                                                   */
+} dci_cache;
+
+/* One sampled mini-batch: L bipartite blocks and the node lists F_0 (seeds) .. F_L (input
+ * nodes).  F_h is the prefix of `nodes` of length n_nodes[h]; F_{h+1} is F_h followed by the
+ * nodes first reached at hop h, in the order of their first appearance over the hop's edges
+ * taken row by row.  Block h has one row per node of F_h; row i holds the local ids (indices
+ * into F_{h+1}) of the neighbours sampled for F_h[i].
+ * All arrays are caller-allocated device memory with at least the capacities that
+ * dci_blocks_bounds() returns for the call's (n_seeds, fanouts).  The sizes of the batch are
+ * produced on the GPU, in `counts`: n_nodes[h] = counts[h] (h = 0..L) and
+ * n_edges[h] = counts[DCI_MAX_HOPS + 1 + h]; later calls read them there, so a pipeline needs
+ * no host round trip.  counts_host (nullable, pinned host memory of the same shape) receives a
+ * copy that is valid after dci_sync. */
+typedef struct {
+  int32_t n_hops;
+  int64_t cap_nodes;                 /* entries in nodes[]                                */
+  int64_t cap_rows[DCI_MAX_HOPS];    /* blk_indptr[h] has cap_rows[h] + 1 entries         */
+  int64_t cap_edges[DCI_MAX_HOPS];   /* entries in blk_src[h]                             */
+  int64_t* nodes;                    /* device [cap_nodes] global ids                     */
+  int64_t* blk_indptr[DCI_MAX_HOPS]; /* device                                            */
+  int32_t* blk_src[DCI_MAX_HOPS];    /* device                                            */
+  int64_t* counts;                   /* device [2*DCI_MAX_HOPS + 1]                       */
+  int64_t* counts_host;              /* pinned host [2*DCI_MAX_HOPS + 1] or NULL          */
+} dci_blocks;
+
+/* Per-call statistics, accumulated (+=) by the kernels into a caller-owned device array of
+ * DCI_STATS_WORDS uint64 (clear it before the first use; copy it out after dci_sync).  Pass NULL
+ * to skip them. */
+enum {
+  DCI_STAT_EDGES_SAMPLED = 0,  /* sampled edges over all hops                              */
+  DCI_STAT_ADJ_NODE_HITS = 1,  /* frontier nodes whose list was in the adjacency cache     */
+  DCI_STAT_ADJ_NODE_MISSES = 2,
+  DCI_STAT_ADJ_EDGE_HITS = 3,  /* sampled edges read from the adjacency cache              */
+  DCI_STAT_ADJ_EDGE_MISSES = 4,
+  DCI_STAT_FEAT_HITS = 5,      /* gathered rows read from the feature cache                */
+  DCI_STAT_FEAT_MISSES = 6,
+  DCI_STAT_INPUT_NODES = 7,    /* sum of |F_L| over sampled batches                        */
+  DCI_STAT_T_SAMPLE_NS = 8,    /* dci_presample_count only: GPU time spent sampling        */
+  DCI_STAT_T_FEATURE_NS = 9,   /* dci_presample_count only: GPU time spent loading features */
+  DCI_STATS_WORDS = 16
+};
+
+/* ---- context ----------------------------------------------------------------------------- */
+
+/* Creates a context bound to GPU `device` and to `hip_stream` (a hipStream_t, borrowed; NULL =
+ * the default stream).  `workspace` is device memory of `workspace_bytes` bytes, 256-byte
+ * aligned, borrowed until dci_destroy; it may be NULL/0 and replaced later with
+ * dci_set_workspace.  Returns DCI_ERR_HIP if the device cannot be selected. */
+int32_t dci_create(dci_ctx** out, int32_t device, void* hip_stream, void* workspace, size_t workspace_bytes);
+int32_t dci_set_workspace(dci_ctx* ctx, void* workspace, size_t workspace_bytes);
+void dci_destroy(dci_ctx* ctx);
+/* Waits for everything enqueued on the context's stream. */
+int32_t dci_sync(dci_ctx* ctx);
+/* Message of the last failed call on this context (never NULL; "" if none). */
+const char* dci_last_error(const dci_ctx* ctx);
+
+/* Upper bounds on the sizes of a mini-batch with n_seeds seeds: cap_nodes[h] bounds |F_h|
+ * (h = 0..n_hops), cap_edges[h] the edges of block h.  |F_{h+1}| <= min(|F_h| (1 + f_h),
+ * N + n_seeds).  Returns DCI_ERR_INVALID_ARG for n_hops outside 1..DCI_MAX_HOPS or a fan-out
+ * outside 1..DCI_MAX_FANOUT, DCI_ERR_UNSUPPORTED if a bound reaches 2^31. */
+int32_t dci_blocks_bounds(int64_t num_nodes, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
+                          int64_t* cap_nodes, int64_t* cap_edges);
+
+/* Workspace needed by dci_sample_khop / dci_presample_count for batches of up to n_seeds seeds. */
+size_t dci_sample_workspace_bytes(int64_t num_nodes, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops);
+/* Workspace needed by dci_fill_caches. */
+size_t dci_fill_workspace_bytes(int64_t num_nodes);
+/* Workspace needed by dci_sage_forward for blocks with these row capacities. */
+size_t dci_sage_workspace_bytes(const int64_t* cap_rows, int32_t n_layers, const int32_t* dims);
+
+/* ---- the five calls of the hot path ------------------------------------------------------- */
+
+/* Pre-sampling access counting (Section IV-A, first paragraph; Section IV-B, first paragraph).
+ * Samples the batches [first_batch, first_batch + n_batches) of the seed list - batch b covers
+ * seeds[b*batch_size .. min(n_seeds, (b+1)*batch_size)) and uses RNG batch index
+ * rng_batch0 + (b - first_batch) - exactly as dci_sample_khop would, and accumulates
+ *   adj_count[v]  += 1 and edge_count[indptr[v] + p] += 1 for every sampled position p of every
+ *                    frontier node v at every hop,
+ *   feat_count[u] += 1 for every node u of each batch's input list F_L.
+ * feat_count, adj_count: device uint32 [N]; edge_count: device uint32 [E] or NULL.  The
+ * counters are not cleared.  If feat_scratch (device, >= cap_nodes[L] * F floats) is not NULL
+ * each batch's input rows are also gathered into it, and the GPU times of the sampling part and
+ * of the gathering part are added to DCI_STAT_T_SAMPLE_NS / DCI_STAT_T_FEATURE_NS (the two
+ * times of Eq. (1)); this makes the call wait for the GPU.  cache may be NULL (the usual case:
+ * nothing is cached yet).  seeds: device int64 [n_seeds], distinct. */
+int32_t dci_presample_count(dci_ctx* ctx, const dci_graph* graph, const dci_cache* cache,
+                            const int64_t* seeds, int64_t n_seeds, int32_t batch_size, int64_t first_batch,
+                            int64_t n_batches, uint64_t rng_batch0, const int32_t* fanouts, int32_t n_hops,
+                            uint64_t rng_seed, uint32_t* feat_count, uint32_t* adj_count,
+                            uint32_t* edge_count, float* feat_scratch, uint64_t* stats);
+
+/* Capacity split and dual-cache fill (Eq. (1); Section IV-B; Algorithm 1).
+ *  1. C_adj = floor(budget * t_sample / (t_sample + t_feature)), C_feat = budget - C_adj
+ *     (half each when both times are 0).  A share larger than its side can use - the whole
+ *     adjacency structure is 8*(N+1+E) bytes, the whole feature matrix 4*N*F - is cut to that
+ *     and the excess moves to the other side, so a budget that covers the dataset caches all
+ *     of it.
+ *  2. Feature cache: k = min(N, C_feat / (4F)) rows.  DCI_FEAT_POLICY_PAPER_MEAN takes the nodes
+ *     whose feat_count exceeds the mean over all N nodes, in ascending id, then the other nodes
+ *     in ascending id, and keeps the first k.  DCI_FEAT_POLICY_TOPK orders by feat_count
+ *     descending (ties: ascending id).  feat_remap[v] = row or -1.
+ *  3. Adjacency cache: if 8*(N+1+E) <= C_adj the whole structure is cached with slot = node id.
+ *     Otherwise nodes are ordered by adj_count descending (ties: ascending id) and the longest
+ *     prefix whose compacted form 8*(K+1) + 8*sum(deg) fits in C_adj is cached, lists
+ *     concatenated in that order, each in its original element order.  adj_remap[v] = slot or -1.
+ * cache_buf: device, 256-byte aligned, at least budget_bytes + 256 bytes; the cache arrays are
+ * carved from it (feature rows first).  adj_remap, feat_remap: device int32 [N], written in
+ * full.  edge_count is accepted for symmetry with the counting call and not used by these
+ * policies.  *out is filled on return; this call waits for the GPU. */
+int32_t dci_fill_caches(dci_ctx* ctx, const dci_graph* graph, const uint32_t* feat_count,
+                        const uint32_t* adj_count, const uint32_t* edge_count, uint64_t budget_bytes,
+                        uint64_t t_sample_ns, uint64_t t_feature_ns, int32_t feat_policy, void* cache_buf,
+                        int32_t* adj_remap, int32_t* feat_remap, dci_cache* out);
+
+/* Cache-aware multi-hop uniform neighbour sampling (Section II-C; Section IV, framework
+ * paragraph; hit rule of Section IV-B, third paragraph).
+ * For hop h and every node v = F_h[i]: deg = length of v's list, c = min(fanouts[h], deg).
+ * deg <= fanout takes the whole list in order; otherwise Floyd's subset algorithm draws c
+ * distinct positions, slot s using the Philox4x32-10 output for key = rng_seed and counter =
+ * (v lo, v hi, batch_index, h << 24 | s), reduced to [0, deg - c + s] by a 64x64 -> high-64
+ * multiply.  The list (and its length) is read from the adjacency cache when
+ * cache->adj_remap[v] >= 0 and from graph->indptr/indices otherwise; both hold the same bytes,
+ * so the result does not depend on the cache.  seeds: device int64 [n_seeds]; duplicates are
+ * tolerated (they share a local id).  batch_index < 2^32.  out: see dci_blocks. */
+int32_t dci_sample_khop(dci_ctx* ctx, const dci_graph* graph, const dci_cache* cache, const int64_t* seeds,
+                        int64_t n_seeds, uint64_t batch_index, const int32_t* fanouts, int32_t n_hops,
+                        uint64_t rng_seed, dci_blocks* out, uint64_t* stats);
+
+/* Cache-aware feature gather (Section IV, framework paragraph; Section IV-B, first paragraph):
+ * out[i,:] = feat_cache[feat_remap[id_i],:] on a hit, graph->feat[id_i,:] on a miss.
+ * node_ids: device int64.  The number of rows is *n_dev (device int64, e.g. &counts[L] of a
+ * dci_blocks) when n_dev is not NULL, with n_max an upper bound used to size the launch;
+ * otherwise it is n_max.  out: device [n_max, F]. */
+int32_t dci_gather_features(dci_ctx* ctx, const dci_graph* graph, const dci_cache* cache,
+                            const int64_t* node_ids, int64_t n_max, const int64_t* n_dev, float* out,
+                            uint64_t* stats);
+
+/* GraphSAGE-mean forward over the blocks of one mini-batch (Table III family; mean aggregator).
+ * Layer l = 0..n_layers-1 works on block h = n_layers-1-l: for each row i < n_nodes[h]
+ *   m_i = mean of x[src] over the row's edges (zero vector for an empty row)
+ *   y_i = x_i W_self[l] + m_i W_neigh[l] + bias[l], ReLU on all layers but the last.
+ * x_in: device [n_nodes[L], dims[0]]; w_self[l], w_neigh[l]: device [dims[l], dims[l+1]]
+ * row-major; bias[l]: device [dims[l+1]]; logits: device [cap_rows[0], dims[n_layers]].
+ * n_layers must equal blocks->n_hops.  fp32 storage, fp32 accumulation on the matrix cores. */
+int32_t dci_sage_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_in, int32_t n_layers,
+                         const int32_t* dims, const float* const* w_self, const float* const* w_neigh,
+                         const float* const* bias, float* logits);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DCI_H_ */

@@ -1,0 +1,11 @@
+"""MI355X-native hot path of DCI dual-cache GNN inference (arXiv 2503.01281).
+
+The work is done by ``libdci.so`` (hand-written HIP for gfx950 behind the C boundary declared
+in ``include/dci.h``); this package is the thin ctypes binding with the same call names.
+PyTorch is used for device / pinned memory and the stream only.
+"""
+from .binding import (  # noqa: F401
+    DCI_MAX_HOPS, STATS_WORDS, STAT, Blocks, Cache, Context, DciError, Graph, blocks_bounds,
+    dci_fill_caches, dci_gather_features, dci_presample_count, dci_sage_forward, dci_sample_khop,
+    library_path, load_library,
+)

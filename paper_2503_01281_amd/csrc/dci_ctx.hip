@@ -1,0 +1,106 @@
+// Context management and small shared kernels of libdci.
+#include "dci_internal.h"
+
+#include <new>
+
+namespace dci {
+
+__global__ void k_fill_u32x4(uint4* __restrict__ p, size_t n16, uint32_t pattern) {
+  const uint4 v = make_uint4(pattern, pattern, pattern, pattern);
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+    p[i] = v;
+}
+
+// A fill kernel rather than hipMemsetAsync, so that callers may capture the calls in a graph.
+int32_t fill_bytes(dci_ctx* ctx, void* p, size_t bytes, uint32_t pattern) {
+  if (bytes == 0) return DCI_OK;
+  if ((reinterpret_cast<uintptr_t>(p) & 15) || (bytes & 15))
+    return fail(ctx, DCI_ERR_INVALID_ARG, "fill_bytes: unaligned region");
+  const size_t n16 = bytes / 16;
+  const int block = 256;
+  size_t want = (n16 + block - 1) / block;
+  const int grid = (int)(want < (size_t)ctx->num_cus * 8 ? want : (size_t)ctx->num_cus * 8);
+  hipLaunchKernelGGL(k_fill_u32x4, dim3(grid), dim3(block), 0, ctx->stream, reinterpret_cast<uint4*>(p), n16,
+                     pattern);
+  DCI_LAUNCH_CHECK(ctx);
+  return DCI_OK;
+}
+
+}  // namespace dci
+
+extern "C" {
+
+int32_t dci_create(dci_ctx** out, int32_t device, void* hip_stream, void* workspace, size_t workspace_bytes) {
+  if (!out) return DCI_ERR_INVALID_ARG;
+  *out = nullptr;
+  dci_ctx* ctx = new (std::nothrow) dci_ctx();
+  if (!ctx) return DCI_ERR_HIP;
+  ctx->device = device;
+  ctx->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  hipError_t e = hipSetDevice(device);
+  hipDeviceProp_t prop;
+  if (e == hipSuccess) e = hipGetDeviceProperties(&prop, device);
+  if (e == hipSuccess) {
+    ctx->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    for (int i = 0; i < 3 && e == hipSuccess; ++i) e = hipEventCreate(&ctx->ev[i]);
+  }
+  if (e != hipSuccess) {
+    for (int i = 0; i < 3; ++i)
+      if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
+    delete ctx;
+    return DCI_ERR_HIP;
+  }
+  int32_t rc = dci_set_workspace(ctx, workspace, workspace_bytes);
+  if (rc != DCI_OK) {
+    dci_destroy(ctx);
+    return rc;
+  }
+  *out = ctx;
+  return DCI_OK;
+}
+
+int32_t dci_set_workspace(dci_ctx* ctx, void* workspace, size_t workspace_bytes) {
+  if (!ctx) return DCI_ERR_INVALID_ARG;
+  if ((workspace == nullptr) != (workspace_bytes == 0))
+    return dci::fail(ctx, DCI_ERR_INVALID_ARG, "workspace pointer and size must both be set or both be empty");
+  if (reinterpret_cast<uintptr_t>(workspace) % dci::kAlign)
+    return dci::fail(ctx, DCI_ERR_INVALID_ARG, "workspace must be %zu-byte aligned", dci::kAlign);
+  ctx->ws = static_cast<char*>(workspace);
+  ctx->ws_bytes = workspace_bytes;
+  return DCI_OK;
+}
+
+void dci_destroy(dci_ctx* ctx) {
+  if (!ctx) return;
+  for (int i = 0; i < 3; ++i)
+    if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
+  delete ctx;
+}
+
+int32_t dci_sync(dci_ctx* ctx) {
+  if (!ctx) return DCI_ERR_INVALID_ARG;
+  DCI_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  return DCI_OK;
+}
+
+const char* dci_last_error(const dci_ctx* ctx) { return ctx ? ctx->err : "null context"; }
+
+int32_t dci_blocks_bounds(int64_t num_nodes, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
+                          int64_t* cap_nodes, int64_t* cap_edges) {
+  if (num_nodes < 1 || n_seeds < 0 || !fanouts || n_hops < 1 || n_hops > DCI_MAX_HOPS || !cap_nodes || !cap_edges)
+    return DCI_ERR_INVALID_ARG;
+  const int64_t limit = (int64_t)1 << 31;
+  cap_nodes[0] = n_seeds;
+  for (int32_t h = 0; h < n_hops; ++h) {
+    if (fanouts[h] < 1 || fanouts[h] > DCI_MAX_FANOUT) return DCI_ERR_INVALID_ARG;
+    if (cap_nodes[h] >= limit) return DCI_ERR_UNSUPPORTED;
+    cap_edges[h] = cap_nodes[h] * fanouts[h];
+    int64_t grown = cap_nodes[h] * (1 + (int64_t)fanouts[h]);
+    int64_t all = num_nodes + n_seeds;
+    cap_nodes[h + 1] = grown < all ? grown : all;
+    if (cap_edges[h] >= limit || cap_nodes[h + 1] >= limit) return DCI_ERR_UNSUPPORTED;
+  }
+  return DCI_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,127 @@
+// Cache-aware feature gather (Section IV, framework paragraph; Section IV-B, first paragraph):
+// a row comes from the HBM feature cache when feat_remap[id] >= 0 and from the host feature
+// matrix (zero-copy over the host link) otherwise.
+//
+// The copy is bandwidth bound.  A row is handled by a group of lanes (a whole wavefront for
+// rows of 64 or more vector chunks, a fraction for narrow rows) with 16-, 8- or 4-byte
+// accesses depending on the alignment F allows, consecutive lanes on consecutive chunks, four
+// loads in flight per lane before the first store.
+#include "dci_internal.h"
+
+namespace dci {
+
+constexpr int kGatherBlock = 256;
+
+template <int V>
+struct VecT;
+template <>
+struct VecT<4> {
+  typedef float4 type;
+};
+template <>
+struct VecT<2> {
+  typedef float2 type;
+};
+template <>
+struct VecT<1> {
+  typedef float type;
+};
+
+template <int V>
+__global__ __launch_bounds__(kGatherBlock) void k_gather(const long long* __restrict__ ids, long long n_max,
+                                                         const long long* __restrict__ n_dev,
+                                                         const int* __restrict__ remap,
+                                                         const float* __restrict__ cache,
+                                                         const float* __restrict__ feat, int F, int lpr_log2,
+                                                         float* __restrict__ out, unsigned long long* stats) {
+  typedef typename VecT<V>::type vec_t;
+  long long n = n_dev ? *n_dev : n_max;
+  if (n > n_max) n = n_max;
+  const int chunks = F / V;
+  const int lpr = 1 << lpr_log2;                 // lanes per row
+  const int rows_per_block = kGatherBlock >> lpr_log2;
+  const int sub = (int)threadIdx.x >> lpr_log2;  // row within the block's slice
+  const int cl = (int)threadIdx.x & (lpr - 1);   // first chunk of this lane
+  unsigned long long hits = 0, misses = 0;
+  for (long long base = (long long)blockIdx.x * rows_per_block; base < n; base += (long long)gridDim.x * rows_per_block) {
+    const long long i = base + sub;
+    if (i < n) {
+      const long long id = ids[i];
+      const int r = remap ? remap[id] : -1;
+      const vec_t* src = reinterpret_cast<const vec_t*>(r >= 0 ? cache + (long long)r * F : feat + id * F);
+      vec_t* dst = reinterpret_cast<vec_t*>(out + i * F);
+      if (cl == 0) {
+        if (r >= 0) ++hits; else ++misses;
+      }
+      int c = cl;
+      for (; c + 3 * lpr < chunks; c += 4 * lpr) {
+        const vec_t v0 = src[c], v1 = src[c + lpr], v2 = src[c + 2 * lpr], v3 = src[c + 3 * lpr];
+        dst[c] = v0;
+        dst[c + lpr] = v1;
+        dst[c + 2 * lpr] = v2;
+        dst[c + 3 * lpr] = v3;
+      }
+      for (; c < chunks; c += lpr) dst[c] = src[c];
+    }
+  }
+  if (stats) {
+    hits = wave_sum_u64(hits);
+    misses = wave_sum_u64(misses);
+    if (lane_id() == 0) {
+      if (hits) atomicAdd(&stats[DCI_STAT_FEAT_HITS], hits);
+      if (misses) atomicAdd(&stats[DCI_STAT_FEAT_MISSES], misses);
+    }
+  }
+}
+
+int32_t gather_launch(dci_ctx* ctx, const dci_graph* g, const dci_cache* cache, const int64_t* ids, int64_t n_max,
+                      const int64_t* n_dev, float* out, uint64_t* stats) {
+  const int F = g->feat_dim;
+  const float* fcache = cache ? cache->feat_cache : nullptr;
+  const int* remap = cache ? cache->feat_remap : nullptr;
+  // widest access that every row start (feature matrix, cache and output) is aligned for
+  auto aligned = [](const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; };
+  int V = 1;
+  if (F % 4 == 0 && aligned(g->feat, 16) && aligned(out, 16) && (!fcache || aligned(fcache, 16)))
+    V = 4;
+  else if (F % 2 == 0 && aligned(g->feat, 8) && aligned(out, 8) && (!fcache || aligned(fcache, 8)))
+    V = 2;
+  const int chunks = F / V;
+  int lpr_log2 = 0;
+  while ((1 << lpr_log2) < chunks && lpr_log2 < 6) ++lpr_log2;
+  const int rows_per_block = kGatherBlock >> lpr_log2;
+  int64_t blocks = (n_max + rows_per_block - 1) / rows_per_block;
+  const int64_t cap = (int64_t)ctx->num_cus * 16;
+  if (blocks > cap) blocks = cap;
+  if (blocks < 1) blocks = 1;
+  const long long* ids_ = reinterpret_cast<const long long*>(ids);
+  const long long* nd_ = reinterpret_cast<const long long*>(n_dev);
+  unsigned long long* st = reinterpret_cast<unsigned long long*>(stats);
+  if (V == 4)
+    hipLaunchKernelGGL((k_gather<4>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_, (long long)n_max,
+                       nd_, remap, fcache, g->feat, F, lpr_log2, out, st);
+  else if (V == 2)
+    hipLaunchKernelGGL((k_gather<2>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_, (long long)n_max,
+                       nd_, remap, fcache, g->feat, F, lpr_log2, out, st);
+  else
+    hipLaunchKernelGGL((k_gather<1>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_, (long long)n_max,
+                       nd_, remap, fcache, g->feat, F, lpr_log2, out, st);
+  DCI_LAUNCH_CHECK(ctx);
+  return DCI_OK;
+}
+
+}  // namespace dci
+
+extern "C" int32_t dci_gather_features(dci_ctx* ctx, const dci_graph* graph, const dci_cache* cache,
+                                       const int64_t* node_ids, int64_t n_max, const int64_t* n_dev, float* out,
+                                       uint64_t* stats) {
+  if (!ctx) return DCI_ERR_INVALID_ARG;
+  if (!graph || !graph->feat || graph->feat_dim < 1 || graph->num_nodes < 1)
+    return dci::fail(ctx, DCI_ERR_INVALID_ARG, "graph: feature matrix missing or feat_dim < 1");
+  if (n_max < 0 || (n_max > 0 && (!node_ids || !out)))
+    return dci::fail(ctx, DCI_ERR_INVALID_ARG, "node_ids / out: null or negative count");
+  if (cache && (!cache->feat_remap || (cache->feat_rows > 0 && !cache->feat_cache)))
+    return dci::fail(ctx, DCI_ERR_INVALID_ARG, "cache: null feature arrays");
+  if (n_max == 0) return DCI_OK;
+  return dci::gather_launch(ctx, graph, cache, node_ids, n_max, n_dev, out, stats);
+}

@@ -1,0 +1,119 @@
+// Internal declarations shared by the HIP translation units of libdci (gfx950 only).
+#ifndef DCI_INTERNAL_H_
+#define DCI_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+
+#include "dci.h"
+
+struct dci_ctx {
+  int device = 0;
+  hipStream_t stream = nullptr;
+  char* ws = nullptr;
+  size_t ws_bytes = 0;
+  int num_cus = 256;
+  hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+  char err[512] = {0};
+};
+
+namespace dci {
+
+constexpr int kWave = 64;
+constexpr size_t kAlign = 256;
+
+inline int32_t fail(dci_ctx* ctx, int32_t code, const char* fmt, ...) {
+  if (ctx) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+    va_end(ap);
+  }
+  return code;
+}
+
+#define DCI_HIP(ctx, call)                                                                          \
+  do {                                                                                              \
+    hipError_t e_ = (call);                                                                         \
+    if (e_ != hipSuccess)                                                                           \
+      return dci::fail((ctx), DCI_ERR_HIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_),   \
+                       __FILE__, __LINE__);                                                         \
+  } while (0)
+
+#define DCI_LAUNCH_CHECK(ctx)                                                                       \
+  do {                                                                                              \
+    hipError_t e_ = hipGetLastError();                                                              \
+    if (e_ != hipSuccess)                                                                           \
+      return dci::fail((ctx), DCI_ERR_HIP, "kernel launch failed: %s (%s:%d)", hipGetErrorString(e_), \
+                       __FILE__, __LINE__);                                                         \
+  } while (0)
+
+inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
+
+// Bump allocator over the context's workspace.  Every call carves its temporaries from the
+// start: calls on one context are ordered on one stream, so they never hold it at the same time.
+struct Arena {
+  char* base;
+  size_t cap;
+  size_t off = 0;
+  Arena(char* b, size_t c) : base(b), cap(c) {}
+  template <class T>
+  T* take(size_t n) {
+    size_t bytes = align_up(n * sizeof(T));
+    T* p = reinterpret_cast<T*>(base + off);
+    off += bytes;
+    return p;
+  }
+  bool ok() const { return off <= cap && (base != nullptr || off == 0); }
+};
+
+inline uint64_t next_pow2(uint64_t x) {
+  uint64_t p = 1;
+  while (p < x) p <<= 1;
+  return p;
+}
+
+// -- device helpers -----------------------------------------------------------------------
+
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
+
+__device__ __forceinline__ int wave_incl_scan(int x) {
+  const int lane = lane_id();
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    int y = __shfl_up(x, d, kWave);
+    if (lane >= d) x += y;
+  }
+  return x;
+}
+
+__device__ __forceinline__ long long wave_incl_scan64(long long x) {
+  const int lane = lane_id();
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    long long y = __shfl_up(x, d, kWave);
+    if (lane >= d) x += y;
+  }
+  return x;
+}
+
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long x) {
+#pragma unroll
+  for (int d = kWave / 2; d >= 1; d >>= 1) x += __shfl_down(x, d, kWave);
+  return x;  // valid in lane 0
+}
+
+// Fills `bytes` (a multiple of 16) at a 16-byte aligned address with the 32-bit pattern.
+__global__ void k_fill_u32x4(uint4* __restrict__ p, size_t n16, uint32_t pattern);
+
+int32_t fill_bytes(dci_ctx* ctx, void* p, size_t bytes, uint32_t pattern);
+int32_t gather_launch(dci_ctx* ctx, const dci_graph* g, const dci_cache* cache, const int64_t* ids,
+                      int64_t n_max, const int64_t* n_dev, float* out, uint64_t* stats);
+
+}  // namespace dci
+
+#endif  // DCI_INTERNAL_H_

@@ -1,0 +1,669 @@
+// Cache-aware multi-hop neighbour sampling, mini-batch block construction and pre-sampling
+// access counting (Section II-C; Section IV; Section IV-B, first and third paragraphs).
+//
+// Per hop, four phases, each a grid-wide kernel so that the next sees all of the previous:
+//   1. sample   - one lane group per frontier node (a whole wavefront for fan-outs above 32,
+//                 a half / quarter / eighth for smaller ones): read the node's list bounds from
+//                 the adjacency cache or the host CSR, draw the positions (Floyd's subset
+//                 algorithm on Philox4x32-10, one lane per slot), read the neighbour ids, store
+//                 them at the padded position row*fanout + slot and register every id in the
+//                 batch's hash table with an atomic minimum over that padded position.
+//   2. count    - a lane is the "first appearance" of its node iff the table still holds its own
+//                 padded position; count those per row.
+//   3. scan     - prefix sums over the rows: edge offsets of the block and the base of the new
+//                 local ids of each row.
+//   4. assign   - first appearances append their node to the frontier and publish the new local
+//                 id in the table; then every edge reads its local id from the table.
+// The table stores, per node id, either a final local id (below 2^31) or 2^31 + the smallest
+// padded position seen so far, so one atomic minimum serves both "already in the frontier"
+// and "who came first".
+#include "dci_internal.h"
+
+namespace dci {
+
+struct HashEntry {
+  long long key;
+  unsigned int val;
+  unsigned int pad;
+};
+static_assert(sizeof(HashEntry) == 16, "hash entry must be 16 bytes");
+
+constexpr unsigned int kTentative = 0x80000000u;
+constexpr long long kEmptyKey = -1;
+constexpr int kBlock = 256;
+
+// ---- Philox4x32-10 (Salmon et al., SC'11), counter-based ---------------------------------
+__device__ __forceinline__ unsigned long long philox_u64(unsigned c0, unsigned c1, unsigned c2, unsigned c3,
+                                                         unsigned k0, unsigned k1) {
+  constexpr unsigned M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const unsigned h0 = __umulhi(M0, c0), l0 = M0 * c0;
+    const unsigned h1 = __umulhi(M1, c2), l1 = M1 * c2;
+    c0 = h1 ^ c1 ^ k0;
+    c1 = l1;
+    c2 = h0 ^ c3 ^ k1;
+    c3 = l0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return (unsigned long long)c0 | ((unsigned long long)c1 << 32);
+}
+
+__device__ __forceinline__ unsigned long long uniform_below(unsigned k0, unsigned k1, long long node, unsigned batch,
+                                                            int hop, int slot, unsigned long long m) {
+  const unsigned long long u = philox_u64((unsigned)(unsigned long long)node,
+                                          (unsigned)((unsigned long long)node >> 32), batch,
+                                          ((unsigned)hop << 24) | (unsigned)slot, k0, k1);
+  return __umul64hi(u, m);
+}
+
+// ---- hash table -----------------------------------------------------------------------------
+__device__ __forceinline__ unsigned table_find_or_insert(HashEntry* table, unsigned mask, int shift, long long u) {
+  unsigned slot = (unsigned)(((unsigned long long)u * 0x9E3779B97F4A7C15ull) >> shift) & mask;
+  for (;;) {
+    long long k = __atomic_load_n(&table[slot].key, __ATOMIC_RELAXED);
+    if (k == u) return slot;
+    if (k == kEmptyKey) {
+      const unsigned long long prev =
+          atomicCAS(reinterpret_cast<unsigned long long*>(&table[slot].key), (unsigned long long)kEmptyKey,
+                    (unsigned long long)u);
+      if (prev == (unsigned long long)kEmptyKey || prev == (unsigned long long)u) return slot;
+    }
+    slot = (slot + 1) & mask;
+  }
+}
+
+__device__ __forceinline__ void table_min(HashEntry* table, unsigned slot, unsigned v) {
+  // The value only ever decreases, so a stale (larger) read costs one redundant atomic at most.
+  if (__atomic_load_n(&table[slot].val, __ATOMIC_RELAXED) > v) atomicMin(&table[slot].val, v);
+}
+
+template <int G>
+__device__ __forceinline__ unsigned long long group_bits(unsigned long long ballot, int grp_in_wave) {
+  if (G == 64) return ballot;
+  return (ballot >> (grp_in_wave * G)) & ((1ull << (G & 63)) - 1ull);
+}
+
+// ---- kernels ----------------------------------------------------------------------------------
+
+__global__ __launch_bounds__(kBlock) void k_init_batch(const long long* __restrict__ seeds, long long n_seeds,
+                                                       long long* __restrict__ nodes, long long* __restrict__ counts,
+                                                       HashEntry* table, unsigned mask, int shift) {
+  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n_seeds;
+       i += (long long)gridDim.x * blockDim.x) {
+    const long long v = seeds[i];
+    nodes[i] = v;
+    const unsigned slot = table_find_or_insert(table, mask, shift, v);
+    table_min(table, slot, (unsigned)i);
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) counts[0] = n_seeds;
+}
+
+struct HopArgs {
+  const long long* nodes;
+  const long long* counts;
+  int hop;
+  int fanout;
+  const long long* indptr;
+  const long long* indices;
+  const int* adj_remap;
+  const long long* c_indptr;
+  const long long* c_indices;
+  unsigned k0, k1, batch;
+  long long* tmp_u;
+  int* tmp_slot;
+  int* row_cnt;
+  HashEntry* table;
+  unsigned mask;
+  int shift;
+  unsigned* adj_count;
+  unsigned* edge_count;
+  unsigned long long* stats;
+};
+
+template <int G, bool COUNT>
+__global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
+  const long long n_rows = a.counts[a.hop];
+  const int lane = lane_id();
+  const int gl = lane & (G - 1);
+  const int grp_in_wave = lane / G;
+  constexpr int kGroups = kBlock / G;
+  const int grp_in_block = (int)threadIdx.x / G;
+  const int f = a.fanout;
+  unsigned long long st_nh = 0, st_nm = 0, st_eh = 0, st_em = 0;
+
+  for (long long base = (long long)blockIdx.x * kGroups; base < n_rows; base += (long long)gridDim.x * kGroups) {
+    const long long i = base + grp_in_block;
+    const bool row_ok = i < n_rows;
+    long long v = 0, start = 0, d = 0;
+    const long long* list = a.indices;
+    bool hit = false;
+    if (row_ok) {
+      v = a.nodes[i];
+      const int r = a.adj_remap ? a.adj_remap[v] : -1;
+      hit = r >= 0;
+      if (hit) {
+        start = a.c_indptr[r];
+        d = a.c_indptr[r + 1] - start;
+        list = a.c_indices;
+      } else {
+        start = a.indptr[v];
+        d = a.indptr[v + 1] - start;
+      }
+    }
+    const int c = d < (long long)f ? (int)d : f;
+    long long pos = gl;
+    const bool floyd = row_ok && d > (long long)f;
+    if (__ballot(floyd) != 0ull) {
+      // slot s draws t_s below j_s + 1, j_s = d - f + s; it keeps t_s unless an earlier slot
+      // already holds that value, in which case it takes j_s.
+      const long long j = d - f + gl;
+      long long t = 0;
+      if (floyd && gl < f) t = (long long)uniform_below(a.k0, a.k1, v, a.batch, a.hop, gl, (unsigned long long)(j + 1));
+      long long S = t;
+      for (int s = 1; s < f; ++s) {
+        const long long ts = __shfl(t, s, G);
+        const bool match = floyd && gl < s && S == ts;
+        const bool any = group_bits<G>(__ballot(match), grp_in_wave) != 0ull;
+        if (gl == s && any) S = j;
+      }
+      if (floyd) pos = S;
+    }
+    const bool active = row_ok && gl < c;
+    if (active) {
+      const long long u = list[start + pos];
+      const int p = (int)(i * f + gl);
+      const unsigned slot = table_find_or_insert(a.table, a.mask, a.shift, u);
+      table_min(a.table, slot, kTentative | (unsigned)p);
+      a.tmp_u[p] = u;
+      a.tmp_slot[p] = (int)slot;
+      if (COUNT && a.edge_count) {
+        const long long host_start = hit ? a.indptr[v] : start;
+        atomicAdd(&a.edge_count[host_start + pos], 1u);
+      }
+    }
+    if (row_ok && gl == 0) {
+      a.row_cnt[i] = c;
+      if (COUNT && c > 0) atomicAdd(&a.adj_count[v], (unsigned)c);
+      if (hit) {
+        st_nh += 1;
+        st_eh += (unsigned)c;
+      } else {
+        st_nm += 1;
+        st_em += (unsigned)c;
+      }
+    }
+  }
+  if (a.stats) {
+    st_nh = wave_sum_u64(st_nh);
+    st_nm = wave_sum_u64(st_nm);
+    st_eh = wave_sum_u64(st_eh);
+    st_em = wave_sum_u64(st_em);
+    if (lane == 0) {
+      if (st_nh) atomicAdd(&a.stats[DCI_STAT_ADJ_NODE_HITS], st_nh);
+      if (st_nm) atomicAdd(&a.stats[DCI_STAT_ADJ_NODE_MISSES], st_nm);
+      if (st_eh) atomicAdd(&a.stats[DCI_STAT_ADJ_EDGE_HITS], st_eh);
+      if (st_em) atomicAdd(&a.stats[DCI_STAT_ADJ_EDGE_MISSES], st_em);
+    }
+  }
+}
+
+struct RowArgs {
+  const long long* counts;
+  int hop;
+  int fanout;
+  const int* row_cnt;
+  int* row_first;
+  const int* first_base;
+  const long long* blk_indptr;
+  const long long* tmp_u;
+  const int* tmp_slot;
+  HashEntry* table;
+  long long* nodes;
+  int* blk_src;
+};
+
+// phase 2: number of first appearances per row
+template <int G>
+__global__ __launch_bounds__(kBlock) void k_row_first(RowArgs a) {
+  const long long n_rows = a.counts[a.hop];
+  const int lane = lane_id(), gl = lane & (G - 1), grp_in_wave = lane / G;
+  constexpr int kGroups = kBlock / G;
+  const int grp_in_block = (int)threadIdx.x / G;
+  for (long long base = (long long)blockIdx.x * kGroups; base < n_rows; base += (long long)gridDim.x * kGroups) {
+    const long long i = base + grp_in_block;
+    const bool row_ok = i < n_rows;
+    const int c = row_ok ? a.row_cnt[i] : 0;
+    bool first = false;
+    if (gl < c) {
+      const int p = (int)(i * a.fanout + gl);
+      first = a.table[a.tmp_slot[p]].val == (kTentative | (unsigned)p);
+    }
+    const unsigned long long bits = group_bits<G>(__ballot(first), grp_in_wave);
+    if (row_ok && gl == 0) a.row_first[i] = __popcll(bits);
+  }
+}
+
+// phase 3: one workgroup scans the per-row edge counts (-> blk_indptr) and first-appearance
+// counts (-> first_base), then publishes the sizes of the hop.
+constexpr int kScanThreads = 1024;
+constexpr int kScanItems = 4;
+__global__ __launch_bounds__(kScanThreads) void k_scan_rows(long long* __restrict__ counts, int hop,
+                                                            const int* __restrict__ row_cnt,
+                                                            const int* __restrict__ row_first,
+                                                            long long* __restrict__ blk_indptr,
+                                                            int* __restrict__ first_base,
+                                                            unsigned long long* stats, int last_hop) {
+  __shared__ long long s_c[kScanThreads / kWave];
+  __shared__ int s_f[kScanThreads / kWave];
+  const long long n = counts[hop];
+  const int tid = (int)threadIdx.x, lane = lane_id(), wave = tid / kWave;
+  long long carry_c = 0;
+  int carry_f = 0;
+  for (long long base = 0; base < n; base += (long long)kScanThreads * kScanItems) {
+    int c[kScanItems], fr[kScanItems];
+    long long tc = 0;
+    int tf = 0;
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k) {
+      const long long idx = base + (long long)tid * kScanItems + k;
+      c[k] = idx < n ? row_cnt[idx] : 0;
+      fr[k] = idx < n ? row_first[idx] : 0;
+      tc += c[k];
+      tf += fr[k];
+    }
+    const long long inc_c = wave_incl_scan64(tc);
+    const int inc_f = wave_incl_scan(tf);
+    if (lane == kWave - 1) {
+      s_c[wave] = inc_c;
+      s_f[wave] = inc_f;
+    }
+    __syncthreads();
+    long long off_c = carry_c, tot_c = 0;
+    int off_f = carry_f, tot_f = 0;
+#pragma unroll
+    for (int w = 0; w < kScanThreads / kWave; ++w) {
+      if (w < wave) {
+        off_c += s_c[w];
+        off_f += s_f[w];
+      }
+      tot_c += s_c[w];
+      tot_f += s_f[w];
+    }
+    long long run_c = off_c + inc_c - tc;
+    int run_f = off_f + inc_f - tf;
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k) {
+      const long long idx = base + (long long)tid * kScanItems + k;
+      if (idx < n) {
+        first_base[idx] = run_f;
+        run_c += c[k];
+        run_f += fr[k];
+        blk_indptr[idx + 1] = run_c;
+      }
+    }
+    carry_c += tot_c;
+    carry_f += tot_f;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    blk_indptr[0] = 0;
+    counts[hop + 1] = n + carry_f;
+    counts[DCI_MAX_HOPS + 1 + hop] = carry_c;
+    if (stats) {
+      atomicAdd(&stats[DCI_STAT_EDGES_SAMPLED], (unsigned long long)carry_c);
+      if (last_hop) atomicAdd(&stats[DCI_STAT_INPUT_NODES], (unsigned long long)(n + carry_f));
+    }
+  }
+}
+
+// phase 4a: first appearances take the next local ids, in (row, slot) order
+template <int G>
+__global__ __launch_bounds__(kBlock) void k_assign_new(RowArgs a) {
+  const long long n_rows = a.counts[a.hop];
+  const int lane = lane_id(), gl = lane & (G - 1), grp_in_wave = lane / G;
+  constexpr int kGroups = kBlock / G;
+  const int grp_in_block = (int)threadIdx.x / G;
+  for (long long base = (long long)blockIdx.x * kGroups; base < n_rows; base += (long long)gridDim.x * kGroups) {
+    const long long i = base + grp_in_block;
+    const bool row_ok = i < n_rows;
+    const int c = row_ok ? a.row_cnt[i] : 0;
+    bool first = false;
+    int p = 0, slot = 0;
+    if (gl < c) {
+      p = (int)(i * a.fanout + gl);
+      slot = a.tmp_slot[p];
+      first = a.table[slot].val == (kTentative | (unsigned)p);
+    }
+    const unsigned long long bits = group_bits<G>(__ballot(first), grp_in_wave);
+    if (first) {
+      const int rank = __popcll(bits & ((1ull << gl) - 1ull));
+      const long long id = n_rows + a.first_base[i] + rank;
+      a.nodes[id] = a.tmp_u[p];
+      a.table[slot].val = (unsigned)id;
+    }
+  }
+}
+
+// phase 4b: every edge reads its source's local id
+template <int G>
+__global__ __launch_bounds__(kBlock) void k_write_src(RowArgs a) {
+  const long long n_rows = a.counts[a.hop];
+  const int gl = lane_id() & (G - 1);
+  constexpr int kGroups = kBlock / G;
+  const int grp_in_block = (int)threadIdx.x / G;
+  for (long long base = (long long)blockIdx.x * kGroups; base < n_rows; base += (long long)gridDim.x * kGroups) {
+    const long long i = base + grp_in_block;
+    if (i < n_rows && gl < a.row_cnt[i]) {
+      const int p = (int)(i * a.fanout + gl);
+      a.blk_src[a.blk_indptr[i] + gl] = (int)a.table[a.tmp_slot[p]].val;
+    }
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_count_input_nodes(const long long* __restrict__ nodes,
+                                                              const long long* __restrict__ counts, int n_hops,
+                                                              unsigned* __restrict__ feat_count) {
+  const long long n = counts[n_hops];
+  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x)
+    atomicAdd(&feat_count[nodes[i]], 1u);
+}
+
+__global__ void k_add_u64(unsigned long long* p, unsigned long long v) { atomicAdd(p, v); }
+
+// ---- host side ----------------------------------------------------------------------------------
+
+struct SampleWs {
+  HashEntry* table;
+  uint64_t table_entries;
+  long long* tmp_u;
+  int* tmp_slot;
+  int* row_cnt;
+  int* row_first;
+  int* first_base;
+};
+
+static uint64_t table_entries_for(int64_t cap_nodes_last) {
+  uint64_t want = next_pow2((uint64_t)(cap_nodes_last > 0 ? cap_nodes_last : 1) * 2);
+  return want < 1024 ? 1024 : want;
+}
+
+static void carve_sample_ws(Arena& ar, const int64_t* cap_nodes, const int64_t* cap_edges, int32_t n_hops,
+                            SampleWs* ws) {
+  int64_t max_edges = 1, max_rows = 1;
+  for (int32_t h = 0; h < n_hops; ++h) {
+    if (cap_edges[h] > max_edges) max_edges = cap_edges[h];
+    if (cap_nodes[h] > max_rows) max_rows = cap_nodes[h];
+  }
+  ws->table_entries = table_entries_for(cap_nodes[n_hops]);
+  ws->table = ar.take<HashEntry>(ws->table_entries);
+  ws->tmp_u = ar.take<long long>((size_t)max_edges);
+  ws->tmp_slot = ar.take<int>((size_t)max_edges);
+  ws->row_cnt = ar.take<int>((size_t)max_rows);
+  ws->row_first = ar.take<int>((size_t)max_rows);
+  ws->first_base = ar.take<int>((size_t)max_rows);
+}
+
+static void carve_blocks(Arena& ar, const int64_t* cap_nodes, const int64_t* cap_edges, int32_t n_hops,
+                         dci_blocks* b) {
+  std::memset(b, 0, sizeof(*b));
+  b->n_hops = n_hops;
+  b->cap_nodes = cap_nodes[n_hops];
+  b->nodes = reinterpret_cast<int64_t*>(ar.take<long long>((size_t)(cap_nodes[n_hops] > 0 ? cap_nodes[n_hops] : 1)));
+  for (int32_t h = 0; h < n_hops; ++h) {
+    b->cap_rows[h] = cap_nodes[h];
+    b->cap_edges[h] = cap_edges[h];
+    b->blk_indptr[h] = reinterpret_cast<int64_t*>(ar.take<long long>((size_t)cap_nodes[h] + 1));
+    b->blk_src[h] = ar.take<int>((size_t)(cap_edges[h] > 0 ? cap_edges[h] : 1));
+  }
+  b->counts = reinterpret_cast<int64_t*>(ar.take<long long>(2 * DCI_MAX_HOPS + 1));
+}
+
+static int grid_for_rows(const dci_ctx* ctx, int64_t rows, int groups_per_block) {
+  int64_t blocks = (rows + groups_per_block - 1) / groups_per_block;
+  int64_t cap = (int64_t)ctx->num_cus * 8;
+  if (blocks > cap) blocks = cap;
+  if (blocks < 1) blocks = 1;
+  return (int)blocks;
+}
+
+template <int G>
+static int32_t launch_hop(dci_ctx* ctx, const HopArgs& ha, const RowArgs& ra, bool count, int64_t cap_rows,
+                          long long* counts, long long* blk_indptr, int* first_base_out, unsigned long long* stats,
+                          int last_hop) {
+  const int grid = grid_for_rows(ctx, cap_rows, kBlock / G);
+  if (count)
+    hipLaunchKernelGGL((k_sample_hop<G, true>), dim3(grid), dim3(kBlock), 0, ctx->stream, ha);
+  else
+    hipLaunchKernelGGL((k_sample_hop<G, false>), dim3(grid), dim3(kBlock), 0, ctx->stream, ha);
+  DCI_LAUNCH_CHECK(ctx);
+  hipLaunchKernelGGL((k_row_first<G>), dim3(grid), dim3(kBlock), 0, ctx->stream, ra);
+  DCI_LAUNCH_CHECK(ctx);
+  hipLaunchKernelGGL(k_scan_rows, dim3(1), dim3(kScanThreads), 0, ctx->stream, counts, ra.hop, ra.row_cnt,
+                     (const int*)ra.row_first, blk_indptr, first_base_out, stats, last_hop);
+  DCI_LAUNCH_CHECK(ctx);
+  hipLaunchKernelGGL((k_assign_new<G>), dim3(grid), dim3(kBlock), 0, ctx->stream, ra);
+  DCI_LAUNCH_CHECK(ctx);
+  hipLaunchKernelGGL((k_write_src<G>), dim3(grid), dim3(kBlock), 0, ctx->stream, ra);
+  DCI_LAUNCH_CHECK(ctx);
+  return DCI_OK;
+}
+
+// Enqueues the sampling of one batch.  `count_*` non-null turns on the pre-sampling counters.
+static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* cache, const int64_t* seeds,
+                            int64_t n_seeds, uint64_t batch_index, const int32_t* fanouts, int32_t n_hops,
+                            uint64_t rng_seed, const dci_blocks* out, const SampleWs& ws, uint64_t* stats,
+                            uint32_t* feat_count, uint32_t* adj_count, uint32_t* edge_count) {
+  int rc = fill_bytes(ctx, ws.table, ws.table_entries * sizeof(HashEntry), 0xFFFFFFFFu);
+  if (rc != DCI_OK) return rc;
+  const unsigned mask = (unsigned)(ws.table_entries - 1);
+  int log2n = 0;
+  while ((1ull << log2n) < ws.table_entries) ++log2n;
+  const int shift = 64 - log2n;
+  long long* counts = reinterpret_cast<long long*>(out->counts);
+  long long* nodes = reinterpret_cast<long long*>(out->nodes);
+  {
+    int grid = grid_for_rows(ctx, n_seeds, kBlock);
+    hipLaunchKernelGGL(k_init_batch, dim3(grid), dim3(kBlock), 0, ctx->stream,
+                       reinterpret_cast<const long long*>(seeds), (long long)n_seeds, nodes, counts, ws.table, mask,
+                       shift);
+    DCI_LAUNCH_CHECK(ctx);
+  }
+  const bool count = adj_count != nullptr;
+  for (int32_t h = 0; h < n_hops; ++h) {
+    HopArgs ha;
+    ha.nodes = nodes;
+    ha.counts = counts;
+    ha.hop = h;
+    ha.fanout = fanouts[h];
+    ha.indptr = reinterpret_cast<const long long*>(g->indptr);
+    ha.indices = reinterpret_cast<const long long*>(g->indices);
+    ha.adj_remap = cache ? cache->adj_remap : nullptr;
+    ha.c_indptr = cache ? reinterpret_cast<const long long*>(cache->c_indptr) : nullptr;
+    ha.c_indices = cache ? reinterpret_cast<const long long*>(cache->c_indices) : nullptr;
+    ha.k0 = (unsigned)rng_seed;
+    ha.k1 = (unsigned)(rng_seed >> 32);
+    ha.batch = (unsigned)batch_index;
+    ha.tmp_u = ws.tmp_u;
+    ha.tmp_slot = ws.tmp_slot;
+    ha.row_cnt = ws.row_cnt;
+    ha.table = ws.table;
+    ha.mask = mask;
+    ha.shift = shift;
+    ha.adj_count = adj_count;
+    ha.edge_count = edge_count;
+    ha.stats = reinterpret_cast<unsigned long long*>(stats);
+    RowArgs ra;
+    ra.counts = counts;
+    ra.hop = h;
+    ra.fanout = fanouts[h];
+    ra.row_cnt = ws.row_cnt;
+    ra.row_first = ws.row_first;
+    ra.first_base = ws.first_base;
+    ra.blk_indptr = reinterpret_cast<const long long*>(out->blk_indptr[h]);
+    ra.tmp_u = ws.tmp_u;
+    ra.tmp_slot = ws.tmp_slot;
+    ra.table = ws.table;
+    ra.nodes = nodes;
+    ra.blk_src = out->blk_src[h];
+    long long* bi = reinterpret_cast<long long*>(out->blk_indptr[h]);
+    unsigned long long* st = reinterpret_cast<unsigned long long*>(stats);
+    const int last = h == n_hops - 1;
+    const int f = fanouts[h];
+    if (f <= 8)
+      rc = launch_hop<8>(ctx, ha, ra, count, out->cap_rows[h], counts, bi, ws.first_base, st, last);
+    else if (f <= 16)
+      rc = launch_hop<16>(ctx, ha, ra, count, out->cap_rows[h], counts, bi, ws.first_base, st, last);
+    else if (f <= 32)
+      rc = launch_hop<32>(ctx, ha, ra, count, out->cap_rows[h], counts, bi, ws.first_base, st, last);
+    else
+      rc = launch_hop<64>(ctx, ha, ra, count, out->cap_rows[h], counts, bi, ws.first_base, st, last);
+    if (rc != DCI_OK) return rc;
+  }
+  if (feat_count) {
+    int grid = grid_for_rows(ctx, out->cap_nodes, kBlock);
+    hipLaunchKernelGGL(k_count_input_nodes, dim3(grid), dim3(kBlock), 0, ctx->stream, (const long long*)nodes,
+                       (const long long*)counts, n_hops, feat_count);
+    DCI_LAUNCH_CHECK(ctx);
+  }
+  return DCI_OK;
+}
+
+static int32_t check_common(dci_ctx* ctx, const dci_graph* g, const int64_t* seeds, int64_t n_seeds,
+                            const int32_t* fanouts, int32_t n_hops, uint64_t last_batch_index) {
+  if (!g || !g->indptr || !g->indices || g->num_nodes < 1 || g->num_edges < 0)
+    return fail(ctx, DCI_ERR_INVALID_ARG, "graph: null arrays or bad sizes");
+  if (g->num_nodes >= ((int64_t)1 << 31)) return fail(ctx, DCI_ERR_UNSUPPORTED, "more than 2^31-1 nodes");
+  if (n_seeds < 0 || (!seeds && n_seeds > 0)) return fail(ctx, DCI_ERR_INVALID_ARG, "seeds: null or negative count");
+  if (!fanouts || n_hops < 1 || n_hops > DCI_MAX_HOPS)
+    return fail(ctx, DCI_ERR_INVALID_ARG, "n_hops must be 1..%d", DCI_MAX_HOPS);
+  for (int32_t h = 0; h < n_hops; ++h)
+    if (fanouts[h] < 1 || fanouts[h] > DCI_MAX_FANOUT)
+      return fail(ctx, DCI_ERR_INVALID_ARG, "fanouts[%d] = %d outside 1..%d", h, fanouts[h], DCI_MAX_FANOUT);
+  if (last_batch_index >> 32) return fail(ctx, DCI_ERR_INVALID_ARG, "batch index must be below 2^32");
+  return DCI_OK;
+}
+
+static int32_t check_cache(dci_ctx* ctx, const dci_cache* cache) {
+  if (cache && (!cache->adj_remap || !cache->feat_remap || (cache->adj_nodes > 0 && (!cache->c_indptr || (cache->adj_edges > 0 && !cache->c_indices)))))
+    return fail(ctx, DCI_ERR_INVALID_ARG, "cache: null arrays");
+  return DCI_OK;
+}
+
+}  // namespace dci
+
+using namespace dci;
+
+extern "C" {
+
+size_t dci_sample_workspace_bytes(int64_t num_nodes, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops) {
+  int64_t cap_nodes[DCI_MAX_HOPS + 1], cap_edges[DCI_MAX_HOPS];
+  if (dci_blocks_bounds(num_nodes, n_seeds, fanouts, n_hops, cap_nodes, cap_edges) != DCI_OK) return 0;
+  Arena ar(nullptr, 0);
+  SampleWs ws;
+  dci_blocks b;
+  carve_sample_ws(ar, cap_nodes, cap_edges, n_hops, &ws);
+  carve_blocks(ar, cap_nodes, cap_edges, n_hops, &b);
+  return ar.off;
+}
+
+int32_t dci_sample_khop(dci_ctx* ctx, const dci_graph* graph, const dci_cache* cache, const int64_t* seeds,
+                        int64_t n_seeds, uint64_t batch_index, const int32_t* fanouts, int32_t n_hops,
+                        uint64_t rng_seed, dci_blocks* out, uint64_t* stats) {
+  if (!ctx) return DCI_ERR_INVALID_ARG;
+  int32_t rc = check_common(ctx, graph, seeds, n_seeds, fanouts, n_hops, batch_index);
+  if (rc != DCI_OK) return rc;
+  if ((rc = check_cache(ctx, cache)) != DCI_OK) return rc;
+  if (!out || !out->nodes || !out->counts || out->n_hops != n_hops)
+    return fail(ctx, DCI_ERR_INVALID_ARG, "blocks: null arrays or n_hops mismatch");
+  int64_t cap_nodes[DCI_MAX_HOPS + 1], cap_edges[DCI_MAX_HOPS];
+  rc = dci_blocks_bounds(graph->num_nodes, n_seeds, fanouts, n_hops, cap_nodes, cap_edges);
+  if (rc != DCI_OK) return fail(ctx, rc, "batch bounds reach 2^31");
+  if (out->cap_nodes < cap_nodes[n_hops])
+    return fail(ctx, DCI_ERR_CAPACITY, "blocks.nodes holds %lld entries, %lld needed", (long long)out->cap_nodes,
+                (long long)cap_nodes[n_hops]);
+  for (int32_t h = 0; h < n_hops; ++h) {
+    if (!out->blk_indptr[h] || !out->blk_src[h]) return fail(ctx, DCI_ERR_INVALID_ARG, "blocks: null array at hop %d", h);
+    if (out->cap_rows[h] < cap_nodes[h] || out->cap_edges[h] < cap_edges[h])
+      return fail(ctx, DCI_ERR_CAPACITY, "block %d holds %lld rows / %lld edges, %lld / %lld needed", h,
+                  (long long)out->cap_rows[h], (long long)out->cap_edges[h], (long long)cap_nodes[h],
+                  (long long)cap_edges[h]);
+  }
+  Arena ar(ctx->ws, ctx->ws_bytes);
+  SampleWs ws;
+  carve_sample_ws(ar, cap_nodes, cap_edges, n_hops, &ws);
+  if (!ar.ok())
+    return fail(ctx, DCI_ERR_CAPACITY, "workspace holds %zu bytes, sampling needs %zu", ctx->ws_bytes, ar.off);
+  // launch shapes follow the bounds of this call, not the (possibly larger) capacities
+  dci_blocks view = *out;
+  for (int32_t h = 0; h < n_hops; ++h) view.cap_rows[h] = cap_nodes[h];
+  view.cap_nodes = cap_nodes[n_hops];
+  rc = sample_batch(ctx, graph, cache, seeds, n_seeds, batch_index, fanouts, n_hops, rng_seed, &view, ws, stats,
+                    nullptr, nullptr, nullptr);
+  if (rc != DCI_OK) return rc;
+  if (out->counts_host)
+    DCI_HIP(ctx, hipMemcpyAsync(out->counts_host, out->counts, sizeof(int64_t) * (2 * DCI_MAX_HOPS + 1),
+                                hipMemcpyDeviceToHost, ctx->stream));
+  return DCI_OK;
+}
+
+int32_t dci_presample_count(dci_ctx* ctx, const dci_graph* graph, const dci_cache* cache, const int64_t* seeds,
+                            int64_t n_seeds, int32_t batch_size, int64_t first_batch, int64_t n_batches,
+                            uint64_t rng_batch0, const int32_t* fanouts, int32_t n_hops, uint64_t rng_seed,
+                            uint32_t* feat_count, uint32_t* adj_count, uint32_t* edge_count, float* feat_scratch,
+                            uint64_t* stats) {
+  if (!ctx) return DCI_ERR_INVALID_ARG;
+  if (batch_size < 1 || first_batch < 0 || n_batches < 0)
+    return fail(ctx, DCI_ERR_INVALID_ARG, "batch_size / first_batch / n_batches out of range");
+  int32_t rc = check_common(ctx, graph, seeds, n_seeds, fanouts, n_hops,
+                            rng_batch0 + (uint64_t)(n_batches > 0 ? n_batches - 1 : 0));
+  if (rc != DCI_OK) return rc;
+  if ((rc = check_cache(ctx, cache)) != DCI_OK) return rc;
+  if (!feat_count || !adj_count) return fail(ctx, DCI_ERR_INVALID_ARG, "feat_count / adj_count are required");
+  if (feat_scratch && !graph->feat) return fail(ctx, DCI_ERR_INVALID_ARG, "feat_scratch given but graph.feat is NULL");
+  int64_t cap_nodes[DCI_MAX_HOPS + 1], cap_edges[DCI_MAX_HOPS];
+  rc = dci_blocks_bounds(graph->num_nodes, batch_size, fanouts, n_hops, cap_nodes, cap_edges);
+  if (rc != DCI_OK) return fail(ctx, rc, "batch bounds reach 2^31");
+  Arena ar(ctx->ws, ctx->ws_bytes);
+  SampleWs ws;
+  dci_blocks blk;
+  carve_sample_ws(ar, cap_nodes, cap_edges, n_hops, &ws);
+  carve_blocks(ar, cap_nodes, cap_edges, n_hops, &blk);
+  if (!ar.ok())
+    return fail(ctx, DCI_ERR_CAPACITY, "workspace holds %zu bytes, pre-sampling needs %zu", ctx->ws_bytes, ar.off);
+  double ms_sample = 0.0, ms_feature = 0.0;
+  for (int64_t k = 0; k < n_batches; ++k) {
+    const int64_t lo = (first_batch + k) * batch_size;
+    if (lo >= n_seeds) break;
+    const int64_t hi = lo + batch_size < n_seeds ? lo + batch_size : n_seeds;
+    if (feat_scratch) DCI_HIP(ctx, hipEventRecord(ctx->ev[0], ctx->stream));
+    rc = sample_batch(ctx, graph, cache, seeds + lo, hi - lo, rng_batch0 + (uint64_t)k, fanouts, n_hops, rng_seed,
+                      &blk, ws, stats, feat_count, adj_count, edge_count);
+    if (rc != DCI_OK) return rc;
+    if (feat_scratch) {
+      DCI_HIP(ctx, hipEventRecord(ctx->ev[1], ctx->stream));
+      rc = gather_launch(ctx, graph, cache, blk.nodes, cap_nodes[n_hops], blk.counts + n_hops, feat_scratch, stats);
+      if (rc != DCI_OK) return rc;
+      DCI_HIP(ctx, hipEventRecord(ctx->ev[2], ctx->stream));
+      DCI_HIP(ctx, hipEventSynchronize(ctx->ev[2]));
+      float a = 0.f, b = 0.f;
+      DCI_HIP(ctx, hipEventElapsedTime(&a, ctx->ev[0], ctx->ev[1]));
+      DCI_HIP(ctx, hipEventElapsedTime(&b, ctx->ev[1], ctx->ev[2]));
+      ms_sample += a;
+      ms_feature += b;
+    }
+  }
+  if (feat_scratch && stats) {
+    unsigned long long* st = reinterpret_cast<unsigned long long*>(stats);
+    hipLaunchKernelGGL(k_add_u64, dim3(1), dim3(1), 0, ctx->stream, st + DCI_STAT_T_SAMPLE_NS,
+                       (unsigned long long)(ms_sample * 1.0e6));
+    DCI_LAUNCH_CHECK(ctx);
+    hipLaunchKernelGGL(k_add_u64, dim3(1), dim3(1), 0, ctx->stream, st + DCI_STAT_T_FEATURE_NS,
+                       (unsigned long long)(ms_feature * 1.0e6));
+    DCI_LAUNCH_CHECK(ctx);
+  }
+  return DCI_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,291 @@
+"""GPU parity: every call of the C boundary against the CPU oracle on the same seeded inputs.
+Integer outputs (blocks, counters, remaps, cache arrays, gathered rows) are compared bit for
+bit; logits within 1e-4 of the largest oracle logit of the batch."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env(tiny):
+    import paper_2503_01281_amd as dci
+    from tests import gpu_util
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    ctx = dci.Context(0)
+    g = gpu_util.make_graph(tiny["indptr"], tiny["indices"], tiny["feat"])
+    return dict(dci=dci, gu=gpu_util, ctx=ctx, graph=g, tiny=tiny, w=tiny["w"])
+
+
+def _oracle_caches(tiny, w, ts=3, tf=7, policy=0, budget=None):
+    fc, ac, _, _ = oracle.presample_count(tiny["indptr"], tiny["indices"], tiny["seeds"], w.batch_size,
+                                          w.n_presample, w.fanouts, w.rng_seed, w.presample_first_batch,
+                                          with_edge_count=False)
+    C_adj, C_feat = oracle.split(w.budget_bytes if budget is None else budget, ts, tf, w.num_nodes, w.num_edges,
+                                 w.feat_dim)
+    adj_remap, cp, ci = oracle.fill_adj(tiny["indptr"], tiny["indices"], ac, C_adj)
+    feat_remap, fcache, k = oracle.fill_feat(fc, tiny["feat"], C_feat, policy)
+    return dict(fc=fc, ac=ac, C_adj=C_adj, C_feat=C_feat, adj_remap=adj_remap, c_indptr=cp, c_indices=ci,
+                feat_remap=feat_remap, feat_cache=fcache, k=k)
+
+
+def test_sample_all_batches_no_cache(env):
+    dci, gu, ctx, g, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "graph", "tiny", "w"))
+    seeds_dev = gu.dev(tiny["seeds"])
+    blk = dci.Blocks(ctx, w.num_nodes, w.batch_size, w.fanouts)
+    stats = gu.new_stats()
+    edges = nodes = 0
+    for b in range(w.num_batches):
+        s = seeds_dev[b * w.batch_size:(b + 1) * w.batch_size]
+        dci.dci_sample_khop(ctx, g, None, s, b, w.fanouts, w.rng_seed, blk, stats)
+        got = gu.blocks_to_host(ctx, blk)
+        want = oracle.sample_khop(tiny["indptr"], tiny["indices"], tiny["seeds"][b * w.batch_size:(b + 1) * w.batch_size],
+                                  b, w.fanouts, w.rng_seed)
+        gu.assert_blocks_equal(got, want)
+        edges += int(want.n_edges.sum())
+        nodes += int(want.n_nodes[-1])
+    st = gu.stats_dict(ctx, stats)
+    assert st["edges_sampled"] == edges and st["input_nodes"] == nodes
+    assert st["adj_edge_misses"] == edges and st["adj_edge_hits"] == 0 and st["adj_node_hits"] == 0
+
+
+def test_sample_with_cache_is_transparent_and_counts_hits(env):
+    dci, gu, ctx, g, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "graph", "tiny", "w"))
+    oc = _oracle_caches(tiny, w)
+    cache = gu.upload_cache(oc["adj_remap"], oc["c_indptr"], oc["c_indices"], oc["feat_remap"], oc["feat_cache"])
+    blk = dci.Blocks(ctx, w.num_nodes, w.batch_size, w.fanouts)
+    for b in (0, 3, 7):
+        seeds = tiny["seeds"][b * w.batch_size:(b + 1) * w.batch_size]
+        stats = gu.new_stats()
+        dci.dci_sample_khop(ctx, g, cache, gu.dev(seeds), b, w.fanouts, w.rng_seed, blk, stats)
+        got = gu.blocks_to_host(ctx, blk)
+        want = oracle.sample_khop(tiny["indptr"], tiny["indices"], seeds, b, w.fanouts, w.rng_seed)
+        gu.assert_blocks_equal(got, want)
+        nh = nm = eh = em = 0
+        for h in range(w.n_hops):
+            frontier = want.nodes[:want.n_nodes[h]]
+            hit = oc["adj_remap"][frontier] >= 0
+            rows = np.diff(want.blk_indptr[h])
+            nh += int(hit.sum()); nm += int((~hit).sum()); eh += int(rows[hit].sum()); em += int(rows[~hit].sum())
+        st = gu.stats_dict(ctx, stats)
+        assert (st["adj_node_hits"], st["adj_node_misses"], st["adj_edge_hits"], st["adj_edge_misses"]) == (nh, nm, eh, em)
+        assert nh > 0 and nm > 0
+
+
+@pytest.mark.parametrize("fanouts", [(3,), (8, 8), (16, 2), (9, 17), (25, 10), (33,), (64,), (40, 3), (1, 1, 1, 1),
+                                     (2, 2, 2, 2, 2, 2, 2, 2)])
+@pytest.mark.parametrize("n_seeds", [1, 7, 300])
+def test_sample_fanout_and_batch_shapes(env, fanouts, n_seeds):
+    dci, gu, ctx, g, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "graph", "tiny", "w"))
+    seeds = tiny["seeds"][100:100 + n_seeds]
+    blk = dci.Blocks(ctx, w.num_nodes, n_seeds, fanouts)
+    dci.dci_sample_khop(ctx, g, None, gu.dev(seeds), 17, fanouts, 99, blk)
+    got = gu.blocks_to_host(ctx, blk)
+    want = oracle.sample_khop(tiny["indptr"], tiny["indices"], seeds, 17, fanouts, 99)
+    gu.assert_blocks_equal(got, want)
+
+
+def test_sample_degenerate_inputs(env, small_graphs):
+    dci, gu, ctx = env["dci"], env["gu"], env["ctx"]
+    indptr, indices = small_graphs[3]          # isolated nodes, a self loop, a duplicated edge
+    g = gu.make_graph(indptr, indices, None)
+    for seeds in ([], [0, 4], [1], [1, 1, 3], [0, 1, 2, 3, 4]):
+        seeds = np.array(seeds, dtype=np.int64)
+        blk = dci.Blocks(ctx, 5, len(seeds), (3, 2))
+        sd = gu.dev(seeds) if len(seeds) else torch.zeros(1, dtype=torch.int64, device="cuda")[:0]
+        dci.dci_sample_khop(ctx, g, None, sd, 0, (3, 2), 4, blk)
+        got = gu.blocks_to_host(ctx, blk)
+        want = oracle.sample_khop(indptr, indices, seeds, 0, (3, 2), 4)
+        gu.assert_blocks_equal(got, want)
+
+
+def test_sample_rejects_bad_arguments(env):
+    dci, gu, ctx, g, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "graph", "tiny", "w"))
+    seeds = gu.dev(tiny["seeds"][:16])
+    blk = dci.Blocks(ctx, w.num_nodes, 16, (5, 10))
+    with pytest.raises(dci.DciError) as e:
+        dci.dci_sample_khop(ctx, g, None, seeds, 0, (5, 65), 4, blk)
+    assert e.value.code == -1
+    with pytest.raises(dci.DciError) as e:
+        dci.dci_sample_khop(ctx, g, None, seeds, 1 << 32, (5, 10), 4, blk)
+    assert e.value.code == -1
+    small = dci.Blocks(ctx, w.num_nodes, 4, (5, 10))
+    with pytest.raises(dci.DciError) as e:
+        dci.dci_sample_khop(ctx, g, None, seeds, 0, (5, 10), 4, small)
+    assert e.value.code == -2 and "needed" in str(e.value)
+
+
+@pytest.mark.parametrize("F", [64, 100, 602, 63, 1, 256])
+def test_gather_hit_and_miss_paths(env, F):
+    dci, gu, ctx = env["dci"], env["gu"], env["ctx"]
+    N = 3000
+    feat = synth.features(N, F, 21)
+    rng = np.random.default_rng(F)
+    ids = rng.integers(0, N, 5000).astype(np.int64)
+    fc = rng.integers(0, 5, N).astype(np.uint32)
+    remap, fcache, k = oracle.fill_feat(fc, feat, (N // 3) * 4 * F, 1)
+    indptr = np.zeros(N + 1, dtype=np.int64)
+    g = gu.make_graph(indptr, np.zeros(1, dtype=np.int64)[:0], feat)
+    cache = gu.upload_cache(np.full(N, -1, dtype=np.int32), np.zeros(1, dtype=np.int64), np.zeros(0, dtype=np.int64),
+                            remap, fcache)
+    want = oracle.gather(feat, ids)
+    ids_dev = gu.dev(ids)
+    for c in (None, cache):
+        out = torch.full((len(ids) + 3, F), -7.0, dtype=torch.float32, device="cuda")
+        stats = gu.new_stats()
+        dci.dci_gather_features(ctx, g, c, ids_dev, len(ids), out, stats=stats)
+        st = gu.stats_dict(ctx, stats)
+        assert out[:len(ids)].cpu().numpy().tobytes() == want.tobytes()
+        assert (out[len(ids):] == -7.0).all()                       # nothing written past n
+        hits = int((remap[ids] >= 0).sum()) if c is not None else 0
+        assert (st["feat_hits"], st["feat_misses"]) == (hits, len(ids) - hits)
+    # row count taken from device memory
+    n_dev = torch.tensor([1234], dtype=torch.int64, device="cuda")
+    out = torch.full((len(ids), F), -7.0, dtype=torch.float32, device="cuda")
+    dci.dci_gather_features(ctx, g, cache, ids_dev, len(ids), out, n_dev=n_dev.data_ptr())
+    ctx.sync()
+    assert out[:1234].cpu().numpy().tobytes() == want[:1234].tobytes() and (out[1234:] == -7.0).all()
+
+
+def test_presample_counts(env):
+    dci, gu, ctx, g, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "graph", "tiny", "w"))
+    fc_w, ac_w, ec_w, (edges, nodes) = oracle.presample_count(tiny["indptr"], tiny["indices"], tiny["seeds"], w.batch_size,
+                                                              w.n_presample, w.fanouts, w.rng_seed,
+                                                              w.presample_first_batch)
+    seeds = gu.dev(tiny["seeds"])
+    fc = torch.zeros(w.num_nodes, dtype=torch.int32, device="cuda")
+    ac = torch.zeros(w.num_nodes, dtype=torch.int32, device="cuda")
+    ec = torch.zeros(w.num_edges, dtype=torch.int32, device="cuda")
+    stats = gu.new_stats()
+    # two calls of four batches each must add up to the oracle's eight
+    dci.dci_presample_count(ctx, g, None, seeds, w.batch_size, 0, 4, w.presample_first_batch, w.fanouts, w.rng_seed,
+                            fc, ac, ec, stats=stats)
+    scratch = torch.empty(dci.blocks_bounds(w.num_nodes, w.batch_size, w.fanouts)[0][-1] * w.feat_dim,
+                          dtype=torch.float32, device="cuda")
+    dci.dci_presample_count(ctx, g, None, seeds, w.batch_size, 4, 4, w.presample_first_batch + 4, w.fanouts,
+                            w.rng_seed, fc, ac, ec, feat_scratch=scratch, stats=stats)
+    st = gu.stats_dict(ctx, stats)
+    assert np.array_equal(fc.cpu().numpy().view(np.uint32), fc_w)
+    assert np.array_equal(ac.cpu().numpy().view(np.uint32), ac_w)
+    assert np.array_equal(ec.cpu().numpy().view(np.uint32), ec_w)
+    assert st["edges_sampled"] == edges and st["input_nodes"] == nodes
+    assert st["t_sample_ns"] > 0 and st["t_feature_ns"] > 0
+
+
+def _check_fill(env, budget, ts, tf, policy):
+    dci, gu, ctx, g, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "graph", "tiny", "w"))
+    oc = _oracle_caches(tiny, w, ts, tf, policy, budget)
+    cache = dci.dci_fill_caches(ctx, g, gu.dev(oc["fc"].view(np.int32)), gu.dev(oc["ac"].view(np.int32)), budget, ts, tf,
+                                policy)
+    K, M, k = cache.adj_nodes, cache.adj_edges, cache.feat_rows
+    assert (cache.cap_adj_bytes, cache.cap_feat_bytes) == (oc["C_adj"], oc["C_feat"])
+    assert (K, M, k) == (len(oc["c_indptr"]) - 1, len(oc["c_indices"]), oc["k"])
+    assert np.array_equal(cache.adj_remap.cpu().numpy(), oc["adj_remap"])
+    assert np.array_equal(cache.feat_remap.cpu().numpy(), oc["feat_remap"])
+    assert cache.adj_bytes <= max(oc["C_adj"], 8) and cache.feat_bytes <= oc["C_feat"]
+    base = cache.buf.data_ptr() + cache.buf_offset
+
+    def view(addr, n, dtype):
+        off = addr - cache.buf.data_ptr()
+        nbytes = n * torch.tensor([], dtype=dtype).element_size()
+        return cache.buf[off:off + nbytes].view(dtype).cpu().numpy()
+
+    assert cache.c.feat_cache == base or k == 0
+    if k:
+        assert view(cache.c.feat_cache, k * w.feat_dim, torch.float32).tobytes() == oc["feat_cache"].tobytes()
+    if K:
+        assert np.array_equal(view(cache.c.c_indptr, K + 1, torch.int64), oc["c_indptr"])
+    if M:
+        assert np.array_equal(view(cache.c.c_indices, M, torch.int64), oc["c_indices"])
+    return cache
+
+
+@pytest.mark.parametrize("policy", [0, 1])
+@pytest.mark.parametrize("budget,ts,tf", [(1_127_220, 3, 7), (1_127_220, 7, 3), (1_127_220, 1, 0), (1_127_220, 0, 1),
+                                          (5_636_104, 3, 7), (5_636_103, 1, 1), (20, 1, 1), (0, 1, 1),
+                                          (300_001, 0, 0), (3_000_000, 9, 1), (3_000_000, 1, 9)])
+def test_fill_caches_matches_oracle(env, budget, ts, tf, policy):
+    _check_fill(env, budget, ts, tf, policy)
+
+
+def test_fill_with_many_distinct_counts(env):
+    """Counts above 255 exercise more than one radix pass."""
+    dci, gu, ctx, g, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "graph", "tiny", "w"))
+    rng = np.random.default_rng(3)
+    fc = rng.integers(0, 70000, w.num_nodes).astype(np.uint32)
+    ac = (rng.integers(0, 3, w.num_nodes) * rng.integers(0, 1 << 20, w.num_nodes)).astype(np.uint32)
+    for policy in (0, 1):
+        C_adj, C_feat = oracle.split(900_000, 1, 1, w.num_nodes, w.num_edges, w.feat_dim)
+        adj_remap, cp, ci = oracle.fill_adj(tiny["indptr"], tiny["indices"], ac, C_adj)
+        feat_remap, fcache, k = oracle.fill_feat(fc, tiny["feat"], C_feat, policy)
+        cache = dci.dci_fill_caches(ctx, g, gu.dev(fc.view(np.int32)), gu.dev(ac.view(np.int32)), 900_000, 1, 1, policy)
+        assert np.array_equal(cache.adj_remap.cpu().numpy(), adj_remap)
+        assert np.array_equal(cache.feat_remap.cpu().numpy(), feat_remap)
+        assert (cache.adj_nodes, cache.adj_edges, cache.feat_rows) == (len(cp) - 1, len(ci), k)
+
+
+def _logit_check(got, want):
+    tol = 1e-4 * max(1.0, float(np.abs(want).max()))
+    err = float(np.abs(got.astype(np.float64) - want).max())
+    assert err <= tol, f"max |gpu - oracle| = {err} > {tol}"
+
+
+@pytest.mark.parametrize("dims,fanouts,n_seeds", [((64, 64, 16), (5, 10), 256), ((602, 256, 41), (3, 4), 70),
+                                                  ((100, 256, 256, 47), (2, 3, 4), 33), ((63, 5), (7,), 129),
+                                                  ((128, 130, 172), (5, 5), 200), ((256, 256, 64), (10, 25), 40)])
+def test_sage_forward_matches_oracle(env, dims, fanouts, n_seeds):
+    dci, gu, ctx, g, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "graph", "tiny", "w"))
+    seeds = tiny["seeds"][:n_seeds]
+    want_blk = oracle.sample_khop(tiny["indptr"], tiny["indices"], seeds, 1, fanouts, 4)
+    blk = dci.Blocks(ctx, w.num_nodes, n_seeds, fanouts)
+    dci.dci_sample_khop(ctx, g, None, gu.dev(seeds), 1, fanouts, 4, blk)
+    feat = synth.features(w.num_nodes, dims[0], 31)
+    ws, wn, bs = synth.sage_weights(dims, 32)
+    x = feat[want_blk.nodes]
+    want = oracle.sage_forward(want_blk, x, ws, wn, bs)
+    x_dev = torch.zeros(blk.cap_nodes[-1], dims[0], dtype=torch.float32, device="cuda")
+    x_dev[:len(x)] = torch.from_numpy(x).cuda()
+    logits = torch.full((blk.cap_nodes[0], dims[-1]), float("nan"), dtype=torch.float32, device="cuda")
+    dci.dci_sage_forward(ctx, blk, x_dev, [gu.dev(a) for a in ws], [gu.dev(a) for a in wn], [gu.dev(a) for a in bs],
+                         logits)
+    ctx.sync()
+    _logit_check(logits[:n_seeds].cpu().numpy(), want)
+
+
+def test_end_to_end_tiny(env):
+    """presample -> fill -> sample -> gather -> forward, all on the GPU, against the oracle."""
+    dci, gu, ctx, g, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "graph", "tiny", "w"))
+    seeds = gu.dev(tiny["seeds"])
+    fc = torch.zeros(w.num_nodes, dtype=torch.int32, device="cuda")
+    ac = torch.zeros(w.num_nodes, dtype=torch.int32, device="cuda")
+    dci.dci_presample_count(ctx, g, None, seeds, w.batch_size, 0, w.n_presample, w.presample_first_batch, w.fanouts,
+                            w.rng_seed, fc, ac)
+    cache = dci.dci_fill_caches(ctx, g, fc, ac, w.budget_bytes, 3, 7, 0)
+    oc = _oracle_caches(tiny, w)
+    assert np.array_equal(cache.adj_remap.cpu().numpy(), oc["adj_remap"])
+    assert np.array_equal(cache.feat_remap.cpu().numpy(), oc["feat_remap"])
+    blk = dci.Blocks(ctx, w.num_nodes, w.batch_size, w.fanouts)
+    x = torch.empty(blk.cap_nodes[-1], w.feat_dim, dtype=torch.float32, device="cuda")
+    logits = torch.empty(w.batch_size, w.classes, dtype=torch.float32, device="cuda")
+    ws, wn, bs = ([gu.dev(a) for a in tiny[k]] for k in ("w_self", "w_neigh", "bias"))
+    for b in range(w.num_batches):
+        sl = slice(b * w.batch_size, (b + 1) * w.batch_size)
+        stats = gu.new_stats()
+        dci.dci_sample_khop(ctx, g, cache, seeds[sl], b, w.fanouts, w.rng_seed, blk, stats)
+        dci.dci_gather_features(ctx, g, cache, blk.nodes, blk.cap_nodes[-1], x, n_dev=blk.n_input_dev(), stats=stats)
+        dci.dci_sage_forward(ctx, blk, x, ws, wn, bs, logits)
+        got = gu.blocks_to_host(ctx, blk)
+        want_blk = oracle.sample_khop(tiny["indptr"], tiny["indices"], tiny["seeds"][sl], b, w.fanouts, w.rng_seed)
+        gu.assert_blocks_equal(got, want_blk)
+        n_in = got["n_nodes"][-1]
+        want_x = oracle.gather(tiny["feat"], want_blk.nodes)
+        assert x[:n_in].cpu().numpy().tobytes() == want_x.tobytes()
+        want = oracle.sage_forward(want_blk, want_x, tiny["w_self"], tiny["w_neigh"], tiny["bias"])
+        _logit_check(logits.cpu().numpy(), want)
+        st = gu.stats_dict(ctx, stats)
+        assert st["feat_hits"] == int((oc["feat_remap"][want_blk.nodes] >= 0).sum())
+        assert st["feat_hits"] + st["feat_misses"] == n_in
