@@ -131,6 +131,29 @@ int32_t dci_sync(dci_ctx* ctx);
 /* Message of the last failed call on this context (never NULL; "" if none). */
 const char* dci_last_error(const dci_ctx* ctx);
 
+/* Kernel timing, for benchmarks and profiles.  Kernel classes whose bit is set in class_mask are
+ * bracketed by HIP events on the context's stream (up to DCI_TIMING_MAX_LAUNCHES launches
+ * between two reads; later ones are not recorded).  dci_timing_read waits for the stream, adds
+ * up the elapsed time and the number of recorded launches per class into total_ms[DCI_K_COUNT]
+ * and launches[DCI_K_COUNT], and starts over.  class_mask = 0 switches timing off (the default). */
+enum {
+  DCI_K_TABLE_CLEAR = 0, /* clearing the batch's hash table                        */
+  DCI_K_INIT = 1,        /* seeds into the frontier                                */
+  DCI_K_SAMPLE = 2,      /* per hop: draw positions, read neighbours, register ids */
+  DCI_K_ROW_FIRST = 3,   /* per hop: first appearances per row                     */
+  DCI_K_SCAN = 4,        /* per hop: row offsets                                   */
+  DCI_K_ASSIGN = 5,      /* per hop: new local ids                                 */
+  DCI_K_WRITE_SRC = 6,   /* per hop: local id of every edge                        */
+  DCI_K_GATHER = 7,      /* feature gather                                         */
+  DCI_K_MEAN = 8,        /* per layer: neighbour mean                              */
+  DCI_K_LINEAR = 9,      /* per layer: dense layer on the matrix cores             */
+  DCI_K_COUNT_NODES = 10,/* pre-sampling: visits of the input nodes                */
+  DCI_K_COUNT = 11
+};
+#define DCI_TIMING_MAX_LAUNCHES 8192
+int32_t dci_timing_enable(dci_ctx* ctx, uint32_t class_mask);
+int32_t dci_timing_read(dci_ctx* ctx, double* total_ms, int64_t* launches);
+
 /* Upper bounds on the sizes of a mini-batch with n_seeds seeds: cap_nodes[h] bounds |F_h|
  * (h = 0..n_hops), cap_edges[h] the edges of block h.  |F_{h+1}| <= min(|F_h| (1 + f_h),
  * N + n_seeds).  Returns DCI_ERR_INVALID_ARG for n_hops outside 1..DCI_MAX_HOPS or a fan-out

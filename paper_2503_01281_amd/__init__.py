@@ -5,7 +5,7 @@ in ``include/dci.h``); this package is the thin ctypes binding with the same cal
 PyTorch is used for device / pinned memory and the stream only.
 """
 from .binding import (  # noqa: F401
-    DCI_MAX_HOPS, STATS_WORDS, STAT, Blocks, Cache, Context, DciError, Graph, blocks_bounds,
+    DCI_MAX_HOPS, KERNEL_CLASSES, STATS_WORDS, STAT, Blocks, Cache, Context, DciError, Graph, blocks_bounds,
     dci_fill_caches, dci_gather_features, dci_presample_count, dci_sage_forward, dci_sample_khop,
     library_path, load_library,
 )

@@ -16,6 +16,9 @@ STATS_WORDS = 16
 STAT = dict(edges_sampled=0, adj_node_hits=1, adj_node_misses=2, adj_edge_hits=3, adj_edge_misses=4,
             feat_hits=5, feat_misses=6, input_nodes=7, t_sample_ns=8, t_feature_ns=9)
 
+KERNEL_CLASSES = ["table_clear", "init", "sample", "row_first", "scan", "assign", "write_src", "gather", "mean",
+                  "linear", "count_nodes"]
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libdci.so")
 _lib = None
@@ -78,7 +81,9 @@ def load_library():
     lib.dci_sample_khop.argtypes = [P, P, P, P, i64, u64, P, i32, u64, P, P]
     lib.dci_gather_features.argtypes = [P, P, P, P, i64, P, P, P]
     lib.dci_sage_forward.argtypes = [P, P, P, i32, P, P, P, P, P]
-    for name in ("dci_create", "dci_set_workspace", "dci_sync", "dci_blocks_bounds", "dci_presample_count",
+    lib.dci_timing_enable.argtypes = [P, C.c_uint32]
+    lib.dci_timing_read.argtypes = [P, P, P]
+    for name in ("dci_timing_enable", "dci_timing_read", "dci_create", "dci_set_workspace", "dci_sync", "dci_blocks_bounds", "dci_presample_count",
                  "dci_fill_caches", "dci_sample_khop", "dci_gather_features", "dci_sage_forward"):
         getattr(lib, name).restype = i32
     _lib = lib
@@ -138,6 +143,20 @@ class Context:
 
     def sync(self):
         self.check(self.lib.dci_sync(self._h))
+
+    def timing_enable(self, classes):
+        """classes: iterable of kernel-class names from KERNEL_CLASSES (empty = off)."""
+        mask = 0
+        for name in classes:
+            mask |= 1 << KERNEL_CLASSES.index(name)
+        self.check(self.lib.dci_timing_enable(self._h, mask))
+
+    def timing_read(self):
+        """{class: (total_ms, launches)} since the last read; waits for the stream."""
+        ms = (C.c_double * len(KERNEL_CLASSES))()
+        n = (C.c_int64 * len(KERNEL_CLASSES))()
+        self.check(self.lib.dci_timing_read(self._h, ms, n))
+        return {k: (float(ms[i]), int(n[i])) for i, k in enumerate(KERNEL_CLASSES)}
 
     def close(self):
         if self._h:

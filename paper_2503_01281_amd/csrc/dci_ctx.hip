@@ -74,7 +74,42 @@ void dci_destroy(dci_ctx* ctx) {
   if (!ctx) return;
   for (int i = 0; i < 3; ++i)
     if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
+  if (ctx->t_events) {
+    for (int i = 0; i < 2 * DCI_TIMING_MAX_LAUNCHES; ++i)
+      if (ctx->t_events[i]) (void)hipEventDestroy(ctx->t_events[i]);
+    delete[] ctx->t_events;
+  }
+  delete[] ctx->t_class;
   delete ctx;
+}
+
+int32_t dci_timing_enable(dci_ctx* ctx, uint32_t class_mask) {
+  if (!ctx) return DCI_ERR_INVALID_ARG;
+  if (class_mask && !ctx->t_events) {
+    ctx->t_events = new (std::nothrow) hipEvent_t[2 * DCI_TIMING_MAX_LAUNCHES]();
+    ctx->t_class = new (std::nothrow) int8_t[DCI_TIMING_MAX_LAUNCHES]();
+    if (!ctx->t_events || !ctx->t_class) return dci::fail(ctx, DCI_ERR_HIP, "out of host memory for timing events");
+    for (int i = 0; i < 2 * DCI_TIMING_MAX_LAUNCHES; ++i) DCI_HIP(ctx, hipEventCreate(&ctx->t_events[i]));
+  }
+  ctx->timing_mask = class_mask;
+  return DCI_OK;
+}
+
+int32_t dci_timing_read(dci_ctx* ctx, double* total_ms, int64_t* launches) {
+  if (!ctx || !total_ms || !launches) return DCI_ERR_INVALID_ARG;
+  for (int k = 0; k < DCI_K_COUNT; ++k) {
+    total_ms[k] = 0.0;
+    launches[k] = 0;
+  }
+  DCI_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  for (int i = 0; i < ctx->t_used; ++i) {
+    float ms = 0.f;
+    DCI_HIP(ctx, hipEventElapsedTime(&ms, ctx->t_events[2 * i], ctx->t_events[2 * i + 1]));
+    total_ms[ctx->t_class[i]] += ms;
+    launches[ctx->t_class[i]] += 1;
+  }
+  ctx->t_used = 0;
+  return DCI_OK;
 }
 
 int32_t dci_sync(dci_ctx* ctx) {

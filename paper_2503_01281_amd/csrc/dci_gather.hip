@@ -97,6 +97,7 @@ int32_t gather_launch(dci_ctx* ctx, const dci_graph* g, const dci_cache* cache, 
   const long long* ids_ = reinterpret_cast<const long long*>(ids);
   const long long* nd_ = reinterpret_cast<const long long*>(n_dev);
   unsigned long long* st = reinterpret_cast<unsigned long long*>(stats);
+  Timed timed(ctx, DCI_K_GATHER);
   if (V == 4)
     hipLaunchKernelGGL((k_gather<4>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_, (long long)n_max,
                        nd_, remap, fcache, g->feat, F, lpr_log2, out, st);

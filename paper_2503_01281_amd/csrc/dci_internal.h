@@ -19,6 +19,11 @@ struct dci_ctx {
   int num_cus = 256;
   hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
   char err[512] = {0};
+  // optional per-kernel-class timing
+  uint32_t timing_mask = 0;
+  hipEvent_t* t_events = nullptr;  // 2 * DCI_TIMING_MAX_LAUNCHES, created on first enable
+  int8_t* t_class = nullptr;
+  int t_used = 0;
 };
 
 namespace dci {
@@ -51,6 +56,24 @@ inline int32_t fail(dci_ctx* ctx, int32_t code, const char* fmt, ...) {
       return dci::fail((ctx), DCI_ERR_HIP, "kernel launch failed: %s (%s:%d)", hipGetErrorString(e_), \
                        __FILE__, __LINE__);                                                         \
   } while (0)
+
+// Brackets the launches issued during its lifetime with a pair of events when the class is timed.
+struct Timed {
+  dci_ctx* ctx;
+  int idx = -1;
+  Timed(dci_ctx* c, int cls) : ctx(c) {
+    if ((c->timing_mask >> cls) & 1u) {
+      if (c->t_used < DCI_TIMING_MAX_LAUNCHES) {
+        idx = c->t_used++;
+        c->t_class[idx] = (int8_t)cls;
+        (void)hipEventRecord(c->t_events[2 * idx], c->stream);
+      }
+    }
+  }
+  ~Timed() {
+    if (idx >= 0) (void)hipEventRecord(ctx->t_events[2 * idx + 1], ctx->stream);
+  }
+};
 
 inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
 

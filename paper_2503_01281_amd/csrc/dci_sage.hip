@@ -259,6 +259,8 @@ int32_t dci_sage_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_
     int64_t mb = (cap + rows_per_block - 1) / rows_per_block;
     if (mb > (int64_t)ctx->num_cus * 16) mb = (int64_t)ctx->num_cus * 16;
     const long long* bi = reinterpret_cast<const long long*>(blocks->blk_indptr[h]);
+    {
+    Timed timed(ctx, DCI_K_MEAN);
     if (V == 4)
       hipLaunchKernelGGL((k_sage_mean<4>), dim3((int)mb), dim3(kMeanBlock), 0, ctx->stream, counts, h, bi,
                          (const int*)blocks->blk_src[h], x, D, lpr_log2, ws.m);
@@ -268,6 +270,7 @@ int32_t dci_sage_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_
     else
       hipLaunchKernelGGL((k_sage_mean<1>), dim3((int)mb), dim3(kMeanBlock), 0, ctx->stream, counts, h, bi,
                          (const int*)blocks->blk_src[h], x, D, lpr_log2, ws.m);
+    }
     DCI_LAUNCH_CHECK(ctx);
     // dense layer
     LinearArgs la;
@@ -284,7 +287,10 @@ int32_t dci_sage_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_
     la.relu = l != n_layers - 1;
     dim3 grid((unsigned)((Do + BN - 1) / BN), (unsigned)((cap + BM - 1) / BM));
     if (grid.y > 65535u) return fail(ctx, DCI_ERR_UNSUPPORTED, "sage_forward: too many row tiles");
-    hipLaunchKernelGGL(k_sage_linear, grid, dim3(kGemmThreads), 0, ctx->stream, la);
+    {
+      Timed timed(ctx, DCI_K_LINEAR);
+      hipLaunchKernelGGL(k_sage_linear, grid, dim3(kGemmThreads), 0, ctx->stream, la);
+    }
     DCI_LAUNCH_CHECK(ctx);
     x = y;
   }

@@ -433,19 +433,34 @@ static int32_t launch_hop(dci_ctx* ctx, const HopArgs& ha, const RowArgs& ra, bo
                           long long* counts, long long* blk_indptr, int* first_base_out, unsigned long long* stats,
                           int last_hop) {
   const int grid = grid_for_rows(ctx, cap_rows, kBlock / G);
-  if (count)
-    hipLaunchKernelGGL((k_sample_hop<G, true>), dim3(grid), dim3(kBlock), 0, ctx->stream, ha);
-  else
-    hipLaunchKernelGGL((k_sample_hop<G, false>), dim3(grid), dim3(kBlock), 0, ctx->stream, ha);
+  {
+    Timed t(ctx, DCI_K_SAMPLE);
+    if (count)
+      hipLaunchKernelGGL((k_sample_hop<G, true>), dim3(grid), dim3(kBlock), 0, ctx->stream, ha);
+    else
+      hipLaunchKernelGGL((k_sample_hop<G, false>), dim3(grid), dim3(kBlock), 0, ctx->stream, ha);
+  }
   DCI_LAUNCH_CHECK(ctx);
-  hipLaunchKernelGGL((k_row_first<G>), dim3(grid), dim3(kBlock), 0, ctx->stream, ra);
+  {
+    Timed t(ctx, DCI_K_ROW_FIRST);
+    hipLaunchKernelGGL((k_row_first<G>), dim3(grid), dim3(kBlock), 0, ctx->stream, ra);
+  }
   DCI_LAUNCH_CHECK(ctx);
-  hipLaunchKernelGGL(k_scan_rows, dim3(1), dim3(kScanThreads), 0, ctx->stream, counts, ra.hop, ra.row_cnt,
-                     (const int*)ra.row_first, blk_indptr, first_base_out, stats, last_hop);
+  {
+    Timed t(ctx, DCI_K_SCAN);
+    hipLaunchKernelGGL(k_scan_rows, dim3(1), dim3(kScanThreads), 0, ctx->stream, counts, ra.hop, ra.row_cnt,
+                       (const int*)ra.row_first, blk_indptr, first_base_out, stats, last_hop);
+  }
   DCI_LAUNCH_CHECK(ctx);
-  hipLaunchKernelGGL((k_assign_new<G>), dim3(grid), dim3(kBlock), 0, ctx->stream, ra);
+  {
+    Timed t(ctx, DCI_K_ASSIGN);
+    hipLaunchKernelGGL((k_assign_new<G>), dim3(grid), dim3(kBlock), 0, ctx->stream, ra);
+  }
   DCI_LAUNCH_CHECK(ctx);
-  hipLaunchKernelGGL((k_write_src<G>), dim3(grid), dim3(kBlock), 0, ctx->stream, ra);
+  {
+    Timed t(ctx, DCI_K_WRITE_SRC);
+    hipLaunchKernelGGL((k_write_src<G>), dim3(grid), dim3(kBlock), 0, ctx->stream, ra);
+  }
   DCI_LAUNCH_CHECK(ctx);
   return DCI_OK;
 }
@@ -455,7 +470,11 @@ static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* c
                             int64_t n_seeds, uint64_t batch_index, const int32_t* fanouts, int32_t n_hops,
                             uint64_t rng_seed, const dci_blocks* out, const SampleWs& ws, uint64_t* stats,
                             uint32_t* feat_count, uint32_t* adj_count, uint32_t* edge_count) {
-  int rc = fill_bytes(ctx, ws.table, ws.table_entries * sizeof(HashEntry), 0xFFFFFFFFu);
+  int rc;
+  {
+    Timed t(ctx, DCI_K_TABLE_CLEAR);
+    rc = fill_bytes(ctx, ws.table, ws.table_entries * sizeof(HashEntry), 0xFFFFFFFFu);
+  }
   if (rc != DCI_OK) return rc;
   const unsigned mask = (unsigned)(ws.table_entries - 1);
   int log2n = 0;
@@ -465,6 +484,7 @@ static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* c
   long long* nodes = reinterpret_cast<long long*>(out->nodes);
   {
     int grid = grid_for_rows(ctx, n_seeds, kBlock);
+    Timed t(ctx, DCI_K_INIT);
     hipLaunchKernelGGL(k_init_batch, dim3(grid), dim3(kBlock), 0, ctx->stream,
                        reinterpret_cast<const long long*>(seeds), (long long)n_seeds, nodes, counts, ws.table, mask,
                        shift);
@@ -523,6 +543,7 @@ static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* c
   }
   if (feat_count) {
     int grid = grid_for_rows(ctx, out->cap_nodes, kBlock);
+    Timed t(ctx, DCI_K_COUNT_NODES);
     hipLaunchKernelGGL(k_count_input_nodes, dim3(grid), dim3(kBlock), 0, ctx->stream, (const long long*)nodes,
                        (const long long*)counts, n_hops, feat_count);
     DCI_LAUNCH_CHECK(ctx);
