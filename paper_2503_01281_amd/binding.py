@@ -297,6 +297,8 @@ def dci_gather_features(ctx: Context, graph: Graph, cache: Optional[Cache], node
     """``n_dev`` is the device address of an int64 row count (e.g. ``blocks.n_input_dev()``) or None."""
     assert node_ids.is_cuda and node_ids.dtype == torch.int64 and out.is_cuda and out.dtype == torch.float32
     assert out.numel() >= n_max * graph.feat_dim and node_ids.numel() >= n_max
+    if stats is not None:
+        ctx.ensure_workspace(1 << 20)
     ctx.check(ctx.lib.dci_gather_features(ctx.handle, C.byref(graph.c), None if cache is None else C.byref(cache.c),
                                           _ptr(node_ids), n_max, n_dev, _ptr(out), _ptr(stats)))
 

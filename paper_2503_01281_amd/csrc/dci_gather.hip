@@ -33,7 +33,8 @@ __global__ __launch_bounds__(kGatherBlock) void k_gather(const long long* __rest
                                                          const int* __restrict__ remap,
                                                          const float* __restrict__ cache,
                                                          const float* __restrict__ feat, int F, int lpr_log2,
-                                                         float* __restrict__ out, unsigned long long* stats) {
+                                                         float* __restrict__ out,
+                                                         unsigned long long* __restrict__ partials) {
   typedef typename VecT<V>::type vec_t;
   long long n = n_dev ? *n_dev : n_max;
   if (n > n_max) n = n_max;
@@ -64,18 +65,59 @@ __global__ __launch_bounds__(kGatherBlock) void k_gather(const long long* __rest
       for (; c < chunks; c += lpr) dst[c] = src[c];
     }
   }
-  if (stats) {
+  if (partials) {
+    // Hit / miss totals leave the kernel as one pair per workgroup; thousands of atomics on
+    // one counter would serialise in L2 and cost more than the copy itself.
+    __shared__ unsigned long long s_h[kGatherBlock / kWave], s_m[kGatherBlock / kWave];
     hits = wave_sum_u64(hits);
     misses = wave_sum_u64(misses);
     if (lane_id() == 0) {
-      if (hits) atomicAdd(&stats[DCI_STAT_FEAT_HITS], hits);
-      if (misses) atomicAdd(&stats[DCI_STAT_FEAT_MISSES], misses);
+      s_h[threadIdx.x / kWave] = hits;
+      s_m[threadIdx.x / kWave] = misses;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      unsigned long long h = 0, m = 0;
+      for (int w = 0; w < kGatherBlock / kWave; ++w) {
+        h += s_h[w];
+        m += s_m[w];
+      }
+      partials[2 * blockIdx.x] = h;
+      partials[2 * blockIdx.x + 1] = m;
     }
   }
 }
 
+__global__ __launch_bounds__(kGatherBlock) void k_fold_gather_stats(const unsigned long long* __restrict__ partials,
+                                                                    int n_blocks, unsigned long long* stats) {
+  unsigned long long h = 0, m = 0;
+  for (int b = (int)threadIdx.x; b < n_blocks; b += kGatherBlock) {
+    h += partials[2 * b];
+    m += partials[2 * b + 1];
+  }
+  __shared__ unsigned long long s_h[kGatherBlock / kWave], s_m[kGatherBlock / kWave];
+  h = wave_sum_u64(h);
+  m = wave_sum_u64(m);
+  if (lane_id() == 0) {
+    s_h[threadIdx.x / kWave] = h;
+    s_m[threadIdx.x / kWave] = m;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    h = m = 0;
+    for (int w = 0; w < kGatherBlock / kWave; ++w) {
+      h += s_h[w];
+      m += s_m[w];
+    }
+    atomicAdd(&stats[DCI_STAT_FEAT_HITS], h);
+    atomicAdd(&stats[DCI_STAT_FEAT_MISSES], m);
+  }
+}
+
+size_t gather_partials_bytes(const dci_ctx* ctx) { return (size_t)ctx->num_cus * 16 * 2 * sizeof(unsigned long long); }
+
 int32_t gather_launch(dci_ctx* ctx, const dci_graph* g, const dci_cache* cache, const int64_t* ids, int64_t n_max,
-                      const int64_t* n_dev, float* out, uint64_t* stats) {
+                      const int64_t* n_dev, float* out, uint64_t* stats, void* partials_buf) {
   const int F = g->feat_dim;
   const float* fcache = cache ? cache->feat_cache : nullptr;
   const int* remap = cache ? cache->feat_remap : nullptr;
@@ -96,7 +138,8 @@ int32_t gather_launch(dci_ctx* ctx, const dci_graph* g, const dci_cache* cache, 
   if (blocks < 1) blocks = 1;
   const long long* ids_ = reinterpret_cast<const long long*>(ids);
   const long long* nd_ = reinterpret_cast<const long long*>(n_dev);
-  unsigned long long* st = reinterpret_cast<unsigned long long*>(stats);
+  unsigned long long* st = stats ? reinterpret_cast<unsigned long long*>(partials_buf) : nullptr;
+  {
   Timed timed(ctx, DCI_K_GATHER);
   if (V == 4)
     hipLaunchKernelGGL((k_gather<4>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_, (long long)n_max,
@@ -107,7 +150,13 @@ int32_t gather_launch(dci_ctx* ctx, const dci_graph* g, const dci_cache* cache, 
   else
     hipLaunchKernelGGL((k_gather<1>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_, (long long)n_max,
                        nd_, remap, fcache, g->feat, F, lpr_log2, out, st);
+  }
   DCI_LAUNCH_CHECK(ctx);
+  if (st) {
+    hipLaunchKernelGGL(k_fold_gather_stats, dim3(1), dim3(kGatherBlock), 0, ctx->stream,
+                       (const unsigned long long*)st, (int)blocks, reinterpret_cast<unsigned long long*>(stats));
+    DCI_LAUNCH_CHECK(ctx);
+  }
   return DCI_OK;
 }
 
@@ -124,5 +173,13 @@ extern "C" int32_t dci_gather_features(dci_ctx* ctx, const dci_graph* graph, con
   if (cache && (!cache->feat_remap || (cache->feat_rows > 0 && !cache->feat_cache)))
     return dci::fail(ctx, DCI_ERR_INVALID_ARG, "cache: null feature arrays");
   if (n_max == 0) return DCI_OK;
-  return dci::gather_launch(ctx, graph, cache, node_ids, n_max, n_dev, out, stats);
+  void* partials = nullptr;
+  if (stats) {
+    dci::Arena ar(ctx->ws, ctx->ws_bytes);
+    partials = ar.take<char>(dci::gather_partials_bytes(ctx));
+    if (!ar.ok())
+      return dci::fail(ctx, DCI_ERR_CAPACITY, "workspace holds %zu bytes, gather statistics need %zu", ctx->ws_bytes,
+                       ar.off);
+  }
+  return dci::gather_launch(ctx, graph, cache, node_ids, n_max, n_dev, out, stats, partials);
 }

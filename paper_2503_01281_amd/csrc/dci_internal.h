@@ -134,8 +134,10 @@ __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long x)
 __global__ void k_fill_u32x4(uint4* __restrict__ p, size_t n16, uint32_t pattern);
 
 int32_t fill_bytes(dci_ctx* ctx, void* p, size_t bytes, uint32_t pattern);
+// partials_buf: gather_partials_bytes(ctx) bytes of device scratch, needed when stats != NULL
 int32_t gather_launch(dci_ctx* ctx, const dci_graph* g, const dci_cache* cache, const int64_t* ids,
-                      int64_t n_max, const int64_t* n_dev, float* out, uint64_t* stats);
+                      int64_t n_max, const int64_t* n_dev, float* out, uint64_t* stats, void* partials_buf);
+size_t gather_partials_bytes(const dci_ctx* ctx);
 
 }  // namespace dci
 

@@ -31,6 +31,8 @@ static_assert(sizeof(HashEntry) == 16, "hash entry must be 16 bytes");
 constexpr unsigned int kTentative = 0x80000000u;
 constexpr long long kEmptyKey = -1;
 constexpr int kBlock = 256;
+constexpr int kRowHitBit = 1 << 30;   // row_cnt[i] = sampled edges of row i | this bit if the list was cached
+constexpr int kRowCntMask = kRowHitBit - 1;
 
 // ---- Philox4x32-10 (Salmon et al., SC'11), counter-based ---------------------------------
 __device__ __forceinline__ unsigned long long philox_u64(unsigned c0, unsigned c1, unsigned c2, unsigned c3,
@@ -119,7 +121,6 @@ struct HopArgs {
   int shift;
   unsigned* adj_count;
   unsigned* edge_count;
-  unsigned long long* stats;
 };
 
 template <int G, bool COUNT>
@@ -131,7 +132,6 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
   constexpr int kGroups = kBlock / G;
   const int grp_in_block = (int)threadIdx.x / G;
   const int f = a.fanout;
-  unsigned long long st_nh = 0, st_nm = 0, st_eh = 0, st_em = 0;
 
   for (long long base = (long long)blockIdx.x * kGroups; base < n_rows; base += (long long)gridDim.x * kGroups) {
     const long long i = base + grp_in_block;
@@ -184,27 +184,9 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
       }
     }
     if (row_ok && gl == 0) {
-      a.row_cnt[i] = c;
+      // the hit flag rides in bit 30 so that the row scan can total the hit statistics
+      a.row_cnt[i] = c | (hit ? kRowHitBit : 0);
       if (COUNT && c > 0) atomicAdd(&a.adj_count[v], (unsigned)c);
-      if (hit) {
-        st_nh += 1;
-        st_eh += (unsigned)c;
-      } else {
-        st_nm += 1;
-        st_em += (unsigned)c;
-      }
-    }
-  }
-  if (a.stats) {
-    st_nh = wave_sum_u64(st_nh);
-    st_nm = wave_sum_u64(st_nm);
-    st_eh = wave_sum_u64(st_eh);
-    st_em = wave_sum_u64(st_em);
-    if (lane == 0) {
-      if (st_nh) atomicAdd(&a.stats[DCI_STAT_ADJ_NODE_HITS], st_nh);
-      if (st_nm) atomicAdd(&a.stats[DCI_STAT_ADJ_NODE_MISSES], st_nm);
-      if (st_eh) atomicAdd(&a.stats[DCI_STAT_ADJ_EDGE_HITS], st_eh);
-      if (st_em) atomicAdd(&a.stats[DCI_STAT_ADJ_EDGE_MISSES], st_em);
     }
   }
 }
@@ -234,7 +216,7 @@ __global__ __launch_bounds__(kBlock) void k_row_first(RowArgs a) {
   for (long long base = (long long)blockIdx.x * kGroups; base < n_rows; base += (long long)gridDim.x * kGroups) {
     const long long i = base + grp_in_block;
     const bool row_ok = i < n_rows;
-    const int c = row_ok ? a.row_cnt[i] : 0;
+    const int c = row_ok ? (a.row_cnt[i] & kRowCntMask) : 0;
     bool first = false;
     if (gl < c) {
       const int p = (int)(i * a.fanout + gl);
@@ -261,6 +243,7 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_rows(long long* __restric
   const int tid = (int)threadIdx.x, lane = lane_id(), wave = tid / kWave;
   long long carry_c = 0;
   int carry_f = 0;
+  unsigned long long hit_rows = 0, hit_edges = 0;
   for (long long base = 0; base < n; base += (long long)kScanThreads * kScanItems) {
     int c[kScanItems], fr[kScanItems];
     long long tc = 0;
@@ -268,7 +251,12 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_rows(long long* __restric
 #pragma unroll
     for (int k = 0; k < kScanItems; ++k) {
       const long long idx = base + (long long)tid * kScanItems + k;
-      c[k] = idx < n ? row_cnt[idx] : 0;
+      const int raw = idx < n ? row_cnt[idx] : 0;
+      c[k] = raw & kRowCntMask;
+      if (raw & kRowHitBit) {
+        hit_rows += 1;
+        hit_edges += (unsigned)c[k];
+      }
       fr[k] = idx < n ? row_first[idx] : 0;
       tc += c[k];
       tf += fr[k];
@@ -307,12 +295,30 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_rows(long long* __restric
     carry_f += tot_f;
     __syncthreads();
   }
+  // hit totals of the hop: per-wave sums through LDS, then one thread publishes everything
+  __shared__ unsigned long long s_hr[kScanThreads / kWave], s_he[kScanThreads / kWave];
+  hit_rows = wave_sum_u64(hit_rows);
+  hit_edges = wave_sum_u64(hit_edges);
+  if (lane == 0) {
+    s_hr[wave] = hit_rows;
+    s_he[wave] = hit_edges;
+  }
+  __syncthreads();
   if (tid == 0) {
     blk_indptr[0] = 0;
     counts[hop + 1] = n + carry_f;
     counts[DCI_MAX_HOPS + 1 + hop] = carry_c;
     if (stats) {
+      unsigned long long hr = 0, he = 0;
+      for (int w = 0; w < kScanThreads / kWave; ++w) {
+        hr += s_hr[w];
+        he += s_he[w];
+      }
       atomicAdd(&stats[DCI_STAT_EDGES_SAMPLED], (unsigned long long)carry_c);
+      atomicAdd(&stats[DCI_STAT_ADJ_NODE_HITS], hr);
+      atomicAdd(&stats[DCI_STAT_ADJ_NODE_MISSES], (unsigned long long)n - hr);
+      atomicAdd(&stats[DCI_STAT_ADJ_EDGE_HITS], he);
+      atomicAdd(&stats[DCI_STAT_ADJ_EDGE_MISSES], (unsigned long long)carry_c - he);
       if (last_hop) atomicAdd(&stats[DCI_STAT_INPUT_NODES], (unsigned long long)(n + carry_f));
     }
   }
@@ -328,7 +334,7 @@ __global__ __launch_bounds__(kBlock) void k_assign_new(RowArgs a) {
   for (long long base = (long long)blockIdx.x * kGroups; base < n_rows; base += (long long)gridDim.x * kGroups) {
     const long long i = base + grp_in_block;
     const bool row_ok = i < n_rows;
-    const int c = row_ok ? a.row_cnt[i] : 0;
+    const int c = row_ok ? (a.row_cnt[i] & kRowCntMask) : 0;
     bool first = false;
     int p = 0, slot = 0;
     if (gl < c) {
@@ -355,7 +361,7 @@ __global__ __launch_bounds__(kBlock) void k_write_src(RowArgs a) {
   const int grp_in_block = (int)threadIdx.x / G;
   for (long long base = (long long)blockIdx.x * kGroups; base < n_rows; base += (long long)gridDim.x * kGroups) {
     const long long i = base + grp_in_block;
-    if (i < n_rows && gl < a.row_cnt[i]) {
+    if (i < n_rows && gl < (a.row_cnt[i] & kRowCntMask)) {
       const int p = (int)(i * a.fanout + gl);
       a.blk_src[a.blk_indptr[i] + gl] = (int)a.table[a.tmp_slot[p]].val;
     }
@@ -513,7 +519,6 @@ static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* c
     ha.shift = shift;
     ha.adj_count = adj_count;
     ha.edge_count = edge_count;
-    ha.stats = reinterpret_cast<unsigned long long*>(stats);
     RowArgs ra;
     ra.counts = counts;
     ra.hop = h;
@@ -586,6 +591,7 @@ size_t dci_sample_workspace_bytes(int64_t num_nodes, int64_t n_seeds, const int3
   dci_blocks b;
   carve_sample_ws(ar, cap_nodes, cap_edges, n_hops, &ws);
   carve_blocks(ar, cap_nodes, cap_edges, n_hops, &b);
+  (void)ar.take<char>(256 * 1024);  // room for the gather statistics of the pre-sampling pass
   return ar.off;
 }
 
@@ -651,6 +657,7 @@ int32_t dci_presample_count(dci_ctx* ctx, const dci_graph* graph, const dci_cach
   dci_blocks blk;
   carve_sample_ws(ar, cap_nodes, cap_edges, n_hops, &ws);
   carve_blocks(ar, cap_nodes, cap_edges, n_hops, &blk);
+  void* gather_partials = ar.take<char>(gather_partials_bytes(ctx));
   if (!ar.ok())
     return fail(ctx, DCI_ERR_CAPACITY, "workspace holds %zu bytes, pre-sampling needs %zu", ctx->ws_bytes, ar.off);
   double ms_sample = 0.0, ms_feature = 0.0;
@@ -664,7 +671,8 @@ int32_t dci_presample_count(dci_ctx* ctx, const dci_graph* graph, const dci_cach
     if (rc != DCI_OK) return rc;
     if (feat_scratch) {
       DCI_HIP(ctx, hipEventRecord(ctx->ev[1], ctx->stream));
-      rc = gather_launch(ctx, graph, cache, blk.nodes, cap_nodes[n_hops], blk.counts + n_hops, feat_scratch, stats);
+      rc = gather_launch(ctx, graph, cache, blk.nodes, cap_nodes[n_hops], blk.counts + n_hops, feat_scratch, stats,
+                         gather_partials);
       if (rc != DCI_OK) return rc;
       DCI_HIP(ctx, hipEventRecord(ctx->ev[2], ctx->stream));
       DCI_HIP(ctx, hipEventSynchronize(ctx->ev[2]));
