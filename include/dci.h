@@ -145,10 +145,12 @@ enum {
   DCI_K_ASSIGN = 5,      /* per hop: new local ids                                 */
   DCI_K_WRITE_SRC = 6,   /* per hop: local id of every edge                        */
   DCI_K_GATHER = 7,      /* feature gather                                         */
-  DCI_K_MEAN = 8,        /* per layer: neighbour mean                              */
-  DCI_K_LINEAR = 9,      /* per layer: dense layer on the matrix cores             */
+  DCI_K_MEAN = 8,        /* layers after the first: neighbour mean                 */
+  DCI_K_LINEAR = 9,      /* layers after the first: dense layer on the matrix cores */
   DCI_K_COUNT_NODES = 10,/* pre-sampling: visits of the input nodes                */
-  DCI_K_COUNT = 11
+  DCI_K_MEAN_IN = 11,    /* first layer (input features): neighbour mean           */
+  DCI_K_LINEAR_IN = 12,  /* first layer (input features): dense layer              */
+  DCI_K_COUNT = 13
 };
 #define DCI_TIMING_MAX_LAUNCHES 8192
 int32_t dci_timing_enable(dci_ctx* ctx, uint32_t class_mask);

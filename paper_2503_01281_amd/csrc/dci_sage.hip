@@ -5,9 +5,8 @@
 //                   per destination row, consecutive lanes on consecutive chunks of the row);
 //   k_sage_linear - y = x W_self + m W_neigh + b (+ ReLU): one dense contraction over the
 //                   concatenated K = 2*D axis on the matrix cores (v_mfma_f32_32x32x2f32, fp32 in,
-//                   fp32 accumulate), 128x128 output tile per workgroup of four wavefronts,
-//                   operands staged through LDS in k-major order so that fragment reads are
-//                   conflict free.
+//                   fp32 accumulate), operands staged through LDS in k-major order so that
+//                   fragment reads are conflict free.
 // Row counts come from the block's device-side `counts`, so no host round trip is needed; the
 // grids are sized for the capacities and surplus workgroups leave at once.
 #include "dci_internal.h"
@@ -84,7 +83,18 @@ __global__ __launch_bounds__(kMeanBlock) void k_sage_mean(const long long* __res
 }
 
 // ---- dense layer on the matrix cores ---------------------------------------------------------
-constexpr int BM = 128, BN = 128, BK = 16, LDS_PAD = 4;
+// y[M, N] = a_self[M, K] w_self[K, N] + a_neigh[M, K] w_neigh[K, N] + bias, i.e. one contraction
+// over the concatenated axis of length 2K.  M is read from device memory.
+//
+// Tiling: 64x64 outputs per workgroup of four wavefronts, each wavefront one 32x32 MFMA tile
+// (v_mfma_f32_32x32x2f32: lane l feeds A[l%32][l/32] and B[l/32][l%32]).  fp32 matrix math is
+// slow enough (64 cycles per instruction) that small tiles keep the matrix cores fed, and the
+// row counts of a mini-batch are small enough (thousands) that large tiles would leave most of
+// the 256 compute units idle.  Operands go global -> registers -> LDS (k-major, so fragment
+// reads hit consecutive banks) with the next k-slab in flight while the current one is used.
+// Workgroup ids are mapped so that the column tiles of one row tile run on the same XCD and
+// share its L2.
+constexpr int TM = 64, TN = 64, TK = 32, LDS_PAD = 4;
 constexpr int kGemmThreads = 256;
 
 struct LinearArgs {
@@ -97,97 +107,136 @@ struct LinearArgs {
   const float* bias;     // [N]
   float* y;              // [M, N]
   int K, N, relu;
+  int n_tiles_n;
 };
 
+// VA: floats per global access along K for the activations (needs K % VA == 0 and aligned bases)
+// VB: floats per global access along N for the weights (needs N % VB == 0)
+template <int VA, int VB>
 __global__ __launch_bounds__(kGemmThreads) void k_sage_linear(LinearArgs a) {
-  __shared__ float As[2][BK][BM + LDS_PAD];
-  __shared__ float Bs[2][BK][BN + LDS_PAD];
+  __shared__ __attribute__((aligned(16))) float As[2][TK][TM + LDS_PAD];
+  __shared__ __attribute__((aligned(16))) float Bs[2][TK][TN + LDS_PAD];
   const long long M = a.counts[a.hop];
-  const long long row0 = (long long)blockIdx.y * BM;
-  const int col0 = (int)blockIdx.x * BN;
+  const int id = (int)blockIdx.x;
+  const int xcd = id & 7, j = id >> 3;
+  const int nt = j % a.n_tiles_n;
+  const long long row0 = ((long long)(j / a.n_tiles_n) * 8 + xcd) * TM;
+  const int col0 = nt * TN;
   if (row0 >= M) return;
   const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int K = a.K, N = a.N;
-  const int kt_per_src = (K + BK - 1) / BK;
+  const int kt_per_src = (K + TK - 1) / TK;
   const int n_kt = 2 * kt_per_src;
 
-  floatx16 acc[2][2];
+  // two accumulators (even / odd k pairs) so that consecutive matrix instructions are independent
+  floatx16 acc, acc1;
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  for (int r = 0; r < 16; ++r) {
+    acc[r] = 0.f;
+    acc1[r] = 0.f;
+  }
 
-  float ra[8], rb[8];
-  auto load_tile = [&](int kt) {
+  constexpr int kPer = TM * TK / kGemmThreads;  // floats of each operand per thread and slab
+  auto load_slab = [&](int kt, float (&ra)[kPer], float (&rb)[kPer]) {
     const bool second = kt >= kt_per_src;
     const float* A = second ? a.a_neigh : a.a_self;
     const float* W = second ? a.w_neigh : a.w_self;
-    const int k0 = (second ? kt - kt_per_src : kt) * BK;
+    const int k0 = (second ? kt - kt_per_src : kt) * TK;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
+    for (int q = 0; q < kPer / VA; ++q) {
       const int e = tid + kGemmThreads * q;
-      const int ak = e & (BK - 1), ar = e >> 4;  // A: 16 consecutive k per row
-      const long long row = row0 + ar;
-      ra[q] = (row < M && k0 + ak < K) ? A[row * K + k0 + ak] : 0.f;
-      const int bn = e & (BN - 1), bk = e >> 7;  // W: 128 consecutive n per k
-      rb[q] = (k0 + bk < K && col0 + bn < N) ? W[(long long)(k0 + bk) * N + col0 + bn] : 0.f;
+      const int kc = e % (TK / VA), m = e / (TK / VA);
+      const long long row = row0 + m;
+      const int k = k0 + kc * VA;
+      const bool ok = row < M && k < K;
+      if (VA == 4) {
+        const float4 v = ok ? *reinterpret_cast<const float4*>(A + row * K + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+        ra[4 * q] = v.x; ra[4 * q + 1] = v.y; ra[4 * q + 2] = v.z; ra[4 * q + 3] = v.w;
+      } else if (VA == 2) {
+        const float2 v = ok ? *reinterpret_cast<const float2*>(A + row * K + k) : make_float2(0.f, 0.f);
+        ra[2 * q] = v.x; ra[2 * q + 1] = v.y;
+      } else {
+        ra[q] = ok ? A[row * K + k] : 0.f;
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < kPer / VB; ++q) {
+      const int e = tid + kGemmThreads * q;
+      const int nc = e % (TN / VB), kk = e / (TN / VB);
+      const int n = col0 + nc * VB;
+      const bool ok = k0 + kk < K && n < N;
+      if (VB == 4) {
+        const float4 v = ok ? *reinterpret_cast<const float4*>(W + (long long)(k0 + kk) * N + n) : make_float4(0.f, 0.f, 0.f, 0.f);
+        rb[4 * q] = v.x; rb[4 * q + 1] = v.y; rb[4 * q + 2] = v.z; rb[4 * q + 3] = v.w;
+      } else {
+        rb[q] = ok ? W[(long long)(k0 + kk) * N + n] : 0.f;
+      }
     }
   };
-  auto store_tile = [&](int buf) {
+  auto store_slab = [&](int buf, const float (&ra)[kPer], const float (&rb)[kPer]) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
+    for (int q = 0; q < kPer / VA; ++q) {
       const int e = tid + kGemmThreads * q;
-      As[buf][e & (BK - 1)][e >> 4] = ra[q];
-      Bs[buf][e >> 7][e & (BN - 1)] = rb[q];
+      const int kc = e % (TK / VA), m = e / (TK / VA);
+#pragma unroll
+      for (int v = 0; v < VA; ++v) As[buf][kc * VA + v][m] = ra[VA * q + v];
+    }
+#pragma unroll
+    for (int q = 0; q < kPer / VB; ++q) {
+      const int e = tid + kGemmThreads * q;
+      const int nc = e % (TN / VB), kk = e / (TN / VB);
+      if (VB == 4)
+        *reinterpret_cast<float4*>(&Bs[buf][kk][nc * 4]) = make_float4(rb[4 * q], rb[4 * q + 1], rb[4 * q + 2], rb[4 * q + 3]);
+      else
+        Bs[buf][kk][nc] = rb[q];
+    }
+  };
+  const int am = wm * 32 + (lane & 31), bn = wn * 32 + (lane & 31), kh = lane >> 5;
+  auto compute = [&](int buf) {
+#pragma unroll
+    for (int kk = 0; kk < TK / 2; kk += 2) {
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(As[buf][2 * kk + kh][am], Bs[buf][2 * kk + kh][bn], acc, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(As[buf][2 * kk + 2 + kh][am], Bs[buf][2 * kk + 2 + kh][bn], acc1, 0, 0, 0);
     }
   };
 
-  load_tile(0);
-  store_tile(0);
+  // Software pipeline over the (even number of) k-slabs: while slab kt is multiplied out of one
+  // LDS buffer, slab kt+1 sits in registers on its way to the other buffer and the global loads
+  // of slab kt+2 are already in flight, so a slab has two iterations to arrive.
+  float ra0[kPer], rb0[kPer], ra1[kPer], rb1[kPer];
+  load_slab(0, ra0, rb0);
+  load_slab(1, ra1, rb1);
+  store_slab(0, ra0, rb0);
   __syncthreads();
-  for (int kt = 0; kt < n_kt; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < n_kt) load_tile(kt + 1);
-#pragma unroll
-    for (int kk = 0; kk < BK / 2; ++kk) {
-      const int k = 2 * kk + (lane >> 5);
-      float fa[2], fb[2];
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        fa[t] = As[buf][k][wm * 64 + t * 32 + (lane & 31)];
-        fb[t] = Bs[buf][k][wn * 64 + t * 32 + (lane & 31)];
-      }
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < n_kt) store_tile(buf ^ 1);
+  for (int kt = 0; kt < n_kt; kt += 2) {
+    if (kt + 2 < n_kt) load_slab(kt + 2, ra0, rb0);
+    compute(0);
+    store_slab(1, ra1, rb1);
+    __syncthreads();
+    if (kt + 3 < n_kt) load_slab(kt + 3, ra1, rb1);
+    compute(1);
+    if (kt + 2 < n_kt) store_slab(0, ra0, rb0);
     __syncthreads();
   }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] += acc1[r];
 
   // accumulator layout of the 32x32 tile: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4,
   // column l%32.
+  const int col = col0 + bn;
+  if (col < N) {
+    const float b = a.bias[col];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int col = col0 + wn * 64 + j * 32 + (lane & 31);
-      if (col >= N) continue;
-      const float b = a.bias[col];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const long long row = row0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (row < M) {
-          float v = acc[i][j][r] + b;
-          if (a.relu) v = v > 0.f ? v : 0.f;
-          a.y[row * N + col] = v;
-        }
+    for (int r = 0; r < 16; ++r) {
+      const long long row = row0 + wm * 32 + 8 * (r >> 2) + 4 * kh + (r & 3);
+      if (row < M) {
+        float v = acc[r] + b;
+        if (a.relu) v = v > 0.f ? v : 0.f;
+        a.y[row * N + col] = v;
       }
     }
+  }
 }
 
 struct SageWs {
@@ -260,7 +309,7 @@ int32_t dci_sage_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_
     if (mb > (int64_t)ctx->num_cus * 16) mb = (int64_t)ctx->num_cus * 16;
     const long long* bi = reinterpret_cast<const long long*>(blocks->blk_indptr[h]);
     {
-    Timed timed(ctx, DCI_K_MEAN);
+    Timed timed(ctx, l == 0 ? DCI_K_MEAN_IN : DCI_K_MEAN);
     if (V == 4)
       hipLaunchKernelGGL((k_sage_mean<4>), dim3((int)mb), dim3(kMeanBlock), 0, ctx->stream, counts, h, bi,
                          (const int*)blocks->blk_src[h], x, D, lpr_log2, ws.m);
@@ -285,11 +334,29 @@ int32_t dci_sage_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_
     la.K = D;
     la.N = Do;
     la.relu = l != n_layers - 1;
-    dim3 grid((unsigned)((Do + BN - 1) / BN), (unsigned)((cap + BM - 1) / BM));
-    if (grid.y > 65535u) return fail(ctx, DCI_ERR_UNSUPPORTED, "sage_forward: too many row tiles");
+    la.n_tiles_n = (Do + TN - 1) / TN;
+    const int64_t m_tiles8 = ((cap + TM - 1) / TM + 7) / 8 * 8;  // row tiles, rounded up to whole XCD rounds
+    const int64_t n_blocks = m_tiles8 * la.n_tiles_n;
+    if (n_blocks >= ((int64_t)1 << 31)) return fail(ctx, DCI_ERR_UNSUPPORTED, "sage_forward: too many tiles");
+    int va = 1;
+    if (D % 4 == 0 && aligned(x, 16) && aligned(ws.m, 16)) va = 4;
+    else if (D % 2 == 0 && aligned(x, 8) && aligned(ws.m, 8)) va = 2;
+    const int vb = (Do % 4 == 0 && aligned(w_self[l], 16) && aligned(w_neigh[l], 16)) ? 4 : 1;
+    dim3 grid((unsigned)n_blocks);
     {
-      Timed timed(ctx, DCI_K_LINEAR);
-      hipLaunchKernelGGL(k_sage_linear, grid, dim3(kGemmThreads), 0, ctx->stream, la);
+      Timed timed(ctx, l == 0 ? DCI_K_LINEAR_IN : DCI_K_LINEAR);
+      if (va == 4 && vb == 4)
+        hipLaunchKernelGGL((k_sage_linear<4, 4>), grid, dim3(kGemmThreads), 0, ctx->stream, la);
+      else if (va == 4)
+        hipLaunchKernelGGL((k_sage_linear<4, 1>), grid, dim3(kGemmThreads), 0, ctx->stream, la);
+      else if (va == 2 && vb == 4)
+        hipLaunchKernelGGL((k_sage_linear<2, 4>), grid, dim3(kGemmThreads), 0, ctx->stream, la);
+      else if (va == 2)
+        hipLaunchKernelGGL((k_sage_linear<2, 1>), grid, dim3(kGemmThreads), 0, ctx->stream, la);
+      else if (vb == 4)
+        hipLaunchKernelGGL((k_sage_linear<1, 4>), grid, dim3(kGemmThreads), 0, ctx->stream, la);
+      else
+        hipLaunchKernelGGL((k_sage_linear<1, 1>), grid, dim3(kGemmThreads), 0, ctx->stream, la);
     }
     DCI_LAUNCH_CHECK(ctx);
     x = y;
