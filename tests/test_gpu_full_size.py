@@ -1,0 +1,123 @@
+"""GPU parity at the full sizes of the medium and large workloads, in the launch configuration that
+bench.py times: counters, remaps and cache arrays in full, two whole batches bit for bit (logits to
+1e-4 of the largest oracle logit), with the configured budget and with a budget small enough that
+both caches are partial."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _setup(name):
+    import paper_2503_01281_amd as dci
+    from tests import gpu_util as gu
+    w = synth.WORKLOADS[name]
+    indptr = torch.empty(w.num_nodes + 1, dtype=torch.int64, pin_memory=True)
+    indices = torch.empty(w.num_edges, dtype=torch.int64, pin_memory=True)
+    feat = torch.empty(w.num_nodes, w.feat_dim, dtype=torch.float32, pin_memory=True)
+    synth.rmat_csr(w.num_nodes, w.num_edges, w.rmat, w.graph_seed, indptr_ptr=indptr.data_ptr(),
+                   indices_ptr=indices.data_ptr())
+    synth.features(w.num_nodes, w.feat_dim, w.feature_seed, ptr=feat.data_ptr())
+    seeds = synth.seeds(w.num_nodes, w.num_seeds, w.seed_seed)
+    ws, wn, bs = synth.sage_weights(w.dims, w.weight_seed)
+    ctx = dci.Context(0)
+    g = dci.Graph(indptr, indices, feat)
+    return dict(dci=dci, gu=gu, w=w, ctx=ctx, g=g, indptr=indptr.numpy(), indices=indices.numpy(), feat=feat.numpy(),
+                seeds=seeds, ws=ws, wn=wn, bs=bs)
+
+
+@pytest.fixture(scope="module", params=["medium", "large"])
+def big(request):
+    return _setup(request.param)
+
+
+def _run_batches(e, cache, batches):
+    dci, gu, w, ctx, g = e["dci"], e["gu"], e["w"], e["ctx"], e["g"]
+    blk = dci.Blocks(ctx, w.num_nodes, w.batch_size, w.fanouts)
+    x = torch.empty(blk.cap_nodes[-1], w.feat_dim, dtype=torch.float32, device="cuda")
+    logits = torch.empty(w.batch_size, w.classes, dtype=torch.float32, device="cuda")
+    ws, wn, bs = ([gu.dev(a) for a in e[k]] for k in ("ws", "wn", "bs"))
+    seeds_dev = gu.dev(e["seeds"])
+    for b in batches:
+        sl = slice(b * w.batch_size, min(w.num_seeds, (b + 1) * w.batch_size))
+        n_seeds = sl.stop - sl.start
+        stats = gu.new_stats()
+        dci.dci_sample_khop(ctx, g, cache, seeds_dev[sl], b, w.fanouts, w.rng_seed, blk, stats)
+        dci.dci_gather_features(ctx, g, cache, blk.nodes, blk.cap_nodes[-1], x, n_dev=blk.n_input_dev(), stats=stats)
+        dci.dci_sage_forward(ctx, blk, x, ws, wn, bs, logits)
+        got = gu.blocks_to_host(ctx, blk)
+        want = oracle.sample_khop(e["indptr"], e["indices"], e["seeds"][sl], b, w.fanouts, w.rng_seed)
+        gu.assert_blocks_equal(got, want)
+        n_in = got["n_nodes"][-1]
+        want_x = oracle.gather(e["feat"], want.nodes)
+        assert x[:n_in].cpu().numpy().tobytes() == want_x.tobytes()
+        ref = oracle.sage_forward(want, want_x, e["ws"], e["wn"], e["bs"])
+        err = float(np.abs(logits[:n_seeds].cpu().numpy() - ref).max())
+        assert err <= 1e-4 * max(1.0, float(np.abs(ref).max())), err
+        yield b, want, gu.stats_dict(ctx, stats)
+
+
+def test_presample_fill_and_batches(big):
+    e = big
+    dci, gu, w, ctx, g = e["dci"], e["gu"], e["w"], e["ctx"], e["g"]
+    # pre-sampling counters, in full
+    fc_w, ac_w, _, (edges, nodes) = oracle.presample_count(e["indptr"], e["indices"], e["seeds"], w.batch_size,
+                                                          w.n_presample, w.fanouts, w.rng_seed,
+                                                          w.presample_first_batch, with_edge_count=False)
+    fc = torch.zeros(w.num_nodes, dtype=torch.int32, device="cuda")
+    ac = torch.zeros(w.num_nodes, dtype=torch.int32, device="cuda")
+    stats = gu.new_stats()
+    dci.dci_presample_count(ctx, g, None, gu.dev(e["seeds"]), w.batch_size, 0, w.n_presample,
+                            w.presample_first_batch, w.fanouts, w.rng_seed, fc, ac, stats=stats)
+    st = gu.stats_dict(ctx, stats)
+    assert np.array_equal(fc.cpu().numpy().view(np.uint32), fc_w)
+    assert np.array_equal(ac.cpu().numpy().view(np.uint32), ac_w)
+    assert (st["edges_sampled"], st["input_nodes"]) == (edges, nodes)
+
+    # the configured budget covers the whole dataset: everything is cached, every access hits
+    cache = dci.dci_fill_caches(ctx, g, fc, ac, w.budget_bytes, 3, 7, 0)
+    assert (cache.adj_nodes, cache.adj_edges, cache.feat_rows) == (w.num_nodes, w.num_edges, w.num_nodes)
+    assert np.array_equal(cache.adj_remap.cpu().numpy(), np.arange(w.num_nodes, dtype=np.int32))
+    fr = cache.feat_remap.cpu().numpy()
+    fr_w, _, _ = oracle.fill_feat(fc_w, None, cache.cap_feat_bytes, 0, feat_dim=w.feat_dim)
+    assert np.array_equal(fr, fr_w)
+    for b, want, st in _run_batches(e, cache, [0, w.num_batches - 1]):
+        assert st["adj_edge_misses"] == 0 and st["feat_misses"] == 0 and st["feat_hits"] == len(want.nodes)
+    del cache
+
+    # a budget under pressure (0.4 GB, the point of the paper's Fig. 11): both caches partial
+    budget = 400_000_000
+    for policy in (0, 1):
+        C_adj, C_feat = oracle.split(budget, 3, 7, w.num_nodes, w.num_edges, w.feat_dim)
+        adj_remap, cp, ci = oracle.fill_adj(e["indptr"], e["indices"], ac_w, C_adj)
+        feat_remap, _, k = oracle.fill_feat(fc_w, None, C_feat, policy, feat_dim=w.feat_dim)
+        cache = dci.dci_fill_caches(ctx, g, fc, ac, budget, 3, 7, policy)
+        assert (cache.cap_adj_bytes, cache.cap_feat_bytes) == (C_adj, C_feat)
+        assert (cache.adj_nodes, cache.adj_edges, cache.feat_rows) == (len(cp) - 1, len(ci), k)
+        assert 0 < cache.adj_nodes < w.num_nodes and 0 < k < w.num_nodes
+        assert np.array_equal(cache.adj_remap.cpu().numpy(), adj_remap)
+        assert np.array_equal(cache.feat_remap.cpu().numpy(), feat_remap)
+        base = cache.buf.data_ptr()
+
+        def view(addr, n, dtype):
+            off = addr - base
+            return cache.buf[off:off + n * torch.tensor([], dtype=dtype).element_size()].view(dtype)
+
+        assert np.array_equal(view(cache.c.c_indptr, len(cp), torch.int64).cpu().numpy(), cp)
+        assert np.array_equal(view(cache.c.c_indices, len(ci), torch.int64).cpu().numpy(), ci)
+        rows = np.flatnonzero(feat_remap >= 0)
+        pick = rows[np.random.default_rng(policy).permutation(len(rows))[:20000]]
+        got_rows = view(cache.c.feat_cache, k * w.feat_dim, torch.float32).view(k, w.feat_dim)[
+            torch.from_numpy(feat_remap[pick].astype(np.int64)).cuda()].cpu().numpy()
+        assert got_rows.tobytes() == e["feat"][pick].tobytes()
+        if policy == 0:
+            for b, want, st in _run_batches(e, cache, [1]):
+                hit = feat_remap[want.nodes] >= 0
+                assert (st["feat_hits"], st["feat_misses"]) == (int(hit.sum()), int((~hit).sum()))
+                assert st["feat_hits"] > 0 and st["feat_misses"] > 0
+                assert st["adj_edge_hits"] > 0 and st["adj_edge_misses"] > 0
+        del cache
