@@ -138,12 +138,13 @@ const char* dci_last_error(const dci_ctx* ctx);
  * and launches[DCI_K_COUNT], and starts over.  class_mask = 0 switches timing off (the default). */
 enum {
   DCI_K_TABLE_CLEAR = 0, /* clearing the batch's hash table                        */
-  DCI_K_INIT = 1,        /* seeds into the frontier                                */
-  DCI_K_SAMPLE = 2,      /* per hop: draw positions, read neighbours, register ids */
-  DCI_K_ROW_FIRST = 3,   /* per hop: first appearances per row                     */
-  DCI_K_SCAN = 4,        /* per hop: row offsets                                   */
-  DCI_K_ASSIGN = 5,      /* per hop: new local ids                                 */
-  DCI_K_WRITE_SRC = 6,   /* per hop: local id of every edge                        */
+  DCI_K_SAMPLE = 1,      /* per hop: draw positions, read neighbours, register ids
+                            (also writes the previous hop's edge local ids)       */
+  DCI_K_RELABEL = 2,     /* per hop: first appearances, row offsets, new local ids */
+  DCI_K_WRITE_SRC = 3,   /* last hop: local id of every edge                       */
+  DCI_K_RESERVED4 = 4,
+  DCI_K_RESERVED5 = 5,
+  DCI_K_RESERVED6 = 6,
   DCI_K_GATHER = 7,      /* feature gather                                         */
   DCI_K_MEAN = 8,        /* layers after the first: neighbour mean                 */
   DCI_K_LINEAR = 9,      /* layers after the first: dense layer on the matrix cores */

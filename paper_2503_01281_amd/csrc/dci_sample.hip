@@ -89,22 +89,11 @@ __device__ __forceinline__ unsigned long long group_bits(unsigned long long ball
 
 // ---- kernels ----------------------------------------------------------------------------------
 
-__global__ __launch_bounds__(kBlock) void k_init_batch(const long long* __restrict__ seeds, long long n_seeds,
-                                                       long long* __restrict__ nodes, long long* __restrict__ counts,
-                                                       HashEntry* table, unsigned mask, int shift) {
-  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n_seeds;
-       i += (long long)gridDim.x * blockDim.x) {
-    const long long v = seeds[i];
-    nodes[i] = v;
-    const unsigned slot = table_find_or_insert(table, mask, shift, v);
-    table_min(table, slot, (unsigned)i);
-  }
-  if (blockIdx.x == 0 && threadIdx.x == 0) counts[0] = n_seeds;
-}
-
 struct HopArgs {
-  const long long* nodes;
-  const long long* counts;
+  const long long* seeds;  // hop 0 only: the seeds become F_0 inside this kernel
+  long long n_seeds;
+  long long* nodes;
+  long long* counts;
   int hop;
   int fanout;
   const long long* indptr;
@@ -121,11 +110,48 @@ struct HopArgs {
   int shift;
   unsigned* adj_count;
   unsigned* edge_count;
+  // previous hop, whose edges get their local ids at the start of this kernel (hop >= 1)
+  int prev_fanout;
+  const int* prev_row_cnt;
+  const int* prev_tmp_slot;
+  const long long* prev_blk_indptr;
+  int* prev_blk_src;
 };
 
-template <int G, bool COUNT>
+// blk_src of a finished hop: every edge reads the (by now final) local id of its source.
+// One thread per padded position row * fanout + slot.
+__device__ __forceinline__ void write_block_sources(long long n_rows, int fanout, const int* __restrict__ row_cnt,
+                                                    const int* __restrict__ tmp_slot,
+                                                    const long long* __restrict__ blk_indptr,
+                                                    const HashEntry* table, int* __restrict__ blk_src) {
+  const long long total = n_rows * fanout;
+  for (long long q = blockIdx.x * (long long)blockDim.x + threadIdx.x; q < total; q += (long long)gridDim.x * blockDim.x) {
+    const long long i = q / fanout;
+    const int s = (int)(q - i * fanout);
+    if (s < (row_cnt[i] & kRowCntMask)) blk_src[blk_indptr[i] + s] = (int)table[tmp_slot[q]].val;
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_write_src(const long long* __restrict__ counts, int hop, int fanout,
+                                                      const int* row_cnt, const int* tmp_slot,
+                                                      const long long* blk_indptr, const HashEntry* table,
+                                                      int* blk_src) {
+  write_block_sources(counts[hop], fanout, row_cnt, tmp_slot, blk_indptr, table, blk_src);
+}
+
+// Phase 1 of a hop.  INIT (hop 0): row i first turns seed i into frontier entry i (final local id
+// i in the table; an atomic minimum, so it also wins against a neighbour lane that registered
+// the same node a moment earlier).  Otherwise the kernel starts by finishing the previous hop
+// (write_block_sources), which only needs values that are already final.
+template <int G, bool COUNT, bool INIT>
 __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
-  const long long n_rows = a.counts[a.hop];
+  const long long n_rows = INIT ? a.n_seeds : a.counts[a.hop];
+  if (INIT) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) a.counts[0] = a.n_seeds;
+  } else {
+    write_block_sources(a.counts[a.hop - 1], a.prev_fanout, a.prev_row_cnt, a.prev_tmp_slot, a.prev_blk_indptr,
+                        a.table, a.prev_blk_src);
+  }
   const int lane = lane_id();
   const int gl = lane & (G - 1);
   const int grp_in_wave = lane / G;
@@ -140,7 +166,15 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
     const long long* list = a.indices;
     bool hit = false;
     if (row_ok) {
-      v = a.nodes[i];
+      if (INIT) {
+        v = a.seeds[i];
+        if (gl == 0) {
+          a.nodes[i] = v;
+          table_min(a.table, table_find_or_insert(a.table, a.mask, a.shift, v), (unsigned)i);
+        }
+      } else {
+        v = a.nodes[i];
+      }
       const int r = a.adj_remap ? a.adj_remap[v] : -1;
       hit = r >= 0;
       if (hit) {
@@ -184,119 +218,121 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
       }
     }
     if (row_ok && gl == 0) {
-      // the hit flag rides in bit 30 so that the row scan can total the hit statistics
+      // the hit flag rides in bit 30 so that the relabel kernel can total the hit statistics
       a.row_cnt[i] = c | (hit ? kRowHitBit : 0);
       if (COUNT && c > 0) atomicAdd(&a.adj_count[v], (unsigned)c);
     }
   }
 }
 
-struct RowArgs {
-  const long long* counts;
+// Phase 2 of a hop, one pass: count the first appearances of every row, prefix-sum edge counts and
+// first-appearance counts over all rows, and give the first appearances their local ids.
+// The prefix sums run as a chained scan over tiles of rows with decoupled look-back: a workgroup
+// takes the next tile number from a ticket counter (so every earlier tile is already running),
+// publishes its own totals, and adds up its predecessors' published values until it meets one
+// that already carries an inclusive prefix.  Status word: flag (2 bits) | firsts (31) | edges (31);
+// the all-ones fill pattern reads as "not yet published".  A status word carries its whole
+// message, so the atomic accesses are relaxed: release / acquire at device scope would add an
+// L2 write-back / invalidate to every publish and every poll.
+constexpr int kTileIters = 8;
+constexpr unsigned long long kStInvalid = 3ull, kStAggregate = 1ull, kStInclusive = 2ull;
+constexpr unsigned kLookbackSpinLimit = 1u << 24;  // polls; far beyond any real wait, ends a wedged launch
+
+__device__ __forceinline__ unsigned long long st_pack(unsigned long long flag, unsigned long long firsts,
+                                                      unsigned long long edges) {
+  return (flag << 62) | (firsts << 31) | edges;
+}
+
+struct RelabelArgs {
+  long long* counts;
   int hop;
   int fanout;
   const int* row_cnt;
-  int* row_first;
-  const int* first_base;
-  const long long* blk_indptr;
   const long long* tmp_u;
   const int* tmp_slot;
   HashEntry* table;
   long long* nodes;
-  int* blk_src;
+  long long* blk_indptr;
+  unsigned long long* status;  // one word per tile, filled with ones beforehand
+  unsigned* ticket;            // filled with ones beforehand: the first ticket is 0xFFFFFFFF + 1 = 0
+  unsigned long long* stats;
+  int last_hop;
 };
 
-// phase 2: number of first appearances per row
 template <int G>
-__global__ __launch_bounds__(kBlock) void k_row_first(RowArgs a) {
-  const long long n_rows = a.counts[a.hop];
-  const int lane = lane_id(), gl = lane & (G - 1), grp_in_wave = lane / G;
+__global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
   constexpr int kGroups = kBlock / G;
-  const int grp_in_block = (int)threadIdx.x / G;
-  for (long long base = (long long)blockIdx.x * kGroups; base < n_rows; base += (long long)gridDim.x * kGroups) {
-    const long long i = base + grp_in_block;
-    const bool row_ok = i < n_rows;
-    const int c = row_ok ? (a.row_cnt[i] & kRowCntMask) : 0;
-    bool first = false;
-    if (gl < c) {
-      const int p = (int)(i * a.fanout + gl);
-      first = a.table[a.tmp_slot[p]].val == (kTentative | (unsigned)p);
-    }
-    const unsigned long long bits = group_bits<G>(__ballot(first), grp_in_wave);
-    if (row_ok && gl == 0) a.row_first[i] = __popcll(bits);
-  }
-}
-
-// phase 3: one workgroup scans the per-row edge counts (-> blk_indptr) and first-appearance
-// counts (-> first_base), then publishes the sizes of the hop.
-constexpr int kScanThreads = 1024;
-constexpr int kScanItems = 4;
-__global__ __launch_bounds__(kScanThreads) void k_scan_rows(long long* __restrict__ counts, int hop,
-                                                            const int* __restrict__ row_cnt,
-                                                            const int* __restrict__ row_first,
-                                                            long long* __restrict__ blk_indptr,
-                                                            int* __restrict__ first_base,
-                                                            unsigned long long* stats, int last_hop) {
-  __shared__ long long s_c[kScanThreads / kWave];
-  __shared__ int s_f[kScanThreads / kWave];
-  const long long n = counts[hop];
+  constexpr int TR = kGroups * kTileIters;  // rows per tile, at most kBlock
+  constexpr int kWaves = kBlock / kWave;
+  static_assert(TR <= kBlock, "one thread per tile row in the block scan");
+  __shared__ int s_c[TR], s_f[TR];
+  __shared__ int s_wc[kWaves], s_wf[kWaves];
+  __shared__ unsigned long long s_hr[kWaves], s_he[kWaves];
+  __shared__ unsigned s_tile;
+  __shared__ long long s_ec;
+  __shared__ int s_ef;
   const int tid = (int)threadIdx.x, lane = lane_id(), wave = tid / kWave;
-  long long carry_c = 0;
-  int carry_f = 0;
-  unsigned long long hit_rows = 0, hit_edges = 0;
-  for (long long base = 0; base < n; base += (long long)kScanThreads * kScanItems) {
-    int c[kScanItems], fr[kScanItems];
-    long long tc = 0;
-    int tf = 0;
-#pragma unroll
-    for (int k = 0; k < kScanItems; ++k) {
-      const long long idx = base + (long long)tid * kScanItems + k;
-      const int raw = idx < n ? row_cnt[idx] : 0;
-      c[k] = raw & kRowCntMask;
-      if (raw & kRowHitBit) {
-        hit_rows += 1;
-        hit_edges += (unsigned)c[k];
-      }
-      fr[k] = idx < n ? row_first[idx] : 0;
-      tc += c[k];
-      tf += fr[k];
+  const int gl = lane & (G - 1), grp_in_wave = lane / G, grp = tid / G;
+  const long long n_rows = a.counts[a.hop];
+  if (tid == 0) s_tile = atomicAdd(a.ticket, 1u) + 1u;
+  __syncthreads();
+  const unsigned tile = s_tile;
+  const long long row0 = (long long)tile * TR;
+  if (row0 >= n_rows) {
+    if (tile == 0 && tid == 0) {  // empty frontier: the hop adds nothing
+      a.blk_indptr[0] = 0;
+      a.counts[a.hop + 1] = n_rows;
+      a.counts[DCI_MAX_HOPS + 1 + a.hop] = 0;
     }
-    const long long inc_c = wave_incl_scan64(tc);
-    const int inc_f = wave_incl_scan(tf);
-    if (lane == kWave - 1) {
-      s_c[wave] = inc_c;
-      s_f[wave] = inc_f;
-    }
-    __syncthreads();
-    long long off_c = carry_c, tot_c = 0;
-    int off_f = carry_f, tot_f = 0;
-#pragma unroll
-    for (int w = 0; w < kScanThreads / kWave; ++w) {
-      if (w < wave) {
-        off_c += s_c[w];
-        off_f += s_f[w];
-      }
-      tot_c += s_c[w];
-      tot_f += s_f[w];
-    }
-    long long run_c = off_c + inc_c - tc;
-    int run_f = off_f + inc_f - tf;
-#pragma unroll
-    for (int k = 0; k < kScanItems; ++k) {
-      const long long idx = base + (long long)tid * kScanItems + k;
-      if (idx < n) {
-        first_base[idx] = run_f;
-        run_c += c[k];
-        run_f += fr[k];
-        blk_indptr[idx + 1] = run_c;
-      }
-    }
-    carry_c += tot_c;
-    carry_f += tot_f;
-    __syncthreads();
+    return;
   }
-  // hit totals of the hop: per-wave sums through LDS, then one thread publishes everything
-  __shared__ unsigned long long s_hr[kScanThreads / kWave], s_he[kScanThreads / kWave];
+  const int f = a.fanout;
+
+  // per row: sampled edges, first appearances (the table still holds the lane's own position).
+  // The three dependent loads (row count -> table slot -> table value) are issued stage by stage
+  // for all of the lane's rows, so that the tile pays the memory latency three times, not 24.
+  int raw[kTileIters], slot[kTileIters];
+  unsigned val[kTileIters];
+#pragma unroll
+  for (int it = 0; it < kTileIters; ++it) {
+    const long long i = row0 + it * kGroups + grp;
+    raw[it] = i < n_rows ? a.row_cnt[i] : 0;
+  }
+#pragma unroll
+  for (int it = 0; it < kTileIters; ++it) {
+    const long long i = row0 + it * kGroups + grp;
+    slot[it] = gl < (raw[it] & kRowCntMask) ? a.tmp_slot[i * f + gl] : -1;
+  }
+#pragma unroll
+  for (int it = 0; it < kTileIters; ++it) val[it] = slot[it] >= 0 ? a.table[slot[it]].val : 0u;
+  unsigned first_bits = 0;
+  unsigned long long hit_rows = 0, hit_edges = 0;
+#pragma unroll
+  for (int it = 0; it < kTileIters; ++it) {
+    const int r = it * kGroups + grp;
+    const int c = raw[it] & kRowCntMask;
+    const unsigned p = (unsigned)((row0 + r) * f + gl);
+    const bool first = slot[it] >= 0 && val[it] == (kTentative | p);
+    const unsigned long long bits = group_bits<G>(__ballot(first), grp_in_wave);
+    if (first) first_bits |= 1u << it;
+    if (gl == 0) {
+      s_c[r] = c;
+      s_f[r] = __popcll(bits);
+      if (raw[it] & kRowHitBit) {
+        hit_rows += 1;
+        hit_edges += (unsigned)c;
+      }
+    }
+  }
+  __syncthreads();
+
+  // scan of the tile's rows, one thread per row
+  const int c_t = tid < TR ? s_c[tid] : 0, f_t = tid < TR ? s_f[tid] : 0;
+  const int inc_c = wave_incl_scan(c_t), inc_f = wave_incl_scan(f_t);
+  if (lane == kWave - 1) {
+    s_wc[wave] = inc_c;
+    s_wf[wave] = inc_f;
+  }
   hit_rows = wave_sum_u64(hit_rows);
   hit_edges = wave_sum_u64(hit_edges);
   if (lane == 0) {
@@ -304,66 +340,115 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_rows(long long* __restric
     s_he[wave] = hit_edges;
   }
   __syncthreads();
+  int off_c = 0, off_f = 0, tot_c = 0, tot_f = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    if (w < wave) {
+      off_c += s_wc[w];
+      off_f += s_wf[w];
+    }
+    tot_c += s_wc[w];
+    tot_f += s_wf[w];
+  }
+  if (tid < TR) {
+    s_c[tid] = off_c + inc_c;        // inclusive edge count within the tile
+    s_f[tid] = off_f + inc_f - f_t;  // exclusive first-appearance count within the tile
+  }
+
+  // publish this tile, then look back over the earlier ones (first wavefront)
+  if (wave == 0) {
+    long long ec = 0;
+    int ef = 0;
+    if (tile == 0) {
+      if (lane == 0)
+        __hip_atomic_store(&a.status[0], st_pack(kStInclusive, (unsigned)tot_f, (unsigned)tot_c), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+      if (lane == 0)
+        __hip_atomic_store(&a.status[tile], st_pack(kStAggregate, (unsigned)tot_f, (unsigned)tot_c), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+      long long j = (long long)tile - 1;
+      unsigned polls = 0;
+      for (;;) {
+        const long long idx = j - lane;
+        unsigned long long st = idx >= 0 ? __hip_atomic_load(&a.status[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                         : st_pack(kStInclusive, 0, 0);
+        while (__ballot((st >> 62) == kStInvalid) != 0ull && polls < kLookbackSpinLimit) {
+          __builtin_amdgcn_s_sleep(1);
+          ++polls;
+          if ((st >> 62) == kStInvalid)
+            st = __hip_atomic_load(&a.status[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        const unsigned long long inc_mask = __ballot((st >> 62) == kStInclusive);
+        const int stop = inc_mask ? (int)__ffsll((long long)inc_mask) - 1 : kWave;  // nearest tile with a prefix
+        long long pc = 0;
+        int pf = 0;
+        if (lane <= stop && (st >> 62) != kStInvalid) {
+          pc = (long long)(st & 0x7FFFFFFFull);
+          pf = (int)((st >> 31) & 0x7FFFFFFFull);
+        }
+        ec += (long long)wave_sum_u64((unsigned long long)pc);
+        ef += (int)wave_sum_u64((unsigned long long)pf);
+        if (inc_mask != 0ull || polls >= kLookbackSpinLimit) break;
+        j -= kWave;
+      }
+      ec = __shfl(ec, 0, kWave);
+      ef = __shfl(ef, 0, kWave);
+      if (lane == 0)
+        __hip_atomic_store(&a.status[tile], st_pack(kStInclusive, (unsigned)(ef + tot_f), (unsigned long long)(ec + tot_c)),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (lane == 0) {
+      s_ec = ec;
+      s_ef = ef;
+    }
+  }
+  __syncthreads();
+  const long long ec = s_ec;
+  const int ef = s_ef;
+  if (tid < TR && row0 + tid < n_rows) a.blk_indptr[row0 + tid + 1] = ec + s_c[tid];
+
+  // first appearances take the next local ids, in (row, slot) order
+  long long new_id[kTileIters], new_u[kTileIters];
+#pragma unroll
+  for (int it = 0; it < kTileIters; ++it) {
+    const int r = it * kGroups + grp;
+    const bool first = (first_bits >> it) & 1u;
+    const unsigned long long bits = group_bits<G>(__ballot(first), grp_in_wave);
+    new_id[it] = first ? n_rows + ef + s_f[r] + __popcll(bits & ((1ull << gl) - 1ull)) : -1;
+  }
+#pragma unroll
+  for (int it = 0; it < kTileIters; ++it)
+    new_u[it] = new_id[it] >= 0 ? a.tmp_u[(row0 + it * kGroups + grp) * f + gl] : 0;
+#pragma unroll
+  for (int it = 0; it < kTileIters; ++it)
+    if (new_id[it] >= 0) {
+      a.nodes[new_id[it]] = new_u[it];
+      a.table[slot[it]].val = (unsigned)new_id[it];
+    }
+
   if (tid == 0) {
-    blk_indptr[0] = 0;
-    counts[hop + 1] = n + carry_f;
-    counts[DCI_MAX_HOPS + 1 + hop] = carry_c;
-    if (stats) {
+    if (tile == 0) a.blk_indptr[0] = 0;
+    const bool last_tile = row0 + TR >= n_rows;
+    if (last_tile) {
+      a.counts[a.hop + 1] = n_rows + ef + tot_f;
+      a.counts[DCI_MAX_HOPS + 1 + a.hop] = ec + tot_c;
+    }
+    if (a.stats) {
       unsigned long long hr = 0, he = 0;
-      for (int w = 0; w < kScanThreads / kWave; ++w) {
+      for (int w = 0; w < kWaves; ++w) {
         hr += s_hr[w];
         he += s_he[w];
       }
-      atomicAdd(&stats[DCI_STAT_EDGES_SAMPLED], (unsigned long long)carry_c);
-      atomicAdd(&stats[DCI_STAT_ADJ_NODE_HITS], hr);
-      atomicAdd(&stats[DCI_STAT_ADJ_NODE_MISSES], (unsigned long long)n - hr);
-      atomicAdd(&stats[DCI_STAT_ADJ_EDGE_HITS], he);
-      atomicAdd(&stats[DCI_STAT_ADJ_EDGE_MISSES], (unsigned long long)carry_c - he);
-      if (last_hop) atomicAdd(&stats[DCI_STAT_INPUT_NODES], (unsigned long long)(n + carry_f));
-    }
-  }
-}
-
-// phase 4a: first appearances take the next local ids, in (row, slot) order
-template <int G>
-__global__ __launch_bounds__(kBlock) void k_assign_new(RowArgs a) {
-  const long long n_rows = a.counts[a.hop];
-  const int lane = lane_id(), gl = lane & (G - 1), grp_in_wave = lane / G;
-  constexpr int kGroups = kBlock / G;
-  const int grp_in_block = (int)threadIdx.x / G;
-  for (long long base = (long long)blockIdx.x * kGroups; base < n_rows; base += (long long)gridDim.x * kGroups) {
-    const long long i = base + grp_in_block;
-    const bool row_ok = i < n_rows;
-    const int c = row_ok ? (a.row_cnt[i] & kRowCntMask) : 0;
-    bool first = false;
-    int p = 0, slot = 0;
-    if (gl < c) {
-      p = (int)(i * a.fanout + gl);
-      slot = a.tmp_slot[p];
-      first = a.table[slot].val == (kTentative | (unsigned)p);
-    }
-    const unsigned long long bits = group_bits<G>(__ballot(first), grp_in_wave);
-    if (first) {
-      const int rank = __popcll(bits & ((1ull << gl) - 1ull));
-      const long long id = n_rows + a.first_base[i] + rank;
-      a.nodes[id] = a.tmp_u[p];
-      a.table[slot].val = (unsigned)id;
-    }
-  }
-}
-
-// phase 4b: every edge reads its source's local id
-template <int G>
-__global__ __launch_bounds__(kBlock) void k_write_src(RowArgs a) {
-  const long long n_rows = a.counts[a.hop];
-  const int gl = lane_id() & (G - 1);
-  constexpr int kGroups = kBlock / G;
-  const int grp_in_block = (int)threadIdx.x / G;
-  for (long long base = (long long)blockIdx.x * kGroups; base < n_rows; base += (long long)gridDim.x * kGroups) {
-    const long long i = base + grp_in_block;
-    if (i < n_rows && gl < (a.row_cnt[i] & kRowCntMask)) {
-      const int p = (int)(i * a.fanout + gl);
-      a.blk_src[a.blk_indptr[i] + gl] = (int)a.table[a.tmp_slot[p]].val;
+      const long long rows_here = n_rows - row0 < TR ? n_rows - row0 : TR;
+      // a handful of atomics per tile (a few hundred tiles at most), each only when non-zero
+      if (tot_c) atomicAdd(&a.stats[DCI_STAT_EDGES_SAMPLED], (unsigned long long)tot_c);
+      if (hr) atomicAdd(&a.stats[DCI_STAT_ADJ_NODE_HITS], hr);
+      if (rows_here - (long long)hr) atomicAdd(&a.stats[DCI_STAT_ADJ_NODE_MISSES], (unsigned long long)rows_here - hr);
+      if (he) atomicAdd(&a.stats[DCI_STAT_ADJ_EDGE_HITS], he);
+      if (tot_c - (long long)he) atomicAdd(&a.stats[DCI_STAT_ADJ_EDGE_MISSES], (unsigned long long)tot_c - he);
+      if (last_tile && a.last_hop)
+        atomicAdd(&a.stats[DCI_STAT_INPUT_NODES], (unsigned long long)(n_rows + ef + tot_f));
     }
   }
 }
@@ -381,13 +466,14 @@ __global__ void k_add_u64(unsigned long long* p, unsigned long long v) { atomicA
 // ---- host side ----------------------------------------------------------------------------------
 
 struct SampleWs {
-  HashEntry* table;
-  uint64_t table_entries;
+  HashEntry* table;        // the table, the tile status words and the tickets are one region,
+  uint64_t table_entries;  // cleared with a single all-ones fill per batch
+  unsigned long long* status[DCI_MAX_HOPS];
+  unsigned* ticket;        // [DCI_MAX_HOPS]
+  size_t clear_bytes;
   long long* tmp_u;
-  int* tmp_slot;
-  int* row_cnt;
-  int* row_first;
-  int* first_base;
+  int* tmp_slot[2];  // by hop parity: a hop's slots are still read while the next hop samples
+  int* row_cnt[2];
 };
 
 static uint64_t table_entries_for(int64_t cap_nodes_last) {
@@ -395,20 +481,40 @@ static uint64_t table_entries_for(int64_t cap_nodes_last) {
   return want < 1024 ? 1024 : want;
 }
 
-static void carve_sample_ws(Arena& ar, const int64_t* cap_nodes, const int64_t* cap_edges, int32_t n_hops,
-                            SampleWs* ws) {
+static int group_for(int fanout) { return fanout <= 8 ? 8 : fanout <= 16 ? 16 : fanout <= 32 ? 32 : 64; }
+
+static int64_t tiles_for(int64_t rows, int fanout) {
+  const int64_t tr = (int64_t)(kBlock / group_for(fanout)) * kTileIters;
+  const int64_t t = (rows + tr - 1) / tr;
+  return t < 1 ? 1 : t;
+}
+
+static void carve_sample_ws(Arena& ar, const int64_t* cap_nodes, const int64_t* cap_edges, const int32_t* fanouts,
+                            int32_t n_hops, SampleWs* ws) {
   int64_t max_edges = 1, max_rows = 1;
+  size_t status_words = 0;
   for (int32_t h = 0; h < n_hops; ++h) {
     if (cap_edges[h] > max_edges) max_edges = cap_edges[h];
     if (cap_nodes[h] > max_rows) max_rows = cap_nodes[h];
+    status_words += (size_t)tiles_for(cap_nodes[h], fanouts[h]);
   }
   ws->table_entries = table_entries_for(cap_nodes[n_hops]);
-  ws->table = ar.take<HashEntry>(ws->table_entries);
+  const size_t table_bytes = ws->table_entries * sizeof(HashEntry);
+  const size_t sync_bytes = align_up(status_words * 8 + DCI_MAX_HOPS * 4, 16);
+  char* region = ar.take<char>(table_bytes + sync_bytes);
+  ws->table = reinterpret_cast<HashEntry*>(region);
+  unsigned long long* st = reinterpret_cast<unsigned long long*>(region + table_bytes);
+  for (int32_t h = 0; h < n_hops; ++h) {
+    ws->status[h] = st;
+    st += tiles_for(cap_nodes[h], fanouts[h]);
+  }
+  ws->ticket = reinterpret_cast<unsigned*>(st);
+  ws->clear_bytes = table_bytes + sync_bytes;
   ws->tmp_u = ar.take<long long>((size_t)max_edges);
-  ws->tmp_slot = ar.take<int>((size_t)max_edges);
-  ws->row_cnt = ar.take<int>((size_t)max_rows);
-  ws->row_first = ar.take<int>((size_t)max_rows);
-  ws->first_base = ar.take<int>((size_t)max_rows);
+  for (int k = 0; k < 2; ++k) {
+    ws->tmp_slot[k] = ar.take<int>((size_t)max_edges);
+    ws->row_cnt[k] = ar.take<int>((size_t)max_rows);
+  }
 }
 
 static void carve_blocks(Arena& ar, const int64_t* cap_nodes, const int64_t* cap_edges, int32_t n_hops,
@@ -435,43 +541,34 @@ static int grid_for_rows(const dci_ctx* ctx, int64_t rows, int groups_per_block)
 }
 
 template <int G>
-static int32_t launch_hop(dci_ctx* ctx, const HopArgs& ha, const RowArgs& ra, bool count, int64_t cap_rows,
-                          long long* counts, long long* blk_indptr, int* first_base_out, unsigned long long* stats,
-                          int last_hop) {
+static int32_t launch_hop(dci_ctx* ctx, const HopArgs& ha, const RelabelArgs& ra, bool count, int64_t cap_rows) {
   const int grid = grid_for_rows(ctx, cap_rows, kBlock / G);
   {
     Timed t(ctx, DCI_K_SAMPLE);
-    if (count)
-      hipLaunchKernelGGL((k_sample_hop<G, true>), dim3(grid), dim3(kBlock), 0, ctx->stream, ha);
-    else
-      hipLaunchKernelGGL((k_sample_hop<G, false>), dim3(grid), dim3(kBlock), 0, ctx->stream, ha);
+    if (ha.hop == 0) {
+      if (count)
+        hipLaunchKernelGGL((k_sample_hop<G, true, true>), dim3(grid), dim3(kBlock), 0, ctx->stream, ha);
+      else
+        hipLaunchKernelGGL((k_sample_hop<G, false, true>), dim3(grid), dim3(kBlock), 0, ctx->stream, ha);
+    } else {
+      if (count)
+        hipLaunchKernelGGL((k_sample_hop<G, true, false>), dim3(grid), dim3(kBlock), 0, ctx->stream, ha);
+      else
+        hipLaunchKernelGGL((k_sample_hop<G, false, false>), dim3(grid), dim3(kBlock), 0, ctx->stream, ha);
+    }
   }
   DCI_LAUNCH_CHECK(ctx);
   {
-    Timed t(ctx, DCI_K_ROW_FIRST);
-    hipLaunchKernelGGL((k_row_first<G>), dim3(grid), dim3(kBlock), 0, ctx->stream, ra);
-  }
-  DCI_LAUNCH_CHECK(ctx);
-  {
-    Timed t(ctx, DCI_K_SCAN);
-    hipLaunchKernelGGL(k_scan_rows, dim3(1), dim3(kScanThreads), 0, ctx->stream, counts, ra.hop, ra.row_cnt,
-                       (const int*)ra.row_first, blk_indptr, first_base_out, stats, last_hop);
-  }
-  DCI_LAUNCH_CHECK(ctx);
-  {
-    Timed t(ctx, DCI_K_ASSIGN);
-    hipLaunchKernelGGL((k_assign_new<G>), dim3(grid), dim3(kBlock), 0, ctx->stream, ra);
-  }
-  DCI_LAUNCH_CHECK(ctx);
-  {
-    Timed t(ctx, DCI_K_WRITE_SRC);
-    hipLaunchKernelGGL((k_write_src<G>), dim3(grid), dim3(kBlock), 0, ctx->stream, ra);
+    Timed t(ctx, DCI_K_RELABEL);
+    hipLaunchKernelGGL((k_relabel_hop<G>), dim3((unsigned)tiles_for(cap_rows, ha.fanout)), dim3(kBlock), 0, ctx->stream,
+                       ra);
   }
   DCI_LAUNCH_CHECK(ctx);
   return DCI_OK;
 }
 
-// Enqueues the sampling of one batch.  `count_*` non-null turns on the pre-sampling counters.
+// Enqueues the sampling of one batch: one clear, two kernels per hop, one closing kernel.
+// `adj_count` non-null turns on the pre-sampling counters.
 static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* cache, const int64_t* seeds,
                             int64_t n_seeds, uint64_t batch_index, const int32_t* fanouts, int32_t n_hops,
                             uint64_t rng_seed, const dci_blocks* out, const SampleWs& ws, uint64_t* stats,
@@ -479,7 +576,7 @@ static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* c
   int rc;
   {
     Timed t(ctx, DCI_K_TABLE_CLEAR);
-    rc = fill_bytes(ctx, ws.table, ws.table_entries * sizeof(HashEntry), 0xFFFFFFFFu);
+    rc = fill_bytes(ctx, ws.table, ws.clear_bytes, 0xFFFFFFFFu);
   }
   if (rc != DCI_OK) return rc;
   const unsigned mask = (unsigned)(ws.table_entries - 1);
@@ -488,17 +585,11 @@ static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* c
   const int shift = 64 - log2n;
   long long* counts = reinterpret_cast<long long*>(out->counts);
   long long* nodes = reinterpret_cast<long long*>(out->nodes);
-  {
-    int grid = grid_for_rows(ctx, n_seeds, kBlock);
-    Timed t(ctx, DCI_K_INIT);
-    hipLaunchKernelGGL(k_init_batch, dim3(grid), dim3(kBlock), 0, ctx->stream,
-                       reinterpret_cast<const long long*>(seeds), (long long)n_seeds, nodes, counts, ws.table, mask,
-                       shift);
-    DCI_LAUNCH_CHECK(ctx);
-  }
   const bool count = adj_count != nullptr;
   for (int32_t h = 0; h < n_hops; ++h) {
     HopArgs ha;
+    ha.seeds = reinterpret_cast<const long long*>(seeds);
+    ha.n_seeds = n_seeds;
     ha.nodes = nodes;
     ha.counts = counts;
     ha.hop = h;
@@ -512,40 +603,53 @@ static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* c
     ha.k1 = (unsigned)(rng_seed >> 32);
     ha.batch = (unsigned)batch_index;
     ha.tmp_u = ws.tmp_u;
-    ha.tmp_slot = ws.tmp_slot;
-    ha.row_cnt = ws.row_cnt;
+    ha.tmp_slot = ws.tmp_slot[h & 1];
+    ha.row_cnt = ws.row_cnt[h & 1];
     ha.table = ws.table;
     ha.mask = mask;
     ha.shift = shift;
     ha.adj_count = adj_count;
     ha.edge_count = edge_count;
-    RowArgs ra;
+    ha.prev_fanout = h > 0 ? fanouts[h - 1] : 1;
+    ha.prev_row_cnt = ws.row_cnt[(h + 1) & 1];
+    ha.prev_tmp_slot = ws.tmp_slot[(h + 1) & 1];
+    ha.prev_blk_indptr = h > 0 ? reinterpret_cast<const long long*>(out->blk_indptr[h - 1]) : nullptr;
+    ha.prev_blk_src = h > 0 ? out->blk_src[h - 1] : nullptr;
+    RelabelArgs ra;
     ra.counts = counts;
     ra.hop = h;
     ra.fanout = fanouts[h];
-    ra.row_cnt = ws.row_cnt;
-    ra.row_first = ws.row_first;
-    ra.first_base = ws.first_base;
-    ra.blk_indptr = reinterpret_cast<const long long*>(out->blk_indptr[h]);
+    ra.row_cnt = ws.row_cnt[h & 1];
     ra.tmp_u = ws.tmp_u;
-    ra.tmp_slot = ws.tmp_slot;
+    ra.tmp_slot = ws.tmp_slot[h & 1];
     ra.table = ws.table;
     ra.nodes = nodes;
-    ra.blk_src = out->blk_src[h];
-    long long* bi = reinterpret_cast<long long*>(out->blk_indptr[h]);
-    unsigned long long* st = reinterpret_cast<unsigned long long*>(stats);
-    const int last = h == n_hops - 1;
-    const int f = fanouts[h];
-    if (f <= 8)
-      rc = launch_hop<8>(ctx, ha, ra, count, out->cap_rows[h], counts, bi, ws.first_base, st, last);
-    else if (f <= 16)
-      rc = launch_hop<16>(ctx, ha, ra, count, out->cap_rows[h], counts, bi, ws.first_base, st, last);
-    else if (f <= 32)
-      rc = launch_hop<32>(ctx, ha, ra, count, out->cap_rows[h], counts, bi, ws.first_base, st, last);
-    else
-      rc = launch_hop<64>(ctx, ha, ra, count, out->cap_rows[h], counts, bi, ws.first_base, st, last);
+    ra.blk_indptr = reinterpret_cast<long long*>(out->blk_indptr[h]);
+    ra.status = ws.status[h];
+    ra.ticket = ws.ticket + h;
+    ra.stats = reinterpret_cast<unsigned long long*>(stats);
+    ra.last_hop = h == n_hops - 1;
+    // launch shapes follow the frontier bound of this call; with zero seeds one workgroup still
+    // runs so that the (empty) sizes get written
+    const int64_t rows = out->cap_rows[h];
+    switch (group_for(fanouts[h])) {
+      case 8: rc = launch_hop<8>(ctx, ha, ra, count, rows); break;
+      case 16: rc = launch_hop<16>(ctx, ha, ra, count, rows); break;
+      case 32: rc = launch_hop<32>(ctx, ha, ra, count, rows); break;
+      default: rc = launch_hop<64>(ctx, ha, ra, count, rows); break;
+    }
     if (rc != DCI_OK) return rc;
   }
+  {
+    const int32_t h = n_hops - 1;
+    const int64_t positions = out->cap_rows[h] * fanouts[h];
+    Timed t(ctx, DCI_K_WRITE_SRC);
+    hipLaunchKernelGGL(k_write_src, dim3(grid_for_rows(ctx, positions, kBlock)), dim3(kBlock), 0, ctx->stream,
+                       (const long long*)counts, h, fanouts[h], (const int*)ws.row_cnt[h & 1],
+                       (const int*)ws.tmp_slot[h & 1], reinterpret_cast<const long long*>(out->blk_indptr[h]),
+                       (const HashEntry*)ws.table, out->blk_src[h]);
+  }
+  DCI_LAUNCH_CHECK(ctx);
   if (feat_count) {
     int grid = grid_for_rows(ctx, out->cap_nodes, kBlock);
     Timed t(ctx, DCI_K_COUNT_NODES);
@@ -589,7 +693,7 @@ size_t dci_sample_workspace_bytes(int64_t num_nodes, int64_t n_seeds, const int3
   Arena ar(nullptr, 0);
   SampleWs ws;
   dci_blocks b;
-  carve_sample_ws(ar, cap_nodes, cap_edges, n_hops, &ws);
+  carve_sample_ws(ar, cap_nodes, cap_edges, fanouts, n_hops, &ws);
   carve_blocks(ar, cap_nodes, cap_edges, n_hops, &b);
   (void)ar.take<char>(256 * 1024);  // room for the gather statistics of the pre-sampling pass
   return ar.off;
@@ -619,7 +723,7 @@ int32_t dci_sample_khop(dci_ctx* ctx, const dci_graph* graph, const dci_cache* c
   }
   Arena ar(ctx->ws, ctx->ws_bytes);
   SampleWs ws;
-  carve_sample_ws(ar, cap_nodes, cap_edges, n_hops, &ws);
+  carve_sample_ws(ar, cap_nodes, cap_edges, fanouts, n_hops, &ws);
   if (!ar.ok())
     return fail(ctx, DCI_ERR_CAPACITY, "workspace holds %zu bytes, sampling needs %zu", ctx->ws_bytes, ar.off);
   // launch shapes follow the bounds of this call, not the (possibly larger) capacities
@@ -655,7 +759,7 @@ int32_t dci_presample_count(dci_ctx* ctx, const dci_graph* graph, const dci_cach
   Arena ar(ctx->ws, ctx->ws_bytes);
   SampleWs ws;
   dci_blocks blk;
-  carve_sample_ws(ar, cap_nodes, cap_edges, n_hops, &ws);
+  carve_sample_ws(ar, cap_nodes, cap_edges, fanouts, n_hops, &ws);
   carve_blocks(ar, cap_nodes, cap_edges, n_hops, &blk);
   void* gather_partials = ar.take<char>(gather_partials_bytes(ctx));
   if (!ar.ok())
