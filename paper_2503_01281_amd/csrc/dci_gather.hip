@@ -3,29 +3,29 @@
 // matrix (zero-copy over the host link) otherwise.
 //
 // The copy is bandwidth bound.  A row is handled by a group of lanes (a whole wavefront for
-// rows of 64 or more vector chunks, a fraction for narrow rows) with 16-, 8- or 4-byte
-// accesses depending on the alignment F allows, consecutive lanes on consecutive chunks, four
-// loads in flight per lane before the first store.
+// rows of 64 or more 16-byte chunks, a fraction for narrow rows); consecutive lanes move
+// consecutive 16-byte chunks, up to four loads in flight per lane before the first store, and the
+// id / remap lookups of the next two rows are issued while the current row is copied.  Rows need
+// only 4-byte alignment: gfx950 global memory takes under-aligned 16-byte accesses, and the
+// F % 4 trailing floats are moved one per lane.
 #include "dci_internal.h"
 
 namespace dci {
 
 constexpr int kGatherBlock = 256;
+constexpr int kGatherBlocksPerCu = 16;
+
+typedef float4 __attribute__((aligned(4))) float4_u;  // 16-byte access at 4-byte alignment
+typedef float2 __attribute__((aligned(4))) float2_u;
 
 template <int V>
-struct VecT;
+struct GVec;
 template <>
-struct VecT<4> {
-  typedef float4 type;
-};
+struct GVec<4> { typedef float4 reg; typedef float4_u mem; };
 template <>
-struct VecT<2> {
-  typedef float2 type;
-};
+struct GVec<2> { typedef float2 reg; typedef float2_u mem; };
 template <>
-struct VecT<1> {
-  typedef float type;
-};
+struct GVec<1> { typedef float reg; typedef float mem; };
 
 template <int V>
 __global__ __launch_bounds__(kGatherBlock) void k_gather(const long long* __restrict__ ids, long long n_max,
@@ -35,39 +35,52 @@ __global__ __launch_bounds__(kGatherBlock) void k_gather(const long long* __rest
                                                          const float* __restrict__ feat, int F, int lpr_log2,
                                                          float* __restrict__ out,
                                                          unsigned long long* __restrict__ partials) {
-  typedef typename VecT<V>::type vec_t;
   long long n = n_dev ? *n_dev : n_max;
   if (n > n_max) n = n_max;
-  const int chunks = F / V;
-  const int lpr = 1 << lpr_log2;                 // lanes per row
+  typedef typename GVec<V>::reg reg_t;
+  typedef typename GVec<V>::mem mem_t;
+  const int chunks = F / V, tail = F % V;
+  const int lpr = 1 << lpr_log2;  // lanes per row
   const int rows_per_block = kGatherBlock >> lpr_log2;
   const int sub = (int)threadIdx.x >> lpr_log2;  // row within the block's slice
   const int cl = (int)threadIdx.x & (lpr - 1);   // first chunk of this lane
+  const long long stride = (long long)gridDim.x * rows_per_block;
   unsigned long long hits = 0, misses = 0;
-  for (long long base = (long long)blockIdx.x * rows_per_block; base < n; base += (long long)gridDim.x * rows_per_block) {
-    const long long i = base + sub;
-    if (i < n) {
-      const long long id = ids[i];
-      const int r = remap ? remap[id] : -1;
-      const vec_t* src = reinterpret_cast<const vec_t*>(r >= 0 ? cache + (long long)r * F : feat + id * F);
-      vec_t* dst = reinterpret_cast<vec_t*>(out + i * F);
-      if (cl == 0) {
-        if (r >= 0) ++hits; else ++misses;
-      }
-      int c = cl;
-      for (; c + 3 * lpr < chunks; c += 4 * lpr) {
-        const vec_t v0 = src[c], v1 = src[c + lpr], v2 = src[c + 2 * lpr], v3 = src[c + 3 * lpr];
-        dst[c] = v0;
-        dst[c + lpr] = v1;
-        dst[c + 2 * lpr] = v2;
-        dst[c + 3 * lpr] = v3;
-      }
-      for (; c < chunks; c += lpr) dst[c] = src[c];
+
+  long long i = (long long)blockIdx.x * rows_per_block + sub;
+  long long id = i < n ? ids[i] : 0;
+  int r = (i < n && remap) ? remap[id] : -1;
+  long long i2 = i + stride;
+  long long id2 = i2 < n ? ids[i2] : 0;
+  while (i < n) {
+    // look-ups of the following rows go out before this row's copy
+    const int r2 = (i2 < n && remap) ? remap[id2] : -1;
+    const long long i3 = i2 + stride;
+    const long long id3 = i3 < n ? ids[i3] : 0;
+
+    const float* src = r >= 0 ? cache + (long long)r * F : feat + id * F;
+    float* dst = out + i * F;
+    if (cl == 0) {
+      if (r >= 0) ++hits; else ++misses;
     }
+    for (int c0 = cl; c0 < chunks; c0 += 4 * lpr) {
+      reg_t v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (c0 + u * lpr < chunks) v[u] = reinterpret_cast<const mem_t*>(src)[c0 + u * lpr];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (c0 + u * lpr < chunks) reinterpret_cast<mem_t*>(dst)[c0 + u * lpr] = v[u];
+    }
+    if (cl < tail) dst[V * chunks + cl] = src[V * chunks + cl];
+
+    i = i2; id = id2; r = r2;
+    i2 = i3; id2 = id3;
   }
   if (partials) {
-    // Hit / miss totals leave the kernel as one pair per workgroup; thousands of atomics on
-    // one counter would serialise in L2 and cost more than the copy itself.
+    // Hit / miss totals leave the kernel as one pair per workgroup and are folded by a second,
+    // tiny kernel: thousands of atomics on one counter serialise in L2 for longer than the copy
+    // takes (measured: +30 us for 4096 workgroups).
     __shared__ unsigned long long s_h[kGatherBlock / kWave], s_m[kGatherBlock / kWave];
     hits = wave_sum_u64(hits);
     misses = wave_sum_u64(misses);
@@ -114,47 +127,49 @@ __global__ __launch_bounds__(kGatherBlock) void k_fold_gather_stats(const unsign
   }
 }
 
-size_t gather_partials_bytes(const dci_ctx* ctx) { return (size_t)ctx->num_cus * 16 * 2 * sizeof(unsigned long long); }
+size_t gather_partials_bytes(const dci_ctx* ctx) {
+  return (size_t)ctx->num_cus * kGatherBlocksPerCu * 2 * sizeof(unsigned long long);
+}
 
 int32_t gather_launch(dci_ctx* ctx, const dci_graph* g, const dci_cache* cache, const int64_t* ids, int64_t n_max,
                       const int64_t* n_dev, float* out, uint64_t* stats, void* partials_buf) {
   const int F = g->feat_dim;
   const float* fcache = cache ? cache->feat_cache : nullptr;
   const int* remap = cache ? cache->feat_remap : nullptr;
-  // widest access that every row start (feature matrix, cache and output) is aligned for
-  auto aligned = [](const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; };
+  // 16-byte chunks when rows start 16-byte aligned; otherwise 8-byte chunks (under-aligned 16-byte
+  // accesses work but measured slower than aligned 8-byte ones)
+  auto aligned = [](const void* p, size_t a) { return p == nullptr || (reinterpret_cast<uintptr_t>(p) % a) == 0; };
   int V = 1;
-  if (F % 4 == 0 && aligned(g->feat, 16) && aligned(out, 16) && (!fcache || aligned(fcache, 16)))
-    V = 4;
-  else if (F % 2 == 0 && aligned(g->feat, 8) && aligned(out, 8) && (!fcache || aligned(fcache, 8)))
-    V = 2;
+  if (F % 4 == 0 && aligned(g->feat, 16) && aligned(out, 16) && aligned(fcache, 16)) V = 4;
+  else if (F % 2 == 0 && aligned(g->feat, 8) && aligned(out, 8) && aligned(fcache, 8)) V = 2;
   const int chunks = F / V;
   int lpr_log2 = 0;
   while ((1 << lpr_log2) < chunks && lpr_log2 < 6) ++lpr_log2;
   const int rows_per_block = kGatherBlock >> lpr_log2;
   int64_t blocks = (n_max + rows_per_block - 1) / rows_per_block;
-  const int64_t cap = (int64_t)ctx->num_cus * 16;
+  const int64_t cap = (int64_t)ctx->num_cus * kGatherBlocksPerCu;
   if (blocks > cap) blocks = cap;
   if (blocks < 1) blocks = 1;
-  const long long* ids_ = reinterpret_cast<const long long*>(ids);
-  const long long* nd_ = reinterpret_cast<const long long*>(n_dev);
-  unsigned long long* st = stats ? reinterpret_cast<unsigned long long*>(partials_buf) : nullptr;
   {
-  Timed timed(ctx, DCI_K_GATHER);
-  if (V == 4)
-    hipLaunchKernelGGL((k_gather<4>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_, (long long)n_max,
-                       nd_, remap, fcache, g->feat, F, lpr_log2, out, st);
-  else if (V == 2)
-    hipLaunchKernelGGL((k_gather<2>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_, (long long)n_max,
-                       nd_, remap, fcache, g->feat, F, lpr_log2, out, st);
-  else
-    hipLaunchKernelGGL((k_gather<1>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_, (long long)n_max,
-                       nd_, remap, fcache, g->feat, F, lpr_log2, out, st);
+    Timed timed(ctx, DCI_K_GATHER);
+    const long long* ids_ = reinterpret_cast<const long long*>(ids);
+    const long long* nd_ = reinterpret_cast<const long long*>(n_dev);
+    unsigned long long* st = stats ? reinterpret_cast<unsigned long long*>(partials_buf) : nullptr;
+    if (V == 4)
+      hipLaunchKernelGGL((k_gather<4>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_, (long long)n_max,
+                         nd_, remap, fcache, g->feat, F, lpr_log2, out, st);
+    else if (V == 2)
+      hipLaunchKernelGGL((k_gather<2>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_, (long long)n_max,
+                         nd_, remap, fcache, g->feat, F, lpr_log2, out, st);
+    else
+      hipLaunchKernelGGL((k_gather<1>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_, (long long)n_max,
+                         nd_, remap, fcache, g->feat, F, lpr_log2, out, st);
   }
   DCI_LAUNCH_CHECK(ctx);
-  if (st) {
+  if (stats) {
     hipLaunchKernelGGL(k_fold_gather_stats, dim3(1), dim3(kGatherBlock), 0, ctx->stream,
-                       (const unsigned long long*)st, (int)blocks, reinterpret_cast<unsigned long long*>(stats));
+                       reinterpret_cast<const unsigned long long*>(partials_buf), (int)blocks,
+                       reinterpret_cast<unsigned long long*>(stats));
     DCI_LAUNCH_CHECK(ctx);
   }
   return DCI_OK;
@@ -172,6 +187,9 @@ extern "C" int32_t dci_gather_features(dci_ctx* ctx, const dci_graph* graph, con
     return dci::fail(ctx, DCI_ERR_INVALID_ARG, "node_ids / out: null or negative count");
   if (cache && (!cache->feat_remap || (cache->feat_rows > 0 && !cache->feat_cache)))
     return dci::fail(ctx, DCI_ERR_INVALID_ARG, "cache: null feature arrays");
+  if ((reinterpret_cast<uintptr_t>(graph->feat) | reinterpret_cast<uintptr_t>(out) |
+       (cache ? reinterpret_cast<uintptr_t>(cache->feat_cache) : 0)) & 3)
+    return dci::fail(ctx, DCI_ERR_INVALID_ARG, "feature arrays must be 4-byte aligned");
   if (n_max == 0) return DCI_OK;
   void* partials = nullptr;
   if (stats) {

@@ -21,18 +21,22 @@
 
 namespace dci {
 
-struct HashEntry {
-  long long key;
-  unsigned int val;
-  unsigned int pad;
-};
-static_assert(sizeof(HashEntry) == 16, "hash entry must be 16 bytes");
+// One 64-bit word per table entry: node id in the high half, value in the low half, all ones =
+// empty.  Node ids are below 2^31, so a real entry is always smaller than the empty word.
+typedef unsigned long long HashEntry;
 
 constexpr unsigned int kTentative = 0x80000000u;
-constexpr long long kEmptyKey = -1;
+constexpr HashEntry kEmptyEntry = ~0ull;
 constexpr int kBlock = 256;
 constexpr int kRowHitBit = 1 << 30;   // row_cnt[i] = sampled edges of row i | this bit if the list was cached
 constexpr int kRowCntMask = kRowHitBit - 1;
+
+__device__ __forceinline__ unsigned entry_val(const HashEntry* table, unsigned slot) {
+  return reinterpret_cast<const unsigned*>(table)[2 * (size_t)slot];  // low half (little endian)
+}
+__device__ __forceinline__ void entry_set_val(HashEntry* table, unsigned slot, unsigned v) {
+  reinterpret_cast<unsigned*>(table)[2 * (size_t)slot] = v;
+}
 
 // ---- Philox4x32-10 (Salmon et al., SC'11), counter-based ---------------------------------
 __device__ __forceinline__ unsigned long long philox_u64(unsigned c0, unsigned c1, unsigned c2, unsigned c3,
@@ -61,24 +65,27 @@ __device__ __forceinline__ unsigned long long uniform_below(unsigned k0, unsigne
 }
 
 // ---- hash table -----------------------------------------------------------------------------
-__device__ __forceinline__ unsigned table_find_or_insert(HashEntry* table, unsigned mask, int shift, long long u) {
+// Finds or creates the entry of node u (open addressing, linear probing) and lowers its value to
+// v if v is smaller; returns the slot.  For an entry that already holds u, key and value move as
+// one word, so a single 64-bit atomic minimum does it; an empty slot is claimed by compare-and-
+// swap.  Values only decrease and keys never change, so a stale read costs a redundant atomic
+// at most.
+__device__ __forceinline__ unsigned table_insert_min(HashEntry* table, unsigned mask, int shift, long long u,
+                                                     unsigned v) {
   unsigned slot = (unsigned)(((unsigned long long)u * 0x9E3779B97F4A7C15ull) >> shift) & mask;
+  const HashEntry mine = ((HashEntry)u << 32) | v;
   for (;;) {
-    long long k = __atomic_load_n(&table[slot].key, __ATOMIC_RELAXED);
-    if (k == u) return slot;
-    if (k == kEmptyKey) {
-      const unsigned long long prev =
-          atomicCAS(reinterpret_cast<unsigned long long*>(&table[slot].key), (unsigned long long)kEmptyKey,
-                    (unsigned long long)u);
-      if (prev == (unsigned long long)kEmptyKey || prev == (unsigned long long)u) return slot;
+    HashEntry w = __atomic_load_n(&table[slot], __ATOMIC_RELAXED);
+    if (w == kEmptyEntry) {
+      w = atomicCAS(&table[slot], kEmptyEntry, mine);
+      if (w == kEmptyEntry) return slot;
+    }
+    if ((long long)(w >> 32) == u) {
+      if ((unsigned)w > v) atomicMin(&table[slot], mine);
+      return slot;
     }
     slot = (slot + 1) & mask;
   }
-}
-
-__device__ __forceinline__ void table_min(HashEntry* table, unsigned slot, unsigned v) {
-  // The value only ever decreases, so a stale (larger) read costs one redundant atomic at most.
-  if (__atomic_load_n(&table[slot].val, __ATOMIC_RELAXED) > v) atomicMin(&table[slot].val, v);
 }
 
 template <int G>
@@ -116,6 +123,7 @@ struct HopArgs {
   const int* prev_tmp_slot;
   const long long* prev_blk_indptr;
   int* prev_blk_src;
+  int n_write_blocks;  // leading workgroups that only do the previous hop's edge ids
 };
 
 // blk_src of a finished hop: every edge reads the (by now final) local id of its source.
@@ -123,20 +131,25 @@ struct HopArgs {
 __device__ __forceinline__ void write_block_sources(long long n_rows, int fanout, const int* __restrict__ row_cnt,
                                                     const int* __restrict__ tmp_slot,
                                                     const long long* __restrict__ blk_indptr,
-                                                    const HashEntry* table, int* __restrict__ blk_src) {
+                                                    const HashEntry* table, int* __restrict__ blk_src,
+                                                    int block, int n_blocks) {
   const long long total = n_rows * fanout;
-  for (long long q = blockIdx.x * (long long)blockDim.x + threadIdx.x; q < total; q += (long long)gridDim.x * blockDim.x) {
+  for (long long q = block * (long long)blockDim.x + threadIdx.x; q < total; q += (long long)n_blocks * blockDim.x) {
     const long long i = q / fanout;
     const int s = (int)(q - i * fanout);
-    if (s < (row_cnt[i] & kRowCntMask)) blk_src[blk_indptr[i] + s] = (int)table[tmp_slot[q]].val;
+    if (s < (row_cnt[i] & kRowCntMask)) blk_src[blk_indptr[i] + s] = (int)entry_val(table, (unsigned)tmp_slot[q]);
   }
 }
 
+// Closing kernel of a batch: the last hop's edge ids, and the batch sizes for the host.
 __global__ __launch_bounds__(kBlock) void k_write_src(const long long* __restrict__ counts, int hop, int fanout,
                                                       const int* row_cnt, const int* tmp_slot,
                                                       const long long* blk_indptr, const HashEntry* table,
-                                                      int* blk_src) {
-  write_block_sources(counts[hop], fanout, row_cnt, tmp_slot, blk_indptr, table, blk_src);
+                                                      int* blk_src, long long* counts_host) {
+  write_block_sources(counts[hop], fanout, row_cnt, tmp_slot, blk_indptr, table, blk_src, (int)blockIdx.x,
+                      (int)gridDim.x);
+  if (counts_host && blockIdx.x == 0 && threadIdx.x < 2 * DCI_MAX_HOPS + 1)
+    counts_host[threadIdx.x] = counts[threadIdx.x];  // pinned host memory, visible once the stream is idle
 }
 
 // Phase 1 of a hop.  INIT (hop 0): row i first turns seed i into frontier entry i (final local id
@@ -148,10 +161,14 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
   const long long n_rows = INIT ? a.n_seeds : a.counts[a.hop];
   if (INIT) {
     if (blockIdx.x == 0 && threadIdx.x == 0) a.counts[0] = a.n_seeds;
-  } else {
+  } else if ((int)blockIdx.x < a.n_write_blocks) {
+    // the first few workgroups finish the previous hop while the others sample this one
     write_block_sources(a.counts[a.hop - 1], a.prev_fanout, a.prev_row_cnt, a.prev_tmp_slot, a.prev_blk_indptr,
-                        a.table, a.prev_blk_src);
+                        a.table, a.prev_blk_src, (int)blockIdx.x, a.n_write_blocks);
+    return;
   }
+  const int block = (int)blockIdx.x - (INIT ? 0 : a.n_write_blocks);
+  const int n_blocks = (int)gridDim.x - (INIT ? 0 : a.n_write_blocks);
   const int lane = lane_id();
   const int gl = lane & (G - 1);
   const int grp_in_wave = lane / G;
@@ -159,7 +176,7 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
   const int grp_in_block = (int)threadIdx.x / G;
   const int f = a.fanout;
 
-  for (long long base = (long long)blockIdx.x * kGroups; base < n_rows; base += (long long)gridDim.x * kGroups) {
+  for (long long base = (long long)block * kGroups; base < n_rows; base += (long long)n_blocks * kGroups) {
     const long long i = base + grp_in_block;
     const bool row_ok = i < n_rows;
     long long v = 0, start = 0, d = 0;
@@ -170,7 +187,7 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
         v = a.seeds[i];
         if (gl == 0) {
           a.nodes[i] = v;
-          table_min(a.table, table_find_or_insert(a.table, a.mask, a.shift, v), (unsigned)i);
+          (void)table_insert_min(a.table, a.mask, a.shift, v, (unsigned)i);
         }
       } else {
         v = a.nodes[i];
@@ -208,8 +225,7 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
     if (active) {
       const long long u = list[start + pos];
       const int p = (int)(i * f + gl);
-      const unsigned slot = table_find_or_insert(a.table, a.mask, a.shift, u);
-      table_min(a.table, slot, kTentative | (unsigned)p);
+      const unsigned slot = table_insert_min(a.table, a.mask, a.shift, u, kTentative | (unsigned)p);
       a.tmp_u[p] = u;
       a.tmp_slot[p] = (int)slot;
       if (COUNT && a.edge_count) {
@@ -304,7 +320,7 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
     slot[it] = gl < (raw[it] & kRowCntMask) ? a.tmp_slot[i * f + gl] : -1;
   }
 #pragma unroll
-  for (int it = 0; it < kTileIters; ++it) val[it] = slot[it] >= 0 ? a.table[slot[it]].val : 0u;
+  for (int it = 0; it < kTileIters; ++it) val[it] = slot[it] >= 0 ? entry_val(a.table, (unsigned)slot[it]) : 0u;
   unsigned first_bits = 0;
   unsigned long long hit_rows = 0, hit_edges = 0;
 #pragma unroll
@@ -424,7 +440,7 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
   for (int it = 0; it < kTileIters; ++it)
     if (new_id[it] >= 0) {
       a.nodes[new_id[it]] = new_u[it];
-      a.table[slot[it]].val = (unsigned)new_id[it];
+      entry_set_val(a.table, (unsigned)slot[it], (unsigned)new_id[it]);
     }
 
   if (tid == 0) {
@@ -542,7 +558,7 @@ static int grid_for_rows(const dci_ctx* ctx, int64_t rows, int groups_per_block)
 
 template <int G>
 static int32_t launch_hop(dci_ctx* ctx, const HopArgs& ha, const RelabelArgs& ra, bool count, int64_t cap_rows) {
-  const int grid = grid_for_rows(ctx, cap_rows, kBlock / G);
+  const int grid = grid_for_rows(ctx, cap_rows, kBlock / G) + (ha.hop > 0 ? ha.n_write_blocks : 0);
   {
     Timed t(ctx, DCI_K_SAMPLE);
     if (ha.hop == 0) {
@@ -615,6 +631,7 @@ static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* c
     ha.prev_tmp_slot = ws.tmp_slot[(h + 1) & 1];
     ha.prev_blk_indptr = h > 0 ? reinterpret_cast<const long long*>(out->blk_indptr[h - 1]) : nullptr;
     ha.prev_blk_src = h > 0 ? out->blk_src[h - 1] : nullptr;
+    ha.n_write_blocks = h > 0 ? grid_for_rows(ctx, out->cap_rows[h - 1] * fanouts[h - 1], kBlock * 4) : 0;
     RelabelArgs ra;
     ra.counts = counts;
     ra.hop = h;
@@ -647,7 +664,7 @@ static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* c
     hipLaunchKernelGGL(k_write_src, dim3(grid_for_rows(ctx, positions, kBlock)), dim3(kBlock), 0, ctx->stream,
                        (const long long*)counts, h, fanouts[h], (const int*)ws.row_cnt[h & 1],
                        (const int*)ws.tmp_slot[h & 1], reinterpret_cast<const long long*>(out->blk_indptr[h]),
-                       (const HashEntry*)ws.table, out->blk_src[h]);
+                       (const HashEntry*)ws.table, out->blk_src[h], reinterpret_cast<long long*>(out->counts_host));
   }
   DCI_LAUNCH_CHECK(ctx);
   if (feat_count) {
@@ -732,11 +749,7 @@ int32_t dci_sample_khop(dci_ctx* ctx, const dci_graph* graph, const dci_cache* c
   view.cap_nodes = cap_nodes[n_hops];
   rc = sample_batch(ctx, graph, cache, seeds, n_seeds, batch_index, fanouts, n_hops, rng_seed, &view, ws, stats,
                     nullptr, nullptr, nullptr);
-  if (rc != DCI_OK) return rc;
-  if (out->counts_host)
-    DCI_HIP(ctx, hipMemcpyAsync(out->counts_host, out->counts, sizeof(int64_t) * (2 * DCI_MAX_HOPS + 1),
-                                hipMemcpyDeviceToHost, ctx->stream));
-  return DCI_OK;
+  return rc;
 }
 
 int32_t dci_presample_count(dci_ctx* ctx, const dci_graph* graph, const dci_cache* cache, const int64_t* seeds,
