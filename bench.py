@@ -17,6 +17,7 @@ bandwidth, hit rates and per-kernel times ride along, plus
 from __future__ import annotations
 
 import argparse
+import ctypes as C
 import json
 import os
 import sys
@@ -43,6 +44,9 @@ def main() -> int:
     ap.add_argument("--no-cache", action="store_true", help="run the miss path only (no dual cache)")
     ap.add_argument("--feat-policy", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="run sample -> gather -> forward of each batch back to back on one stream; by default the "
+                         "sampling of batch b+1 runs on a second stream while batch b is gathered and multiplied")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region run one device-to-device copy of 1 GiB (a kernel of known "
                          "traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
@@ -107,33 +111,78 @@ def main() -> int:
 
     nb = w.num_batches
 
-    def step(b: int, stats_t):
-        lo = (b % nb) * w.batch_size
-        s = seeds[lo:lo + w.batch_size]
-        dci.dci_sample_khop(ctx, g, cache, s, b % nb, w.fanouts, w.rng_seed, blk, stats_t)
-        dci.dci_gather_features(ctx, g, cache, blk.nodes, blk.cap_nodes[-1], x, n_dev=blk.n_input_dev(), stats=stats_t)
-        dci.dci_sage_forward(ctx, blk, x, ws, wn, bs, logits)
+    # Two streams: the sampling chain of a batch is a string of short, latency-bound kernels that
+    # leaves most of the chip idle, so it runs one batch ahead of the bandwidth- and MFMA-bound
+    # gather / forward kernels (double-buffered blocks, events both ways).  Same default priority.
+    overlap = not args.no_overlap
+    s_stream = torch.cuda.Stream() if overlap else None
+    ctx_s = dci.Context(0, stream=s_stream) if overlap else ctx
+    blks = [blk, dci.Blocks(ctx, w.num_nodes, w.batch_size, w.fanouts)] if overlap else [blk]
+    ctx_s.ensure_workspace(ctx.lib.dci_sample_workspace_bytes(w.num_nodes, w.batch_size,
+                                                              (C.c_int32 * w.n_hops)(*w.fanouts), w.n_hops))
 
-    for b in range(args.warmup):
-        step(b, None)
-    ctx.sync()
+    def sample(b: int, stats_t):
+        lo = (b % nb) * w.batch_size
+        dci.dci_sample_khop(ctx_s, g, cache, seeds[lo:lo + w.batch_size], b % nb, w.fanouts, w.rng_seed,
+                            blks[b % len(blks)], stats_t)
+
+    def consume(b: int, stats_t):
+        bk = blks[b % len(blks)]
+        dci.dci_gather_features(ctx, g, cache, bk.nodes, bk.cap_nodes[-1], x, n_dev=bk.n_input_dev(), stats=stats_t)
+        dci.dci_sage_forward(ctx, bk, x, ws, wn, bs, logits)
+
+    def run_steps(first: int, count: int, stats_s, stats_c):
+        """Exactly `count` whole steps (batches first .. first+count-1); nothing is in flight before or after."""
+        if not overlap:
+            for b in range(first, first + count):
+                sample(b, stats_s)
+                consume(b, stats_c)
+            return
+        main = torch.cuda.current_stream()
+        s_stream.wait_stream(main)
+        sampled = [torch.cuda.Event() for _ in range(count)]
+        consumed = [torch.cuda.Event() for _ in range(count)]
+        with torch.cuda.stream(s_stream):
+            sample(first, stats_s)
+            sampled[0].record(s_stream)
+        for k in range(count):
+            if k + 1 < count:
+                with torch.cuda.stream(s_stream):
+                    if k >= 1:
+                        s_stream.wait_event(consumed[k - 1])  # the buffer of batch k+1 was last read by batch k-1
+                    sample(first + k + 1, stats_s)
+                    sampled[k + 1].record(s_stream)
+            main.wait_event(sampled[k])
+            consume(first + k, stats_c)
+            consumed[k].record(main)
+        main.wait_stream(s_stream)
+
+    run_steps(0, args.warmup, None, None)
+    torch.cuda.synchronize()
 
     # ---- timed region: exactly K steps; the dominant kernel class is bracketed by events
     dominant = "linear_in"
     ctx.timing_enable(dci.KERNEL_CLASSES if args.time_all_kernels else [dominant, "gather"])
+    if args.time_all_kernels and overlap:
+        ctx_s.timing_enable(dci.KERNEL_CLASSES)
     stats = torch.zeros(dci.STATS_WORDS, dtype=torch.int64, device="cuda")
+    stats_s = torch.zeros(dci.STATS_WORDS, dtype=torch.int64, device="cuda") if overlap else stats
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     ev[0].record()
-    for b in range(args.steps):
-        step(b, stats)
+    run_steps(0, args.steps, stats_s, stats)
     ev[1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     wall_s = t1 - t0
     timing = ctx.timing_read()
     ctx.timing_enable([])
+    if overlap:
+        for k, v in ctx_s.timing_read().items():
+            timing[k] = (timing[k][0] + v[0], timing[k][1] + v[1])
+        ctx_s.timing_enable([])
+        stats += stats_s
     st = {k: int(v) for k, v in zip(dci.STAT.keys(), stats.cpu().numpy()[:len(dci.STAT)])}
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
@@ -224,7 +273,7 @@ def main() -> int:
         "config": {"workload": w.name, "nodes": w.num_nodes, "edges": w.num_edges, "feat_dim": w.feat_dim,
                    "fanouts_from_seeds": list(w.fanouts), "batch_size": w.batch_size, "dims": list(w.dims),
                    "budget_bytes": 0 if args.no_cache else w.budget_bytes, "feat_policy": args.feat_policy,
-                   "cache": not args.no_cache},
+                   "cache": not args.no_cache, "overlap_sampling": overlap},
         "extras": {
             "edges_per_step": round(edges / args.steps, 1), "input_nodes_per_step": round(rows / args.steps, 1),
             "gather_GBps_delivered": round(gather_bytes / (gather_ms * 1e-3) / 1e9, 1) if gather_ms > 0 else None,

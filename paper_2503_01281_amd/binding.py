@@ -110,13 +110,14 @@ def blocks_bounds(num_nodes: int, n_seeds: int, fanouts: Sequence[int]):
 
 
 class Context:
-    """A libdci context on the current PyTorch stream of ``device`` with a growable workspace."""
+    """A libdci context on a PyTorch stream of ``device`` (default: the current one) with a growable
+    workspace.  Calls that involve PyTorch allocations should be made with that stream current."""
 
-    def __init__(self, device: int = 0, workspace_bytes: int = 0):
+    def __init__(self, device: int = 0, workspace_bytes: int = 0, stream: Optional["torch.cuda.Stream"] = None):
         self.lib = load_library()
         self.device = torch.device("cuda", device)
         torch.cuda.set_device(self.device)
-        self.stream = torch.cuda.current_stream(self.device)
+        self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
         self._h = C.c_void_p()
         rc = self.lib.dci_create(C.byref(self._h), device, C.c_void_p(self.stream.cuda_stream), None, 0)
         if rc != 0:
