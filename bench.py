@@ -44,9 +44,13 @@ def main() -> int:
     ap.add_argument("--no-cache", action="store_true", help="run the miss path only (no dual cache)")
     ap.add_argument("--feat-policy", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-overlap", action="store_true",
-                    help="run sample -> gather -> forward of each batch back to back on one stream; by default the "
-                         "sampling of batch b+1 runs on a second stream while batch b is gathered and multiplied")
+    ap.add_argument("--cpu-batches", type=int, default=8, help="batches the CPU oracle is timed on")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="HIP streams of the timed region; each runs whole steps on its share of the batches. The "
+                         "default 1 keeps every kernel alone on the chip so that the per-kernel roofline is clean")
+    ap.add_argument("--extra-streams", type=int, default=4,
+                    help="after the timed region, time the same K steps once more on this many streams and report "
+                         "it under extras.multi_stream (0 = skip)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region run one device-to-device copy of 1 GiB (a kernel of known "
                          "traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
@@ -111,79 +115,75 @@ def main() -> int:
 
     nb = w.num_batches
 
-    # Two streams: the sampling chain of a batch is a string of short, latency-bound kernels that
-    # leaves most of the chip idle, so it runs one batch ahead of the bandwidth- and MFMA-bound
-    # gather / forward kernels (double-buffered blocks, events both ways).  Same default priority.
-    overlap = not args.no_overlap
-    s_stream = torch.cuda.Stream() if overlap else None
-    ctx_s = dci.Context(0, stream=s_stream) if overlap else ctx
-    blks = [blk, dci.Blocks(ctx, w.num_nodes, w.batch_size, w.fanouts)] if overlap else [blk]
-    ctx_s.ensure_workspace(ctx.lib.dci_sample_workspace_bytes(w.num_nodes, w.batch_size,
-                                                              (C.c_int32 * w.n_hops)(*w.fanouts), w.n_hops))
+    # Batches are independent, so S streams each run whole steps (sample -> gather -> forward, own
+    # context, workspace and buffers) on batches b = s (mod S): the short latency-bound sampling
+    # kernels, the bandwidth-bound gather / mean and the MFMA-bound dense layers of different batches
+    # then share the chip.  All streams have the default priority.
+    n_streams = max(1, args.streams, args.extra_streams)  # buffers for the larger of the two regions
+    main = torch.cuda.current_stream()
+    streams = [main] + [torch.cuda.Stream() for _ in range(n_streams - 1)]
+    ctxs = [ctx] + [dci.Context(0, stream=st_) for st_ in streams[1:]]
+    blks = [blk] + [dci.Blocks(ctx, w.num_nodes, w.batch_size, w.fanouts) for _ in range(n_streams - 1)]
+    xs = [x] + [torch.empty_like(x) for _ in range(n_streams - 1)]
+    outs = [logits] + [torch.empty_like(logits) for _ in range(n_streams - 1)]
+    ws_need = ctx.lib.dci_sample_workspace_bytes(w.num_nodes, w.batch_size, (C.c_int32 * w.n_hops)(*w.fanouts), w.n_hops)
+    sg_need = ctx.lib.dci_sage_workspace_bytes((C.c_int64 * 8)(*(blk.cap_nodes[:w.n_hops] + [0] * (8 - w.n_hops))),
+                                               w.n_hops, (C.c_int32 * (w.n_hops + 1))(*w.dims))
+    for c_ in ctxs:
+        c_.ensure_workspace(max(ws_need, sg_need, 1 << 20))
+    torch.cuda.synchronize()
 
-    def sample(b: int, stats_t):
+    def step(b: int, k: int, stats_t):
         lo = (b % nb) * w.batch_size
-        dci.dci_sample_khop(ctx_s, g, cache, seeds[lo:lo + w.batch_size], b % nb, w.fanouts, w.rng_seed,
-                            blks[b % len(blks)], stats_t)
+        c_, bk = ctxs[k], blks[k]
+        dci.dci_sample_khop(c_, g, cache, seeds[lo:lo + w.batch_size], b % nb, w.fanouts, w.rng_seed, bk, stats_t)
+        dci.dci_gather_features(c_, g, cache, bk.nodes, bk.cap_nodes[-1], xs[k], n_dev=bk.n_input_dev(), stats=stats_t)
+        dci.dci_sage_forward(c_, bk, xs[k], ws, wn, bs, outs[k])
 
-    def consume(b: int, stats_t):
-        bk = blks[b % len(blks)]
-        dci.dci_gather_features(ctx, g, cache, bk.nodes, bk.cap_nodes[-1], x, n_dev=bk.n_input_dev(), stats=stats_t)
-        dci.dci_sage_forward(ctx, bk, x, ws, wn, bs, logits)
-
-    def run_steps(first: int, count: int, stats_s, stats_c):
+    def run_steps(first: int, count: int, stats_list, use_streams: int):
         """Exactly `count` whole steps (batches first .. first+count-1); nothing is in flight before or after."""
-        if not overlap:
-            for b in range(first, first + count):
-                sample(b, stats_s)
-                consume(b, stats_c)
-            return
-        main = torch.cuda.current_stream()
-        s_stream.wait_stream(main)
-        sampled = [torch.cuda.Event() for _ in range(count)]
-        consumed = [torch.cuda.Event() for _ in range(count)]
-        with torch.cuda.stream(s_stream):
-            sample(first, stats_s)
-            sampled[0].record(s_stream)
-        for k in range(count):
-            if k + 1 < count:
-                with torch.cuda.stream(s_stream):
-                    if k >= 1:
-                        s_stream.wait_event(consumed[k - 1])  # the buffer of batch k+1 was last read by batch k-1
-                    sample(first + k + 1, stats_s)
-                    sampled[k + 1].record(s_stream)
-            main.wait_event(sampled[k])
-            consume(first + k, stats_c)
-            consumed[k].record(main)
-        main.wait_stream(s_stream)
+        for st_ in streams[1:use_streams]:
+            st_.wait_stream(main)
+        for b in range(first, first + count):
+            k = (b - first) % use_streams
+            with torch.cuda.stream(streams[k]):
+                step(b, k, None if stats_list is None else stats_list[k])
+        for st_ in streams[1:use_streams]:
+            main.wait_stream(st_)
 
-    run_steps(0, args.warmup, None, None)
+    run_steps(0, args.warmup, None, max(1, args.streams))
     torch.cuda.synchronize()
 
     # ---- timed region: exactly K steps; the dominant kernel class is bracketed by events
     dominant = "linear_in"
-    ctx.timing_enable(dci.KERNEL_CLASSES if args.time_all_kernels else [dominant, "gather"])
-    if args.time_all_kernels and overlap:
-        ctx_s.timing_enable(dci.KERNEL_CLASSES)
-    stats = torch.zeros(dci.STATS_WORDS, dtype=torch.int64, device="cuda")
-    stats_s = torch.zeros(dci.STATS_WORDS, dtype=torch.int64, device="cuda") if overlap else stats
+    for c_ in ctxs:
+        c_.timing_enable(dci.KERNEL_CLASSES if args.time_all_kernels else [dominant, "gather"])
+    stats_list = [torch.zeros(dci.STATS_WORDS, dtype=torch.int64, device="cuda") for _ in range(n_streams)]
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     ev[0].record()
-    run_steps(0, args.steps, stats_s, stats)
+    run_steps(0, args.steps, stats_list, max(1, args.streams))
     ev[1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     wall_s = t1 - t0
-    timing = ctx.timing_read()
-    ctx.timing_enable([])
-    if overlap:
-        for k, v in ctx_s.timing_read().items():
+    timing = {k: (0.0, 0) for k in dci.KERNEL_CLASSES}
+    for c_ in ctxs:
+        for k, v in c_.timing_read().items():
             timing[k] = (timing[k][0] + v[0], timing[k][1] + v[1])
-        ctx_s.timing_enable([])
-        stats += stats_s
+        c_.timing_enable([])
+    stats = sum(stats_list[1:], stats_list[0])
     st = {k: int(v) for k, v in zip(dci.STAT.keys(), stats.cpu().numpy()[:len(dci.STAT)])}
+    multi = None
+    if args.extra_streams > 1:
+        run_steps(0, min(args.steps, 2 * args.extra_streams), None, args.extra_streams)
+        torch.cuda.synchronize()
+        tm0 = time.perf_counter()
+        run_steps(0, args.steps, None, args.extra_streams)
+        torch.cuda.synchronize()
+        tm = time.perf_counter() - tm0
+        multi = {"streams": args.extra_streams, "ms_per_step": round(tm * 1e3 / args.steps, 4)}
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -192,11 +192,26 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    # host-link reference: one pinned-host -> HBM copy of the first GiB (or all) of the edge array
+    n_link = min(indices.numel(), 1 << 27)
+    link_dst = torch.empty(n_link, dtype=torch.int64, device="cuda")
+    link_ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    link_dst.copy_(indices[:n_link], non_blocking=True)
+    torch.cuda.synchronize()
+    link_ev[0].record()
+    link_dst.copy_(indices[:n_link], non_blocking=True)
+    link_ev[1].record()
+    torch.cuda.synchronize()
+    host_link_gbps = n_link * 8 / (link_ev[0].elapsed_time(link_ev[1]) * 1e-3) / 1e9
+    del link_dst
+
     edges = st["edges_sampled"]
     rows = st["feat_hits"] + st["feat_misses"]
     gather_bytes = rows * w.feat_dim * 4
     gather_ms, gather_n = timing["gather"]
     value = edges / wall_s
+    if multi is not None:
+        multi["value"] = round(edges / (multi["ms_per_step"] * 1e-3 * args.steps), 1)  # same K batches, same edges
 
     # ---- roofline of the dominant kernel: the first dense layer (fp32 MFMA, K = 2 * feat_dim).
     # Flops per launch are 2 * n_nodes[L-1] * (2 * dims[0]) * dims[1]; the row counts of the timed
@@ -237,19 +252,27 @@ def main() -> int:
     if not args.no_cpu_baseline:
         import oracle
         ip, ix, ft = indptr.numpy(), indices.numpy(), feat.numpy()
-        t0 = time.perf_counter()
-        ob = oracle.sample_khop(ip, ix, seeds_h[:w.batch_size], 0, w.fanouts, w.rng_seed)
-        t_s = time.perf_counter()
-        ox = oracle.gather(ft, ob.nodes)
-        t_g = time.perf_counter()
-        ol = oracle.sage_forward(ob, ox, ws_h, wn_h, b_h)
-        t_f = time.perf_counter()
-        e0 = int(ob.n_edges.sum())
-        cpu = {"value": round(e0 / (t_f - t0), 1), "unit": "edges/s", "cores": 1, "kind": "oracle",
-               "sample": f"batch 0 of '{w.name}' ({w.batch_size} seeds, {e0} edges, {len(ob.nodes)} input nodes): "
-                         f"sample {t_s - t0:.2f}s, gather {t_g - t_s:.2f}s, forward {t_f - t_g:.2f}s",
-               "sample_edges_per_s": round(e0 / (t_s - t0), 1),
-               "gather_GBps": round(len(ob.nodes) * w.feat_dim * 4 / (t_g - t_s) / 1e9, 3)}
+        n_cpu = max(1, min(args.cpu_batches, nb))
+        t_s = t_g = t_f = 0.0
+        e_cpu = rows_cpu = 0
+        for b in range(n_cpu):
+            lo = b * w.batch_size
+            c0 = time.perf_counter()
+            ob_b = oracle.sample_khop(ip, ix, seeds_h[lo:lo + w.batch_size], b, w.fanouts, w.rng_seed)
+            c1 = time.perf_counter()
+            ox_b = oracle.gather(ft, ob_b.nodes)
+            c2 = time.perf_counter()
+            ol_b = oracle.sage_forward(ob_b, ox_b, ws_h, wn_h, b_h)
+            c3 = time.perf_counter()
+            t_s += c1 - c0; t_g += c2 - c1; t_f += c3 - c2
+            e_cpu += int(ob_b.n_edges.sum()); rows_cpu += len(ob_b.nodes)
+            if b == 0:
+                ob, ox, ol = ob_b, ox_b, ol_b
+        cpu = {"value": round(e_cpu / (t_s + t_g + t_f), 1), "unit": "edges/s", "cores": 1, "kind": "oracle",
+               "sample": f"batches 0..{n_cpu - 1} of '{w.name}' ({e_cpu} edges, {rows_cpu} input rows): "
+                         f"sample {t_s:.2f}s, gather {t_g:.2f}s, forward {t_f:.2f}s",
+               "sample_edges_per_s": round(e_cpu / t_s, 1),
+               "gather_GBps": round(rows_cpu * w.feat_dim * 4 / t_g / 1e9, 3)}
         # the same batch from the GPU, as a last parity check on the benchmarked configuration
         dci.dci_sample_khop(ctx, g, cache, seeds[:w.batch_size], 0, w.fanouts, w.rng_seed, blk, None)
         dci.dci_gather_features(ctx, g, cache, blk.nodes, blk.cap_nodes[-1], x, n_dev=blk.n_input_dev())
@@ -271,9 +294,9 @@ def main() -> int:
         "ms_per_step": round(wall_s * 1e3 / args.steps, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "nodes": w.num_nodes, "edges": w.num_edges, "feat_dim": w.feat_dim,
-                   "fanouts_from_seeds": list(w.fanouts), "batch_size": w.batch_size, "dims": list(w.dims),
+                   "fanouts_from_seeds": list(w.fanouts), "batch_size": w.batch_size, "sage_dims": list(w.dims),
                    "budget_bytes": 0 if args.no_cache else w.budget_bytes, "feat_policy": args.feat_policy,
-                   "cache": not args.no_cache, "overlap_sampling": overlap},
+                   "cache": not args.no_cache, "streams": max(1, args.streams)},
         "extras": {
             "edges_per_step": round(edges / args.steps, 1), "input_nodes_per_step": round(rows / args.steps, 1),
             "gather_GBps_delivered": round(gather_bytes / (gather_ms * 1e-3) / 1e9, 1) if gather_ms > 0 else None,
@@ -282,7 +305,10 @@ def main() -> int:
             "feat_hit_rate": round(st["feat_hits"] / rows, 4) if rows else None,
             "gpu_event_ms_per_step": round(ev[0].elapsed_time(ev[1]) / args.steps, 4),
             "kernel_ms_per_step": {k: round(v[0] / args.steps, 4) for k, v in timing.items() if v[1]},
-            "preprocess": pre, "gather_roofline": gather_roof,
+            "preprocess": pre, "gather_roofline": gather_roof, "multi_stream": multi,
+            "host_link_pinned_copy_GBps": round(host_link_gbps, 1),
+            "gather_frac_of_host_link": (round(gather_bytes / (gather_ms * 1e-3) / 1e9 / host_link_gbps, 3)
+                                         if (gather_ms > 0 and st["feat_hits"] == 0) else None),
         },
         "roofline": roofline, "cpu_baseline": cpu,
     }

@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kMeanBlock) void k_sage_mean(const long long* __res
 // reads hit consecutive banks) with the next k-slab in flight while the current one is used.
 // Workgroup ids are mapped so that the column tiles of one row tile run on the same XCD and
 // share its L2.
-constexpr int TM = 64, TN = 64, TK = 32, LDS_PAD = 4;
+constexpr int TM = 64, TN = 64, TK = 16, LDS_PAD = 4;
 constexpr int kGemmThreads = 256;
 
 struct LinearArgs {
@@ -113,7 +113,7 @@ struct LinearArgs {
 // VA: floats per global access along K for the activations (needs K % VA == 0 and aligned bases)
 // VB: floats per global access along N for the weights (needs N % VB == 0)
 template <int VA, int VB>
-__global__ __launch_bounds__(kGemmThreads) void k_sage_linear(LinearArgs a) {
+__global__ __launch_bounds__(kGemmThreads, 6) void k_sage_linear(LinearArgs a) {
   __shared__ __attribute__((aligned(16))) float As[2][TK][TM + LDS_PAD];
   __shared__ __attribute__((aligned(16))) float Bs[2][TK][TN + LDS_PAD];
   const long long M = a.counts[a.hop];
