@@ -40,7 +40,10 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=54)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="medium", choices=["tiny", "medium", "large"])
+    ap.add_argument("--workload", default="medium", choices=["tiny", "medium", "large", "huge", "skewed"])
+    ap.add_argument("--features-in-hbm", action="store_true",
+                    help="keep the feature matrix in device memory instead of pinned host memory (forced for the "
+                         "huge and skewed workloads: the boxes pin at most about 60 GB)")
     ap.add_argument("--no-cache", action="store_true", help="run the miss path only (no dual cache)")
     ap.add_argument("--feat-policy", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -73,10 +76,19 @@ def main() -> int:
     t0 = time.time()
     indptr = torch.empty(w.num_nodes + 1, dtype=torch.int64, pin_memory=True)
     indices = torch.empty(w.num_edges, dtype=torch.int64, pin_memory=True)
-    feat = torch.empty(w.num_nodes, w.feat_dim, dtype=torch.float32, pin_memory=True)
+    feat_in_hbm = args.features_in_hbm or w.name in ("huge", "skewed")
     synth.rmat_csr(w.num_nodes, w.num_edges, w.rmat, w.graph_seed, indptr_ptr=indptr.data_ptr(),
                    indices_ptr=indices.data_ptr())
-    synth.features(w.num_nodes, w.feat_dim, w.feature_seed, ptr=feat.data_ptr())
+    if feat_in_hbm:
+        feat_host = torch.from_numpy(synth.features(w.num_nodes, w.feat_dim, w.feature_seed))
+        feat = torch.empty(w.num_nodes, w.feat_dim, dtype=torch.float32, device="cuda")
+        rows_step = max(1, (1 << 28) // w.feat_dim)
+        for lo_ in range(0, w.num_nodes, rows_step):
+            feat[lo_:lo_ + rows_step].copy_(feat_host[lo_:lo_ + rows_step])
+    else:
+        feat = torch.empty(w.num_nodes, w.feat_dim, dtype=torch.float32, pin_memory=True)
+        synth.features(w.num_nodes, w.feat_dim, w.feature_seed, ptr=feat.data_ptr())
+        feat_host = feat
     seeds_h = synth.seeds(w.num_nodes, w.num_seeds, w.seed_seed)
     ws_h, wn_h, b_h = synth.sage_weights(w.dims, w.weight_seed)
     log(f"[bench] inputs for '{w.name}' generated in {time.time() - t0:.1f}s "
@@ -251,7 +263,7 @@ def main() -> int:
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        ip, ix, ft = indptr.numpy(), indices.numpy(), feat.numpy()
+        ip, ix, ft = indptr.numpy(), indices.numpy(), feat_host.numpy()
         n_cpu = max(1, min(args.cpu_batches, nb))
         t_s = t_g = t_f = 0.0
         e_cpu = rows_cpu = 0
@@ -296,7 +308,8 @@ def main() -> int:
         "config": {"workload": w.name, "nodes": w.num_nodes, "edges": w.num_edges, "feat_dim": w.feat_dim,
                    "fanouts_from_seeds": list(w.fanouts), "batch_size": w.batch_size, "sage_dims": list(w.dims),
                    "budget_bytes": 0 if args.no_cache else w.budget_bytes, "feat_policy": args.feat_policy,
-                   "cache": not args.no_cache, "streams": max(1, args.streams)},
+                   "cache": not args.no_cache, "streams": max(1, args.streams),
+                   "features": "hbm" if feat_in_hbm else "pinned host"},
         "extras": {
             "edges_per_step": round(edges / args.steps, 1), "input_nodes_per_step": round(rows / args.steps, 1),
             "gather_GBps_delivered": round(gather_bytes / (gather_ms * 1e-3) / 1e9, 1) if gather_ms > 0 else None,

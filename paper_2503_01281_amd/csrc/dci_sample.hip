@@ -1,22 +1,24 @@
 // Cache-aware multi-hop neighbour sampling, mini-batch block construction and pre-sampling
 // access counting (Section II-C; Section IV; Section IV-B, first and third paragraphs).
 //
-// Per hop, four phases, each a grid-wide kernel so that the next sees all of the previous:
-//   1. sample   - one lane group per frontier node (a whole wavefront for fan-outs above 32,
-//                 a half / quarter / eighth for smaller ones): read the node's list bounds from
-//                 the adjacency cache or the host CSR, draw the positions (Floyd's subset
-//                 algorithm on Philox4x32-10, one lane per slot), read the neighbour ids, store
-//                 them at the padded position row*fanout + slot and register every id in the
-//                 batch's hash table with an atomic minimum over that padded position.
-//   2. count    - a lane is the "first appearance" of its node iff the table still holds its own
-//                 padded position; count those per row.
-//   3. scan     - prefix sums over the rows: edge offsets of the block and the base of the new
-//                 local ids of each row.
-//   4. assign   - first appearances append their node to the frontier and publish the new local
-//                 id in the table; then every edge reads its local id from the table.
-// The table stores, per node id, either a final local id (below 2^31) or 2^31 + the smallest
-// padded position seen so far, so one atomic minimum serves both "already in the frontier"
-// and "who came first".
+// One batch is one clear of the batch's hash table, two kernels per hop and one closing kernel:
+//   k_sample_hop  - one lane group per frontier node (a whole wavefront for fan-outs above 32, a
+//                   half / quarter / eighth for smaller ones): read the node's list bounds from the
+//                   adjacency cache or the host CSR, draw the positions (Floyd's subset algorithm
+//                   on Philox4x32-10, one lane per slot), read the neighbour ids, store them at the
+//                   padded position row*fanout + slot and register every id in the hash table with
+//                   an atomic minimum over that padded position.  At hop 0 the same kernel turns
+//                   the seeds into F_0; at later hops its first workgroups write the previous
+//                   hop's edge ids, whose inputs are final by then.
+//   k_relabel_hop - a lane is the "first appearance" of its node iff the table still holds its own
+//                   padded position.  Counts them per row, prefix-sums edge counts and first
+//                   appearances over all rows (chained scan with decoupled look-back), appends the
+//                   first appearances to the frontier in (row, slot) order and publishes their
+//                   local ids in the table.
+//   k_write_src   - the last hop's edge ids, and the batch sizes for the host.
+// A table word holds the node id in its high half and, in its low half, either a final local id
+// (below 2^31) or 2^31 + the smallest padded position seen so far, so one atomic minimum serves
+// both "already in the frontier" and "who came first".
 #include "dci_internal.h"
 
 namespace dci {
