@@ -46,6 +46,10 @@ def main() -> int:
                          "huge and skewed workloads: the boxes pin at most about 60 GB)")
     ap.add_argument("--no-cache", action="store_true", help="run the miss path only (no dual cache)")
     ap.add_argument("--feat-policy", type=int, default=0)
+    ap.add_argument("--budget", type=float, default=None, help="cache budget in bytes (default: the workload's)")
+    ap.add_argument("--n-presample", type=int, default=None, help="pre-sampled batches (default: the workload's 8)")
+    ap.add_argument("--single-cache", action="store_true",
+                    help="the paper's single-cache comparison: the whole budget goes to features, no adjacency cache")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batches", type=int, default=8, help="batches the CPU oracle is timed on")
     ap.add_argument("--streams", type=int, default=1,
@@ -72,6 +76,10 @@ def main() -> int:
     import synth
 
     w = synth.WORKLOADS[args.workload]
+    if args.budget is not None:
+        w = w.scaled(w.name, budget_bytes=int(args.budget))
+    if args.n_presample is not None:
+        w = w.scaled(w.name, n_presample=args.n_presample)
     torch.cuda.set_device(0)
     t0 = time.time()
     indptr = torch.empty(w.num_nodes + 1, dtype=torch.int64, pin_memory=True)
@@ -118,7 +126,10 @@ def main() -> int:
         t1 = time.time()
         st = stats.cpu().numpy()
         ts, tf = int(st[dci.STAT["t_sample_ns"]]), int(st[dci.STAT["t_feature_ns"]])
-        cache = dci.dci_fill_caches(ctx, g, fc, ac, w.budget_bytes, ts, tf, args.feat_policy)
+        if args.single_cache:
+            cache = dci.dci_fill_caches(ctx, g, fc, ac, w.budget_bytes, 0, 1, args.feat_policy | 0x100)
+        else:
+            cache = dci.dci_fill_caches(ctx, g, fc, ac, w.budget_bytes, ts, tf, args.feat_policy)
         t2 = time.time()
         pre = dict(presample_s=round(t1 - t0, 4), fill_s=round(t2 - t1, 4), t_sample_ns=ts, t_feature_ns=tf,
                    cap_adj_bytes=int(cache.cap_adj_bytes), cap_feat_bytes=int(cache.cap_feat_bytes),
@@ -308,6 +319,7 @@ def main() -> int:
         "config": {"workload": w.name, "nodes": w.num_nodes, "edges": w.num_edges, "feat_dim": w.feat_dim,
                    "fanouts_from_seeds": list(w.fanouts), "batch_size": w.batch_size, "sage_dims": list(w.dims),
                    "budget_bytes": 0 if args.no_cache else w.budget_bytes, "feat_policy": args.feat_policy,
+                   "n_presample": w.n_presample, "single_cache": bool(args.single_cache),
                    "cache": not args.no_cache, "streams": max(1, args.streams),
                    "features": "hbm" if feat_in_hbm else "pinned host"},
         "extras": {

@@ -45,6 +45,9 @@ extern "C" {
 
 #define DCI_FEAT_POLICY_PAPER_MEAN 0 /* above-average nodes first, then the rest (Section IV-B)     */
 #define DCI_FEAT_POLICY_TOPK 1       /* nodes by visit count, descending                            */
+#define DCI_FILL_STRICT_SPLIT 0x100  /* OR-ed into feat_policy: keep the shares of Eq. (1) as they
+                                        are, no spill-over; with t_sample_ns = 0 this is the
+                                        single-cache system of Section V-B (no adjacency cache)    */
 
 typedef struct dci_ctx dci_ctx;
 
@@ -137,21 +140,18 @@ const char* dci_last_error(const dci_ctx* ctx);
  * up the elapsed time and the number of recorded launches per class into total_ms[DCI_K_COUNT]
  * and launches[DCI_K_COUNT], and starts over.  class_mask = 0 switches timing off (the default). */
 enum {
-  DCI_K_TABLE_CLEAR = 0, /* clearing the batch's hash table                        */
+  DCI_K_TABLE_CLEAR = 0, /* clearing the batch's hash table and scan status words   */
   DCI_K_SAMPLE = 1,      /* per hop: draw positions, read neighbours, register ids
-                            (also writes the previous hop's edge local ids)       */
-  DCI_K_RELABEL = 2,     /* per hop: first appearances, row offsets, new local ids */
-  DCI_K_WRITE_SRC = 3,   /* last hop: local id of every edge                       */
-  DCI_K_RESERVED4 = 4,
-  DCI_K_RESERVED5 = 5,
-  DCI_K_RESERVED6 = 6,
-  DCI_K_GATHER = 7,      /* feature gather                                         */
-  DCI_K_MEAN = 8,        /* layers after the first: neighbour mean                 */
-  DCI_K_LINEAR = 9,      /* layers after the first: dense layer on the matrix cores */
-  DCI_K_COUNT_NODES = 10,/* pre-sampling: visits of the input nodes                */
-  DCI_K_MEAN_IN = 11,    /* first layer (input features): neighbour mean           */
-  DCI_K_LINEAR_IN = 12,  /* first layer (input features): dense layer              */
-  DCI_K_COUNT = 13
+                            (also writes the previous hop's edge local ids)        */
+  DCI_K_RELABEL = 2,     /* per hop: first appearances, row offsets, new local ids  */
+  DCI_K_WRITE_SRC = 3,   /* last hop: local id of every edge, batch sizes to host   */
+  DCI_K_GATHER = 4,      /* feature gather                                          */
+  DCI_K_MEAN_IN = 5,     /* first layer (input features): neighbour mean            */
+  DCI_K_LINEAR_IN = 6,   /* first layer (input features): dense layer (matrix cores) */
+  DCI_K_MEAN = 7,        /* later layers: neighbour mean                            */
+  DCI_K_LINEAR = 8,      /* later layers: dense layer                               */
+  DCI_K_COUNT_NODES = 9, /* pre-sampling: visits of the input nodes                 */
+  DCI_K_COUNT = 10
 };
 #define DCI_TIMING_MAX_LAUNCHES 8192
 int32_t dci_timing_enable(dci_ctx* ctx, uint32_t class_mask);
@@ -197,7 +197,7 @@ int32_t dci_presample_count(dci_ctx* ctx, const dci_graph* graph, const dci_cach
  *     (half each when both times are 0).  A share larger than its side can use - the whole
  *     adjacency structure is 8*(N+1+E) bytes, the whole feature matrix 4*N*F - is cut to that
  *     and the excess moves to the other side, so a budget that covers the dataset caches all
- *     of it.
+ *     of it (unless DCI_FILL_STRICT_SPLIT is set in feat_policy).
  *  2. Feature cache: k = min(N, C_feat / (4F)) rows.  DCI_FEAT_POLICY_PAPER_MEAN takes the nodes
  *     whose feat_count exceeds the mean over all N nodes, in ascending id, then the other nodes
  *     in ascending id, and keeps the first k.  DCI_FEAT_POLICY_TOPK orders by feat_count

@@ -16,7 +16,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "dci_oracle.cpp")
-_LIB = os.path.join(_HERE, "libdci_oracle.so")
+_LIB = os.environ.get("DCI_ORACLE_LIB") or os.path.join(_HERE, "libdci_oracle.so")  # override: mutation checks of the pins
 _lib = None
 
 c = ctypes
@@ -48,7 +48,7 @@ def _load():
         lib.oracle_presample_count.argtypes = [_P, _P, _P, c.c_int64, c.c_int32, c.c_int64, c.c_int64,
                                                c.c_uint64, _P, c.c_int32, c.c_uint64, _P, _P, _P, _P]
         lib.oracle_presample_count.restype = c.c_int32
-        lib.oracle_split.argtypes = [c.c_uint64, c.c_uint64, c.c_uint64, c.c_int64, c.c_int64, c.c_int32, _P, _P]
+        lib.oracle_split.argtypes = [c.c_uint64, c.c_uint64, c.c_uint64, c.c_int64, c.c_int64, c.c_int32, c.c_int32, _P, _P]
         lib.oracle_split.restype = None
         lib.oracle_fill_feat.argtypes = [c.c_int64, c.c_int32, _P, _P, c.c_uint64, c.c_int32, _P, _P]
         lib.oracle_fill_feat.restype = c.c_int64
@@ -169,10 +169,10 @@ def presample_count(indptr, indices, seeds, batch_size: int, n_batches: int, fan
     return fc, ac, ec, (int(totals[0]), int(totals[1]))
 
 
-def split(C: int, t_sample: int, t_feature: int, N: int, E: int, F: int):
+def split(C: int, t_sample: int, t_feature: int, N: int, E: int, F: int, spill: bool = True):
     a = c.c_uint64(0)
     f = c.c_uint64(0)
-    _load().oracle_split(C, t_sample, t_feature, N, E, F, c.byref(a), c.byref(f))
+    _load().oracle_split(C, t_sample, t_feature, N, E, F, 1 if spill else 0, c.byref(a), c.byref(f))
     return int(a.value), int(f.value)
 
 

@@ -219,17 +219,20 @@ int32_t oracle_presample_count(const int64_t* indptr, const int64_t* indices, co
   return 0;
 }
 
-// Eq. (1) in integers, followed by the spill-over rule: a share that exceeds what its side
-// can use (the whole adjacency structure, or the whole feature matrix) hands the excess to
-// the other side, so that a budget covering the whole dataset caches all of it.
+// Eq. (1) in integers, followed (when spill != 0) by the spill-over rule: a share that exceeds
+// what its side can use (the whole adjacency structure, or the whole feature matrix) hands the
+// excess to the other side, so that a budget covering the whole dataset caches all of it.
+// spill == 0 keeps the shares of Eq. (1) as they are (with t_sample = 0 this is the single-cache
+// system the paper compares with in Section V-B: no adjacency cache at all).
 void oracle_split(uint64_t C, uint64_t t_sample, uint64_t t_feature, int64_t N, int64_t E, int32_t F,
-                  uint64_t* C_adj, uint64_t* C_feat) {
+                  int32_t spill, uint64_t* C_adj, uint64_t* C_feat) {
   const uint64_t tsum = t_sample + t_feature;
   uint64_t adj0 = tsum == 0 ? C / 2 : (uint64_t)(((u128)C * (u128)t_sample) / (u128)tsum);
   uint64_t feat0 = C - adj0;
   const uint64_t A = (uint64_t)(N + 1 + E) * 8ull;
   const uint64_t Ft = (uint64_t)N * (uint64_t)F * 4ull;
-  if (A <= adj0) {
+  if (!spill) {
+  } else if (A <= adj0) {
     adj0 = A;
     feat0 = C - A;
   } else if (Ft <= feat0) {

@@ -16,8 +16,8 @@ STATS_WORDS = 16
 STAT = dict(edges_sampled=0, adj_node_hits=1, adj_node_misses=2, adj_edge_hits=3, adj_edge_misses=4,
             feat_hits=5, feat_misses=6, input_nodes=7, t_sample_ns=8, t_feature_ns=9)
 
-KERNEL_CLASSES = ["table_clear", "sample", "relabel", "write_src", "_r4", "_r5", "_r6", "gather", "mean",
-                  "linear", "count_nodes", "mean_in", "linear_in"]
+KERNEL_CLASSES = ["table_clear", "sample", "relabel", "write_src", "gather", "mean_in", "linear_in", "mean", "linear",
+                  "count_nodes"]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libdci.so")

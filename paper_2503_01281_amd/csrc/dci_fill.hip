@@ -461,6 +461,8 @@ int32_t dci_fill_caches(dci_ctx* ctx, const dci_graph* g, const uint32_t* feat_c
   if (g->num_nodes >= ((int64_t)1 << 31)) return fail(ctx, DCI_ERR_UNSUPPORTED, "more than 2^31-1 nodes");
   if (!feat_count || !adj_count || !adj_remap || !feat_remap || !out || (!cache_buf && budget_bytes > 0))
     return fail(ctx, DCI_ERR_INVALID_ARG, "fill_caches: null argument");
+  const bool strict_split = (feat_policy & DCI_FILL_STRICT_SPLIT) != 0;
+  feat_policy &= ~DCI_FILL_STRICT_SPLIT;
   if (feat_policy != DCI_FEAT_POLICY_PAPER_MEAN && feat_policy != DCI_FEAT_POLICY_TOPK)
     return fail(ctx, DCI_ERR_INVALID_ARG, "fill_caches: unknown feature policy %d", feat_policy);
   if (reinterpret_cast<uintptr_t>(cache_buf) % kAlign)
@@ -480,7 +482,8 @@ int32_t dci_fill_caches(dci_ctx* ctx, const dci_graph* g, const uint32_t* feat_c
   u64 c_adj = tsum == 0 ? C / 2 : (u64)(((unsigned __int128)C * t_sample_ns) / tsum);
   u64 c_feat = C - c_adj;
   const u64 adj_total = (u64)(N + 1 + E) * 8ull, feat_total = (u64)N * (u64)F * 4ull;
-  if (adj_total <= c_adj) {
+  if (strict_split) {
+  } else if (adj_total <= c_adj) {
     c_adj = adj_total;
     c_feat = C - adj_total;
   } else if (feat_total <= c_feat) {

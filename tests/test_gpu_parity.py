@@ -21,12 +21,12 @@ def env(tiny):
     return dict(dci=dci, gu=gpu_util, ctx=ctx, graph=g, tiny=tiny, w=tiny["w"])
 
 
-def _oracle_caches(tiny, w, ts=3, tf=7, policy=0, budget=None):
+def _oracle_caches(tiny, w, ts=3, tf=7, policy=0, budget=None, spill=True):
     fc, ac, _, _ = oracle.presample_count(tiny["indptr"], tiny["indices"], tiny["seeds"], w.batch_size,
                                           w.n_presample, w.fanouts, w.rng_seed, w.presample_first_batch,
                                           with_edge_count=False)
     C_adj, C_feat = oracle.split(w.budget_bytes if budget is None else budget, ts, tf, w.num_nodes, w.num_edges,
-                                 w.feat_dim)
+                                 w.feat_dim, spill)
     adj_remap, cp, ci = oracle.fill_adj(tiny["indptr"], tiny["indices"], ac, C_adj)
     feat_remap, fcache, k = oracle.fill_feat(fc, tiny["feat"], C_feat, policy)
     return dict(fc=fc, ac=ac, C_adj=C_adj, C_feat=C_feat, adj_remap=adj_remap, c_indptr=cp, c_indices=ci,
@@ -176,11 +176,11 @@ def test_presample_counts(env):
     assert st["t_sample_ns"] > 0 and st["t_feature_ns"] > 0
 
 
-def _check_fill(env, budget, ts, tf, policy):
+def _check_fill(env, budget, ts, tf, policy, spill=True):
     dci, gu, ctx, g, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "graph", "tiny", "w"))
-    oc = _oracle_caches(tiny, w, ts, tf, policy, budget)
+    oc = _oracle_caches(tiny, w, ts, tf, policy, budget, spill)
     cache = dci.dci_fill_caches(ctx, g, gu.dev(oc["fc"].view(np.int32)), gu.dev(oc["ac"].view(np.int32)), budget, ts, tf,
-                                policy)
+                                policy | (0 if spill else 0x100))
     K, M, k = cache.adj_nodes, cache.adj_edges, cache.feat_rows
     assert (cache.cap_adj_bytes, cache.cap_feat_bytes) == (oc["C_adj"], oc["C_feat"])
     assert (K, M, k) == (len(oc["c_indptr"]) - 1, len(oc["c_indices"]), oc["k"])
@@ -210,6 +210,16 @@ def _check_fill(env, budget, ts, tf, policy):
                                           (300_001, 0, 0), (3_000_000, 9, 1), (3_000_000, 1, 9)])
 def test_fill_caches_matches_oracle(env, budget, ts, tf, policy):
     _check_fill(env, budget, ts, tf, policy)
+
+
+@pytest.mark.parametrize("budget,ts,tf", [(5_636_104, 9, 1), (5_000_000, 1, 9), (3_000_000, 0, 1), (3_000_000, 1, 0)])
+def test_fill_strict_split_and_single_cache(env, budget, ts, tf):
+    """Eq. (1) without spill-over; t_sample = 0 gives the single-cache system (no adjacency cache)."""
+    cache = _check_fill(env, budget, ts, tf, 0, spill=False)
+    if ts == 0:
+        assert cache.adj_nodes == 0 and (cache.adj_remap == -1).all()
+    if tf == 0:
+        assert cache.feat_rows == 0 and (cache.feat_remap == -1).all()
 
 
 def test_fill_with_many_distinct_counts(env):

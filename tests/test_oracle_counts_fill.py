@@ -101,6 +101,10 @@ def test_split_spill_over():
     for ts, tf in [(1, 99), (99, 1), (1, 1), (0, 0)]:
         a, f = oracle.split(A + Ft, ts, tf, N, E, F)
         assert a >= A and f >= Ft
+    # without spill-over the shares of Eq. (1) stand; t_sample = 0 is the single-cache system
+    assert oracle.split(1000, 9, 1, N, E, F, spill=False) == (900, 100)
+    assert oracle.split(400, 1, 9, N, E, F, spill=False) == (40, 360)
+    assert oracle.split(400, 0, 5, N, E, F, spill=False) == (0, 400)
 
 
 # ------------------------------------------------------------------------------ feature fill
@@ -143,6 +147,10 @@ def test_feature_fill_mean_is_over_all_nodes():
     fc = np.array([1, 1, 1, 1], dtype=np.uint32)
     remap, _, _ = oracle.fill_feat(fc, None, 2 * 8, 0, feat_dim=2)
     assert remap.tolist() == [0, 1, -1, -1]
+    # counts 1,0,2,1 (mean 1): only node 2 is above; nodes 0 and 3 sit exactly on the mean and follow in id order
+    fc = np.array([1, 0, 2, 1], dtype=np.uint32)
+    remap, _, _ = oracle.fill_feat(fc, None, 2 * 8, 0, feat_dim=2)
+    assert remap.tolist() == [1, -1, 0, -1]
 
 
 # ------------------------------------------------------------------------------ adjacency fill
