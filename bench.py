@@ -50,6 +50,8 @@ def main() -> int:
     ap.add_argument("--n-presample", type=int, default=None, help="pre-sampled batches (default: the workload's 8)")
     ap.add_argument("--single-cache", action="store_true",
                     help="the paper's single-cache comparison: the whole budget goes to features, no adjacency cache")
+    ap.add_argument("--model", default="sage-mean", choices=["sage-mean", "sage-sum", "gcn-avg"],
+                    help="GNN of the forward pass (Table III); the headline configuration is sage-mean")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batches", type=int, default=8, help="batches the CPU oracle is timed on")
     ap.add_argument("--streams", type=int, default=1,
@@ -156,12 +158,18 @@ def main() -> int:
         c_.ensure_workspace(max(ws_need, sg_need, 1 << 20))
     torch.cuda.synchronize()
 
+    model = {"sage-mean": 0, "sage-sum": 1, "gcn-avg": 2}[args.model]
+    k_ops = 1 if model == 2 else 2      # operands of the dense layer's contraction (GCN has one weight matrix)
+
     def step(b: int, k: int, stats_t):
         lo = (b % nb) * w.batch_size
         c_, bk = ctxs[k], blks[k]
         dci.dci_sample_khop(c_, g, cache, seeds[lo:lo + w.batch_size], b % nb, w.fanouts, w.rng_seed, bk, stats_t)
         dci.dci_gather_features(c_, g, cache, bk.nodes, bk.cap_nodes[-1], xs[k], n_dev=bk.n_input_dev(), stats=stats_t)
-        dci.dci_sage_forward(c_, bk, xs[k], ws, wn, bs, outs[k])
+        if model == 0:
+            dci.dci_sage_forward(c_, bk, xs[k], ws, wn, bs, outs[k])
+        else:
+            dci.dci_gnn_forward(c_, bk, xs[k], model, ws, wn, bs, outs[k])
 
     def run_steps(first: int, count: int, stats_list, use_streams: int):
         """Exactly `count` whole steps (batches first .. first+count-1); nothing is in flight before or after."""
@@ -248,14 +256,14 @@ def main() -> int:
         ctx.sync()
         nn = blk.n_nodes()
         for l in range(w.n_hops):
-            fl = 2.0 * nn[w.n_hops - 1 - l] * (2 * w.dims[l]) * w.dims[l + 1]
+            fl = 2.0 * nn[w.n_hops - 1 - l] * (k_ops * w.dims[l]) * w.dims[l + 1]
             flops_all += fl
             if l == 0:
                 flops_in += fl
     lin_tflops = flops_in / (lin_ms * 1e-3) / 1e12 if lin_ms > 0 else 0.0
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and model == 0:   # the stored counters are of the GraphSAGE-mean launch
         try:
             traffic = json.load(open(tpath)).get(f"{dominant}:{w.name}")
         except Exception:
@@ -285,7 +293,7 @@ def main() -> int:
             c1 = time.perf_counter()
             ox_b = oracle.gather(ft, ob_b.nodes)
             c2 = time.perf_counter()
-            ol_b = oracle.sage_forward(ob_b, ox_b, ws_h, wn_h, b_h)
+            ol_b = oracle.gnn_forward(model, ob_b, ox_b, ws_h, wn_h, b_h)
             c3 = time.perf_counter()
             t_s += c1 - c0; t_g += c2 - c1; t_f += c3 - c2
             e_cpu += int(ob_b.n_edges.sum()); rows_cpu += len(ob_b.nodes)
@@ -299,7 +307,7 @@ def main() -> int:
         # the same batch from the GPU, as a last parity check on the benchmarked configuration
         dci.dci_sample_khop(ctx, g, cache, seeds[:w.batch_size], 0, w.fanouts, w.rng_seed, blk, None)
         dci.dci_gather_features(ctx, g, cache, blk.nodes, blk.cap_nodes[-1], x, n_dev=blk.n_input_dev())
-        dci.dci_sage_forward(ctx, blk, x, ws, wn, bs, logits)
+        dci.dci_gnn_forward(ctx, blk, x, model, ws, wn, bs, logits)
         ctx.sync()
         nn = blk.n_nodes()
         ok_nodes = nn == [int(v) for v in ob.n_nodes] and bool(np.array_equal(blk.nodes[:nn[-1]].cpu().numpy(), ob.nodes))
@@ -317,7 +325,7 @@ def main() -> int:
         "ms_per_step": round(wall_s * 1e3 / args.steps, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "nodes": w.num_nodes, "edges": w.num_edges, "feat_dim": w.feat_dim,
-                   "fanouts_from_seeds": list(w.fanouts), "batch_size": w.batch_size, "sage_dims": list(w.dims),
+                   "fanouts_from_seeds": list(w.fanouts), "batch_size": w.batch_size, "sage_dims": list(w.dims), "gnn": args.model,
                    "budget_bytes": 0 if args.no_cache else w.budget_bytes, "feat_policy": args.feat_policy,
                    "n_presample": w.n_presample, "single_cache": bool(args.single_cache),
                    "cache": not args.no_cache, "streams": max(1, args.streams),

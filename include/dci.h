@@ -249,6 +249,21 @@ int32_t dci_sage_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_
                          const int32_t* dims, const float* const* w_self, const float* const* w_neigh,
                          const float* const* bias, float* logits);
 
+/* The same forward pass for the other model variants of Table III:
+ *   DCI_MODEL_SAGE_MEAN  as dci_sage_forward;
+ *   DCI_MODEL_SAGE_SUM   GraphSAGE with the sum aggregator (the table's "Agg: sum"):
+ *                        m_i = sum of x[src] over the row's edges;
+ *   DCI_MODEL_GCN_AVG    GCN with the averaging aggregator (the table's "Agg: avg"): one weight
+ *                        matrix per layer, y_i = a_i w_neigh[l] + bias[l] with a_i the mean over
+ *                        node i itself and its sampled neighbours; w_self is ignored (may be NULL).
+ * All other arguments as for dci_sage_forward. */
+#define DCI_MODEL_SAGE_MEAN 0
+#define DCI_MODEL_SAGE_SUM 1
+#define DCI_MODEL_GCN_AVG 2
+int32_t dci_gnn_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_in, int32_t n_layers,
+                        const int32_t* dims, int32_t model, const float* const* w_self,
+                        const float* const* w_neigh, const float* const* bias, float* logits);
+
 #ifdef __cplusplus
 }
 #endif

@@ -64,6 +64,8 @@ def _load():
         lib.oracle_sample_hop_cached.restype = c.c_int32
         lib.oracle_sage_forward.argtypes = [c.c_int32, _P, _P, _P, _P, _P, _P, _P, _P, _P]
         lib.oracle_sage_forward.restype = None
+        lib.oracle_gnn_forward.argtypes = [c.c_int32, c.c_int32, _P, _P, _P, _P, _P, _P, _P, _P, _P]
+        lib.oracle_gnn_forward.restype = None
         _lib = lib
     return _lib
 
@@ -254,9 +256,19 @@ def sample_hop_cached(indptr, indices, adj_remap, c_indptr, c_indices, frontier,
     return rows, src[:int(rows.sum())].copy(), counts
 
 
+SAGE_MEAN, SAGE_SUM, GCN_AVG = 0, 1, 2
+
+
 def sage_forward(blocks: Blocks, x_in, w_self, w_neigh, bias) -> np.ndarray:
-    """fp64 logits [n_nodes[0], dims[-1]]."""
+    """fp64 logits [n_nodes[0], dims[-1]] of the GraphSAGE-mean model."""
+    return gnn_forward(SAGE_MEAN, blocks, x_in, w_self, w_neigh, bias)
+
+
+def gnn_forward(model: int, blocks: Blocks, x_in, w_self, w_neigh, bias) -> np.ndarray:
+    """fp64 logits [n_nodes[0], dims[-1]]; model = SAGE_MEAN, SAGE_SUM or GCN_AVG (w_self unused)."""
     lib = _load()
+    if w_self is None:
+        w_self = w_neigh
     L = len(w_self)
     assert L == len(blocks.blk_indptr)
     x_in = np.ascontiguousarray(x_in, dtype=np.float32)
@@ -269,6 +281,6 @@ def sage_forward(blocks: Blocks, x_in, w_self, w_neigh, bias) -> np.ndarray:
     bs = [_i32(a) if len(a) else np.zeros(1, dtype=np.int32) for a in blocks.blk_src]
     nn = _i64(blocks.n_nodes)
     out = np.zeros((int(nn[0]), int(dims[L])), dtype=np.float64)
-    lib.oracle_sage_forward(L, nn.ctypes.data, _ptr_array(bi), _ptr_array(bs), x_in.ctypes.data,
-                            dims.ctypes.data, _ptr_array(ws), _ptr_array(wn), _ptr_array(bb), out.ctypes.data)
+    lib.oracle_gnn_forward(model, L, nn.ctypes.data, _ptr_array(bi), _ptr_array(bs), x_in.ctypes.data,
+                           dims.ctypes.data, _ptr_array(ws), _ptr_array(wn), _ptr_array(bb), out.ctypes.data)
     return out

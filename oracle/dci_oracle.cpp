@@ -17,7 +17,8 @@
 //   * adjacency-cache fill ......... Algorithm 1 and Fig. 6, node-granular reading;
 //   * feature gather ............... Section IV, framework paragraph (hit: GPU memory,
 //     miss: host memory; same row either way);
-//   * model ........................ GraphSAGE with mean aggregation (Table III family).
+//   * model ........................ GraphSAGE with mean aggregation (Table III family), plus the
+//     table's own variants: GraphSAGE with the sum aggregator and GCN with the averaging one.
 //
 // The random numbers of the sampler come from Philox4x32-10 (Salmon et al., SC'11) used
 // as a counter-based generator keyed by (seed; node, batch, hop, slot), so a sample is a
@@ -370,16 +371,20 @@ int32_t oracle_sample_hop_cached(const int64_t* indptr, const int64_t* indices, 
   return 0;
 }
 
-// GraphSAGE-mean forward over the blocks of one mini-batch, all arithmetic in fp64.
-// Layer l (0-based) uses block h = L-1-l: for each of the n_nodes[h] destination rows i,
-//   m_i = mean of x[src] over the row's sampled edges (zero vector for an empty row),
-//   y_i = x_i W_self + m_i W_neigh + b, followed by ReLU on every layer but the last.
+// Forward pass over the blocks of one mini-batch, all arithmetic in fp64.
+// Layer l (0-based) uses block h = L-1-l; for each of the n_nodes[h] destination rows i:
+//   model 0, GraphSAGE-mean: m_i = mean of x[src] over the row's sampled edges (zero vector for an
+//            empty row); y_i = x_i W_self + m_i W_neigh + b;
+//   model 1, GraphSAGE-sum (the aggregator Table III prints for GraphSAGE): m_i = sum instead;
+//   model 2, GCN-avg (Table III): a_i = mean over node i itself and its sampled neighbours;
+//            y_i = a_i W_neigh + b (one weight matrix per layer, w_self unused);
+// followed by ReLU on every layer but the last.
 // x_in is [n_nodes[L], dims[0]] fp32; weights are [dims[l], dims[l+1]] row-major fp32;
 // logits is [n_nodes[0], dims[L]] fp64.
-void oracle_sage_forward(int32_t n_layers, const int64_t* n_nodes, const int64_t* const* blk_indptr,
-                         const int32_t* const* blk_src, const float* x_in, const int32_t* dims,
-                         const float* const* w_self, const float* const* w_neigh, const float* const* bias,
-                         double* logits) {
+void oracle_gnn_forward(int32_t model, int32_t n_layers, const int64_t* n_nodes, const int64_t* const* blk_indptr,
+                        const int32_t* const* blk_src, const float* x_in, const int32_t* dims,
+                        const float* const* w_self, const float* const* w_neigh, const float* const* bias,
+                        double* logits) {
   const int32_t L = n_layers;
   std::vector<double> x((size_t)(n_nodes[L] * dims[0]));
   for (size_t i = 0; i < x.size(); ++i) x[i] = (double)x_in[i];
@@ -390,20 +395,23 @@ void oracle_sage_forward(int32_t n_layers, const int64_t* n_nodes, const int64_t
     std::vector<double> y((size_t)(n_dst * Do));
     std::vector<double> m((size_t)D);
     for (int64_t i = 0; i < n_dst; ++i) {
-      std::fill(m.begin(), m.end(), 0.0);
+      const double* xi = &x[(size_t)i * D];
       const int64_t e0 = blk_indptr[h][i], e1 = blk_indptr[h][i + 1];
+      for (int32_t j = 0; j < D; ++j) m[j] = model == 2 ? xi[j] : 0.0;
       for (int64_t e = e0; e < e1; ++e) {
         const double* xs = &x[(size_t)blk_src[h][e] * D];
         for (int32_t j = 0; j < D; ++j) m[j] += xs[j];
       }
-      if (e1 > e0)
-        for (int32_t j = 0; j < D; ++j) m[j] /= (double)(e1 - e0);
-      const double* xi = &x[(size_t)i * D];
+      const double denom = model == 0 ? (double)(e1 - e0) : model == 2 ? (double)(e1 - e0 + 1) : 1.0;
+      if (denom > 0.0)
+        for (int32_t j = 0; j < D; ++j) m[j] /= denom;
       double* yi = &y[(size_t)i * Do];
       for (int32_t o = 0; o < Do; ++o) yi[o] = (double)bias[l][o];
       for (int32_t j = 0; j < D; ++j)
-        for (int32_t o = 0; o < Do; ++o)
-          yi[o] += xi[j] * (double)w_self[l][(size_t)j * Do + o] + m[j] * (double)w_neigh[l][(size_t)j * Do + o];
+        for (int32_t o = 0; o < Do; ++o) {
+          if (model != 2) yi[o] += xi[j] * (double)w_self[l][(size_t)j * Do + o];
+          yi[o] += m[j] * (double)w_neigh[l][(size_t)j * Do + o];
+        }
       if (l != L - 1)
         for (int32_t o = 0; o < Do; ++o)
           if (yi[o] < 0.0) yi[o] = 0.0;
@@ -411,6 +419,13 @@ void oracle_sage_forward(int32_t n_layers, const int64_t* n_nodes, const int64_t
     x.swap(y);
   }
   std::copy(x.begin(), x.begin() + (size_t)(n_nodes[0] * dims[L]), logits);
+}
+
+void oracle_sage_forward(int32_t n_layers, const int64_t* n_nodes, const int64_t* const* blk_indptr,
+                         const int32_t* const* blk_src, const float* x_in, const int32_t* dims,
+                         const float* const* w_self, const float* const* w_neigh, const float* const* bias,
+                         double* logits) {
+  oracle_gnn_forward(0, n_layers, n_nodes, blk_indptr, blk_src, x_in, dims, w_self, w_neigh, bias, logits);
 }
 
 }  // extern "C"

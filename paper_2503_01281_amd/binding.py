@@ -81,10 +81,12 @@ def load_library():
     lib.dci_sample_khop.argtypes = [P, P, P, P, i64, u64, P, i32, u64, P, P]
     lib.dci_gather_features.argtypes = [P, P, P, P, i64, P, P, P]
     lib.dci_sage_forward.argtypes = [P, P, P, i32, P, P, P, P, P]
+    lib.dci_gnn_forward.argtypes = [P, P, P, i32, P, i32, P, P, P, P]
     lib.dci_timing_enable.argtypes = [P, C.c_uint32]
     lib.dci_timing_read.argtypes = [P, P, P]
     for name in ("dci_timing_enable", "dci_timing_read", "dci_create", "dci_set_workspace", "dci_sync", "dci_blocks_bounds", "dci_presample_count",
-                 "dci_fill_caches", "dci_sample_khop", "dci_gather_features", "dci_sage_forward"):
+                 "dci_fill_caches", "dci_sample_khop", "dci_gather_features", "dci_sage_forward",
+                 "dci_gnn_forward"):
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -304,15 +306,29 @@ def dci_gather_features(ctx: Context, graph: Graph, cache: Optional[Cache], node
                                           _ptr(node_ids), n_max, n_dev, _ptr(out), _ptr(stats)))
 
 
+DCI_MODEL_SAGE_MEAN, DCI_MODEL_SAGE_SUM, DCI_MODEL_GCN_AVG = 0, 1, 2
+
+
 def dci_sage_forward(ctx: Context, blocks: Blocks, x_in: torch.Tensor, w_self: Sequence[torch.Tensor],
                      w_neigh: Sequence[torch.Tensor], bias: Sequence[torch.Tensor], logits: torch.Tensor):
-    L = len(w_self)
-    dims = [int(w_self[0].shape[0])] + [int(w.shape[1]) for w in w_self]
-    for t in list(w_self) + list(w_neigh) + list(bias) + [x_in, logits]:
+    dci_gnn_forward(ctx, blocks, x_in, DCI_MODEL_SAGE_MEAN, w_self, w_neigh, bias, logits, _entry="dci_sage_forward")
+
+
+def dci_gnn_forward(ctx: Context, blocks: Blocks, x_in: torch.Tensor, model: int,
+                    w_self: Optional[Sequence[torch.Tensor]], w_neigh: Sequence[torch.Tensor],
+                    bias: Sequence[torch.Tensor], logits: torch.Tensor, _entry: str = "dci_gnn_forward"):
+    """``w_self`` may be None for DCI_MODEL_GCN_AVG (one weight matrix per layer)."""
+    L = len(w_neigh)
+    dims = [int(w_neigh[0].shape[0])] + [int(w.shape[1]) for w in w_neigh]
+    for t in list(w_self or []) + list(w_neigh) + list(bias) + [x_in, logits]:
         assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
     assert logits.numel() >= blocks.cap_nodes[0] * dims[L]
     cap_rows = (C.c_int64 * DCI_MAX_HOPS)(*([blocks.cap_nodes[h] for h in range(L)] + [0] * (DCI_MAX_HOPS - L)))
     ctx.ensure_workspace(ctx.lib.dci_sage_workspace_bytes(cap_rows, L, _i32_array(dims)))
-    arr = lambda ts: (C.c_void_p * L)(*[t.data_ptr() for t in ts])
-    ctx.check(ctx.lib.dci_sage_forward(ctx.handle, C.byref(blocks.c), _ptr(x_in), L, _i32_array(dims), arr(w_self),
-                                       arr(w_neigh), arr(bias), _ptr(logits)))
+    arr = lambda ts: None if ts is None else (C.c_void_p * L)(*[t.data_ptr() for t in ts])
+    if _entry == "dci_sage_forward":
+        ctx.check(ctx.lib.dci_sage_forward(ctx.handle, C.byref(blocks.c), _ptr(x_in), L, _i32_array(dims), arr(w_self),
+                                           arr(w_neigh), arr(bias), _ptr(logits)))
+    else:
+        ctx.check(ctx.lib.dci_gnn_forward(ctx.handle, C.byref(blocks.c), _ptr(x_in), L, _i32_array(dims), int(model),
+                                          arr(w_self), arr(w_neigh), arr(bias), _ptr(logits)))

@@ -46,7 +46,10 @@ __global__ __launch_bounds__(kMeanBlock) void k_sage_mean(const long long* __res
                                                           const long long* __restrict__ blk_indptr,
                                                           const int* __restrict__ blk_src,
                                                           const float* __restrict__ x, int D, int lpr_log2,
-                                                          float* __restrict__ m) {
+                                                          float* __restrict__ m, int mode) {
+  // mode: DCI_MODEL_SAGE_MEAN  mean of the sampled neighbours (zero vector for an empty row)
+  //       DCI_MODEL_SAGE_SUM   their sum
+  //       DCI_MODEL_GCN_AVG    mean over the node itself and its sampled neighbours
   typedef VecF<V> O;
   typedef typename O::type vec_t;
   const long long n_rows = counts[hop];
@@ -60,10 +63,10 @@ __global__ __launch_bounds__(kMeanBlock) void k_sage_mean(const long long* __res
     const long long i = base + sub;
     if (i >= n_rows) continue;
     const long long e0 = blk_indptr[i], e1 = blk_indptr[i + 1];
-    const float cnt = (float)(e1 - e0);
+    const float cnt = (float)(e1 - e0) + (mode == DCI_MODEL_GCN_AVG ? 1.f : 0.f);
     vec_t* dst = reinterpret_cast<vec_t*>(m + i * D);
     for (int c = cl; c < chunks; c += lpr) {
-      vec_t acc = O::zero();
+      vec_t acc = mode == DCI_MODEL_GCN_AVG ? reinterpret_cast<const vec_t*>(x + i * D)[c] : O::zero();
       long long e = e0;
       for (; e + 3 < e1; e += 4) {
         const int s0 = blk_src[e], s1 = blk_src[e + 1], s2 = blk_src[e + 2], s3 = blk_src[e + 3];
@@ -77,7 +80,7 @@ __global__ __launch_bounds__(kMeanBlock) void k_sage_mean(const long long* __res
         O::add(acc, v3);
       }
       for (; e < e1; ++e) O::add(acc, reinterpret_cast<const vec_t*>(x + (long long)blk_src[e] * D)[c]);
-      dst[c] = e1 > e0 ? O::div(acc, cnt) : O::zero();
+      dst[c] = (mode == DCI_MODEL_SAGE_SUM || cnt == 0.f) ? acc : O::div(acc, cnt);
     }
   }
 }
@@ -108,6 +111,7 @@ struct LinearArgs {
   float* y;              // [M, N]
   int K, N, relu;
   int n_tiles_n;
+  int single;  // 1: only the (a_neigh, w_neigh) pair is used (GCN)
 };
 
 // VA: floats per global access along K for the activations (needs K % VA == 0 and aligned bases)
@@ -127,7 +131,9 @@ __global__ __launch_bounds__(kGemmThreads, 6) void k_sage_linear(LinearArgs a) {
   const int wm = wave >> 1, wn = wave & 1;
   const int K = a.K, N = a.N;
   const int kt_per_src = (K + TK - 1) / TK;
-  const int n_kt = 2 * kt_per_src;
+  // the slab loop is unrolled by two; with a single operand pair an odd slab count is rounded up
+  // by one slab that lies wholly beyond K and therefore loads zeros
+  const int n_kt = a.single ? (kt_per_src + 1) / 2 * 2 : 2 * kt_per_src;
 
   // two accumulators (even / odd k pairs) so that consecutive matrix instructions are independent
   floatx16 acc, acc1;
@@ -139,9 +145,9 @@ __global__ __launch_bounds__(kGemmThreads, 6) void k_sage_linear(LinearArgs a) {
 
   constexpr int kPer = TM * TK / kGemmThreads;  // floats of each operand per thread and slab
   auto load_slab = [&](int kt, float (&ra)[kPer], float (&rb)[kPer]) {
-    const bool second = kt >= kt_per_src;
-    const float* A = second ? a.a_neigh : a.a_self;
-    const float* W = second ? a.w_neigh : a.w_self;
+    const bool second = !a.single && kt >= kt_per_src;
+    const float* A = (second || a.single) ? a.a_neigh : a.a_self;
+    const float* W = (second || a.single) ? a.w_neigh : a.w_self;
     const int k0 = (second ? kt - kt_per_src : kt) * TK;
 #pragma unroll
     for (int q = 0; q < kPer / VA; ++q) {
@@ -274,15 +280,24 @@ size_t dci_sage_workspace_bytes(const int64_t* cap_rows, int32_t n_layers, const
 int32_t dci_sage_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_in, int32_t n_layers,
                          const int32_t* dims, const float* const* w_self, const float* const* w_neigh,
                          const float* const* bias, float* logits) {
+  return dci_gnn_forward(ctx, blocks, x_in, n_layers, dims, DCI_MODEL_SAGE_MEAN, w_self, w_neigh, bias, logits);
+}
+
+int32_t dci_gnn_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_in, int32_t n_layers,
+                        const int32_t* dims, int32_t model, const float* const* w_self,
+                        const float* const* w_neigh, const float* const* bias, float* logits) {
   if (!ctx) return DCI_ERR_INVALID_ARG;
-  if (!blocks || !blocks->counts || !x_in || !dims || !w_self || !w_neigh || !bias || !logits)
+  if (model != DCI_MODEL_SAGE_MEAN && model != DCI_MODEL_SAGE_SUM && model != DCI_MODEL_GCN_AVG)
+    return fail(ctx, DCI_ERR_INVALID_ARG, "gnn_forward: unknown model %d", model);
+  const bool gcn = model == DCI_MODEL_GCN_AVG;
+  if (!blocks || !blocks->counts || !x_in || !dims || (!gcn && !w_self) || !w_neigh || !bias || !logits)
     return fail(ctx, DCI_ERR_INVALID_ARG, "sage_forward: null argument");
   if (n_layers < 1 || n_layers > DCI_MAX_HOPS || n_layers != blocks->n_hops)
     return fail(ctx, DCI_ERR_INVALID_ARG, "sage_forward: n_layers must equal blocks.n_hops (1..%d)", DCI_MAX_HOPS);
   for (int32_t l = 0; l <= n_layers; ++l)
     if (dims[l] < 1) return fail(ctx, DCI_ERR_INVALID_ARG, "sage_forward: dims[%d] < 1", l);
   for (int32_t l = 0; l < n_layers; ++l)
-    if (!w_self[l] || !w_neigh[l] || !bias[l] || !blocks->blk_indptr[l] || !blocks->blk_src[l])
+    if ((!gcn && !w_self[l]) || !w_neigh[l] || !bias[l] || !blocks->blk_indptr[l] || !blocks->blk_src[l])
       return fail(ctx, DCI_ERR_INVALID_ARG, "sage_forward: null weight or block array at layer %d", l);
   Arena ar(ctx->ws, ctx->ws_bytes);
   SageWs ws;
@@ -312,13 +327,13 @@ int32_t dci_sage_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_
     Timed timed(ctx, l == 0 ? DCI_K_MEAN_IN : DCI_K_MEAN);
     if (V == 4)
       hipLaunchKernelGGL((k_sage_mean<4>), dim3((int)mb), dim3(kMeanBlock), 0, ctx->stream, counts, h, bi,
-                         (const int*)blocks->blk_src[h], x, D, lpr_log2, ws.m);
+                         (const int*)blocks->blk_src[h], x, D, lpr_log2, ws.m, model);
     else if (V == 2)
       hipLaunchKernelGGL((k_sage_mean<2>), dim3((int)mb), dim3(kMeanBlock), 0, ctx->stream, counts, h, bi,
-                         (const int*)blocks->blk_src[h], x, D, lpr_log2, ws.m);
+                         (const int*)blocks->blk_src[h], x, D, lpr_log2, ws.m, model);
     else
       hipLaunchKernelGGL((k_sage_mean<1>), dim3((int)mb), dim3(kMeanBlock), 0, ctx->stream, counts, h, bi,
-                         (const int*)blocks->blk_src[h], x, D, lpr_log2, ws.m);
+                         (const int*)blocks->blk_src[h], x, D, lpr_log2, ws.m, model);
     }
     DCI_LAUNCH_CHECK(ctx);
     // dense layer
@@ -327,7 +342,8 @@ int32_t dci_sage_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_
     la.hop = h;
     la.a_self = x;
     la.a_neigh = ws.m;
-    la.w_self = w_self[l];
+    la.w_self = gcn ? w_neigh[l] : w_self[l];
+    la.single = gcn ? 1 : 0;
     la.w_neigh = w_neigh[l];
     la.bias = bias[l];
     la.y = y;
@@ -341,7 +357,7 @@ int32_t dci_sage_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_
     int va = 1;
     if (D % 4 == 0 && aligned(x, 16) && aligned(ws.m, 16)) va = 4;
     else if (D % 2 == 0 && aligned(x, 8) && aligned(ws.m, 8)) va = 2;
-    const int vb = (Do % 4 == 0 && aligned(w_self[l], 16) && aligned(w_neigh[l], 16)) ? 4 : 1;
+    const int vb = (Do % 4 == 0 && aligned(la.w_self, 16) && aligned(w_neigh[l], 16)) ? 4 : 1;
     dim3 grid((unsigned)n_blocks);
     {
       Timed timed(ctx, l == 0 ? DCI_K_LINEAR_IN : DCI_K_LINEAR);

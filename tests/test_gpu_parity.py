@@ -266,6 +266,66 @@ def test_sage_forward_matches_oracle(env, dims, fanouts, n_seeds):
     _logit_check(logits[:n_seeds].cpu().numpy(), want)
 
 
+@pytest.mark.parametrize("model", [0, 1, 2])
+@pytest.mark.parametrize("dims,fanouts,n_seeds", [((64, 64, 16), (5, 10), 256), ((100, 130, 47), (3, 4), 70),
+                                                  ((63, 5), (7,), 129), ((602, 256, 256, 41), (2, 3, 4), 33)])
+def test_gnn_forward_model_variants_match_oracle(env, model, dims, fanouts, n_seeds):
+    """GraphSAGE-mean, GraphSAGE-sum and GCN-avg (Table III); input widths of 63, 100 and 130 give the
+    one-operand product of the GCN layer an odd number of 16-wide slabs."""
+    dci, gu, ctx, g, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "graph", "tiny", "w"))
+    seeds = tiny["seeds"][:n_seeds]
+    want_blk = oracle.sample_khop(tiny["indptr"], tiny["indices"], seeds, 2, fanouts, 6)
+    blk = dci.Blocks(ctx, w.num_nodes, n_seeds, fanouts)
+    dci.dci_sample_khop(ctx, g, None, gu.dev(seeds), 2, fanouts, 6, blk)
+    feat = synth.features(w.num_nodes, dims[0], 41)
+    ws, wn, bs = synth.sage_weights(dims, 42)
+    x = feat[want_blk.nodes]
+    want = oracle.gnn_forward(model, want_blk, x, ws, wn, bs)
+    x_dev = torch.zeros(blk.cap_nodes[-1], dims[0], dtype=torch.float32, device="cuda")
+    x_dev[:len(x)] = torch.from_numpy(x).cuda()
+    logits = torch.full((blk.cap_nodes[0], dims[-1]), float("nan"), dtype=torch.float32, device="cuda")
+    dci.dci_gnn_forward(ctx, blk, x_dev, model, None if model == 2 else [gu.dev(a) for a in ws],
+                        [gu.dev(a) for a in wn], [gu.dev(a) for a in bs], logits)
+    ctx.sync()
+    _logit_check(logits[:n_seeds].cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("model", [0, 1, 2])
+def test_gnn_forward_with_empty_rows(env, small_graphs, model):
+    dci, gu, ctx = env["dci"], env["gu"], env["ctx"]
+    indptr, indices = small_graphs[3]          # isolated nodes, a self loop, a duplicated edge
+    g = gu.make_graph(indptr, indices, None)
+    seeds = np.array([0, 4, 1, 3, 2], dtype=np.int64)
+    dims, fanouts = (6, 9, 3), (3, 2)
+    want_blk = oracle.sample_khop(indptr, indices, seeds, 0, fanouts, 4)
+    assert (np.diff(want_blk.blk_indptr[0]) == 0).any()
+    blk = dci.Blocks(ctx, 5, len(seeds), fanouts)
+    dci.dci_sample_khop(ctx, g, None, gu.dev(seeds), 0, fanouts, 4, blk)
+    x = synth.features(5, dims[0], 51)[want_blk.nodes]
+    ws, wn, bs = synth.sage_weights(dims, 52)
+    want = oracle.gnn_forward(model, want_blk, x, ws, wn, bs)
+    x_dev = torch.zeros(blk.cap_nodes[-1], dims[0], dtype=torch.float32, device="cuda")
+    x_dev[:len(x)] = torch.from_numpy(x).cuda()
+    logits = torch.full((blk.cap_nodes[0], dims[-1]), float("nan"), dtype=torch.float32, device="cuda")
+    dci.dci_gnn_forward(ctx, blk, x_dev, model, [gu.dev(a) for a in ws], [gu.dev(a) for a in wn],
+                        [gu.dev(a) for a in bs], logits)
+    ctx.sync()
+    _logit_check(logits[:len(seeds)].cpu().numpy(), want)
+
+
+def test_gnn_forward_rejects_bad_arguments(env):
+    dci, gu, ctx, g, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "graph", "tiny", "w"))
+    blk = dci.Blocks(ctx, w.num_nodes, 8, (2,))
+    dci.dci_sample_khop(ctx, g, None, gu.dev(tiny["seeds"][:8]), 0, (2,), 1, blk)
+    ws, wn, bs = ([gu.dev(a) for a in t] for t in synth.sage_weights((16, 4), 1))
+    x = torch.zeros(blk.cap_nodes[-1], 16, dtype=torch.float32, device="cuda")
+    logits = torch.zeros(8, 4, dtype=torch.float32, device="cuda")
+    with pytest.raises(dci.DciError):
+        dci.dci_gnn_forward(ctx, blk, x, 3, ws, wn, bs, logits)
+    with pytest.raises(dci.DciError):
+        dci.dci_gnn_forward(ctx, blk, x, 0, None, wn, bs, logits)   # GraphSAGE needs both weight sets
+
+
 def test_end_to_end_tiny(env):
     """presample -> fill -> sample -> gather -> forward, all on the GPU, against the oracle."""
     dci, gu, ctx, g, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "graph", "tiny", "w"))

@@ -4,10 +4,10 @@ import numpy as np
 import oracle
 
 
-def _dense_forward(blk, x, w_self, w_neigh, bias):
-    """Independent formulation: per layer build the row-normalised sampled adjacency D^-1 A_s
-    as a dense matrix and use matrix products (numpy, fp64)."""
-    L = len(w_self)
+def _dense_forward(blk, x, w_self, w_neigh, bias, model=0):
+    """Independent formulation: per layer build the sampled adjacency A_s as a dense matrix and use
+    matrix products (numpy, fp64): D^-1 A_s for the mean, A_s for the sum, (D+I)^-1 (A_s + I) for GCN."""
+    L = len(w_neigh)
     x = x.astype(np.float64)
     for l in range(L):
         h = L - 1 - l
@@ -15,11 +15,40 @@ def _dense_forward(blk, x, w_self, w_neigh, bias):
         A = np.zeros((n_dst, n_src))
         rows = np.repeat(np.arange(n_dst), np.diff(blk.blk_indptr[h]))
         np.add.at(A, (rows, blk.blk_src[h]), 1.0)
-        d = A.sum(axis=1, keepdims=True)
-        A = np.divide(A, d, out=np.zeros_like(A), where=d > 0)
-        y = x[:n_dst] @ w_self[l].astype(np.float64) + (A @ x[:n_src]) @ w_neigh[l].astype(np.float64) + bias[l]
+        if model == 2:
+            A[np.arange(n_dst), np.arange(n_dst)] += 1.0
+        if model != 1:
+            d = A.sum(axis=1, keepdims=True)
+            A = np.divide(A, d, out=np.zeros_like(A), where=d > 0)
+        y = (A @ x[:n_src]) @ w_neigh[l].astype(np.float64) + bias[l]
+        if model != 2:
+            y = y + x[:n_dst] @ w_self[l].astype(np.float64)
         x = np.maximum(y, 0.0) if l != L - 1 else y
     return x
+
+
+def test_sum_and_gcn_variants_match_dense_formulation(tiny, small_graphs):
+    w = tiny["w"]
+    blk = oracle.sample_khop(tiny["indptr"], tiny["indices"], tiny["seeds"][:64], 0, w.fanouts, w.rng_seed)
+    x = tiny["feat"][blk.nodes]
+    outs = {}
+    for model in (oracle.SAGE_MEAN, oracle.SAGE_SUM, oracle.GCN_AVG):
+        got = oracle.gnn_forward(model, blk, x, tiny["w_self"], tiny["w_neigh"], tiny["bias"])
+        want = _dense_forward(blk, x, tiny["w_self"], tiny["w_neigh"], tiny["bias"], model)
+        assert np.allclose(got, want, rtol=1e-12, atol=1e-12)
+        outs[model] = got
+    assert not np.allclose(outs[0], outs[1]) and not np.allclose(outs[0], outs[2])
+    # empty rows: sum gives zero, GCN gives the node's own features
+    indptr, indices = small_graphs[3]
+    blk = oracle.sample_khop(indptr, indices, np.array([0, 4, 1], dtype=np.int64), 1, (2,), 4)
+    xx = np.arange(len(blk.nodes) * 3, dtype=np.float32).reshape(-1, 3) + 1
+    eye, zero, b0 = np.eye(3, dtype=np.float32), np.zeros((3, 3), dtype=np.float32), np.zeros(3, dtype=np.float32)
+    got = oracle.gnn_forward(oracle.GCN_AVG, blk, xx, None, [eye], [b0])
+    assert np.array_equal(got[:2], xx[:2].astype(np.float64))           # nodes 0 and 4 have no in-neighbours
+    got = oracle.gnn_forward(oracle.SAGE_SUM, blk, xx, [zero], [eye], [b0])
+    assert np.array_equal(got[:2], np.zeros((2, 3)))
+    e0, e1 = blk.blk_indptr[0][2], blk.blk_indptr[0][3]
+    assert np.allclose(got[2], xx[blk.blk_src[0][e0:e1]].astype(np.float64).sum(axis=0))
 
 
 def test_matches_dense_formulation(tiny):
