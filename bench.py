@@ -52,6 +52,8 @@ def main() -> int:
                     help="the paper's single-cache comparison: the whole budget goes to features, no adjacency cache")
     ap.add_argument("--model", default="sage-mean", choices=["sage-mean", "sage-sum", "gcn-avg"],
                     help="GNN of the forward pass (Table III); the headline configuration is sage-mean")
+    ap.add_argument("--linear-kernel", type=int, default=0, choices=[0, 1, 2],
+                    help="dense-layer kernel of the timed region: 0 by shape (default), 1 tile kernel, 2 wide kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batches", type=int, default=8, help="batches the CPU oracle is timed on")
     ap.add_argument("--streams", type=int, default=1,
@@ -182,6 +184,8 @@ def main() -> int:
         for st_ in streams[1:use_streams]:
             main.wait_stream(st_)
 
+    for c_ in ctxs:
+        c_.set_option(dci.DCI_OPT_LINEAR_KERNEL, args.linear_kernel)
     run_steps(0, args.warmup, None, max(1, args.streams))
     torch.cuda.synchronize()
 
@@ -208,13 +212,19 @@ def main() -> int:
     st = {k: int(v) for k, v in zip(dci.STAT.keys(), stats.cpu().numpy()[:len(dci.STAT)])}
     multi = None
     if args.extra_streams > 1:
+        # with several batches in flight the statically partitioned wide dense-layer kernel (one workgroup per
+        # compute unit) loses to the tile kernel, whose many small workgroups fill whatever the other streams leave
+        for c_ in ctxs:
+            c_.set_option(dci.DCI_OPT_LINEAR_KERNEL, 1)
         run_steps(0, min(args.steps, 2 * args.extra_streams), None, args.extra_streams)
         torch.cuda.synchronize()
         tm0 = time.perf_counter()
         run_steps(0, args.steps, None, args.extra_streams)
         torch.cuda.synchronize()
         tm = time.perf_counter() - tm0
-        multi = {"streams": args.extra_streams, "ms_per_step": round(tm * 1e3 / args.steps, 4)}
+        multi = {"streams": args.extra_streams, "linear_kernel": "tile", "ms_per_step": round(tm * 1e3 / args.steps, 4)}
+        for c_ in ctxs:
+            c_.set_option(dci.DCI_OPT_LINEAR_KERNEL, args.linear_kernel)
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -268,7 +278,8 @@ def main() -> int:
             traffic = json.load(open(tpath)).get(f"{dominant}:{w.name}")
         except Exception:
             traffic = None
-    roofline = {"kernel": "k_sage_linear (first layer)", "bound": "mfma", "achieved": round(lin_tflops, 3),
+    roofline = {"kernel": "k_sage_linear_wide (first layer)" if args.linear_kernel != 1 and w.dims[1] % 128 == 0 and w.dims[0] % 2 == 0
+                else "k_sage_linear (first layer)", "bound": "mfma", "achieved": round(lin_tflops, 3),
                 "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(lin_tflops / FP32_MFMA_PEAK_TFLOPS, 4),
                 "traffic": traffic, "launches": lin_n, "avg_launch_ms": round(lin_ms / max(lin_n, 1), 4),
                 "flops_per_launch": round(flops_in / max(lin_n, 1), 1)}

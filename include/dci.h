@@ -134,6 +134,18 @@ int32_t dci_sync(dci_ctx* ctx);
 /* Message of the last failed call on this context (never NULL; "" if none). */
 const char* dci_last_error(const dci_ctx* ctx);
 
+/* Tuning options of a context.  None changes what is computed (the dense-layer kernels differ only
+ * in the order of the floating-point sums).  DCI_ERR_INVALID_ARG for an unknown option or value.
+ *   DCI_OPT_LINEAR_KERNEL  which dense-layer kernel dci_sage_forward / dci_gnn_forward launch:
+ *       0  by shape (default): the wide kernel (128-column tiles, one workgroup per compute unit)
+ *          when the layer is at least 2048 rows tall by capacity, its output width is a multiple
+ *          of 128, its input width is even and the operands are suitably aligned; else the 64x64
+ *          tile kernel
+ *       1  always the 64x64 tile kernel
+ *       2  the wide kernel whenever width and alignment allow it, whatever the row count */
+#define DCI_OPT_LINEAR_KERNEL 1
+int32_t dci_set_option(dci_ctx* ctx, int32_t option, int64_t value);
+
 /* Kernel timing, for benchmarks and profiles.  Kernel classes whose bit is set in class_mask are
  * bracketed by HIP events on the context's stream (up to DCI_TIMING_MAX_LAUNCHES launches
  * between two reads; later ones are not recorded).  dci_timing_read waits for the stream, adds

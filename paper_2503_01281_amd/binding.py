@@ -82,9 +82,10 @@ def load_library():
     lib.dci_gather_features.argtypes = [P, P, P, P, i64, P, P, P]
     lib.dci_sage_forward.argtypes = [P, P, P, i32, P, P, P, P, P]
     lib.dci_gnn_forward.argtypes = [P, P, P, i32, P, i32, P, P, P, P]
+    lib.dci_set_option.argtypes = [P, i32, i64]
     lib.dci_timing_enable.argtypes = [P, C.c_uint32]
     lib.dci_timing_read.argtypes = [P, P, P]
-    for name in ("dci_timing_enable", "dci_timing_read", "dci_create", "dci_set_workspace", "dci_sync", "dci_blocks_bounds", "dci_presample_count",
+    for name in ("dci_set_option", "dci_timing_enable", "dci_timing_read", "dci_create", "dci_set_workspace", "dci_sync", "dci_blocks_bounds", "dci_presample_count",
                  "dci_fill_caches", "dci_sample_khop", "dci_gather_features", "dci_sage_forward",
                  "dci_gnn_forward"):
         getattr(lib, name).restype = i32
@@ -146,6 +147,9 @@ class Context:
 
     def sync(self):
         self.check(self.lib.dci_sync(self._h))
+
+    def set_option(self, option: int, value: int):
+        self.check(self.lib.dci_set_option(self._h, int(option), int(value)))
 
     def timing_enable(self, classes):
         """classes: iterable of kernel-class names from KERNEL_CLASSES (empty = off)."""
@@ -307,6 +311,7 @@ def dci_gather_features(ctx: Context, graph: Graph, cache: Optional[Cache], node
 
 
 DCI_MODEL_SAGE_MEAN, DCI_MODEL_SAGE_SUM, DCI_MODEL_GCN_AVG = 0, 1, 2
+DCI_OPT_LINEAR_KERNEL = 1
 
 
 def dci_sage_forward(ctx: Context, blocks: Blocks, x_in: torch.Tensor, w_self: Sequence[torch.Tensor],

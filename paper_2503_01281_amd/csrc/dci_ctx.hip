@@ -120,6 +120,16 @@ int32_t dci_sync(dci_ctx* ctx) {
 
 const char* dci_last_error(const dci_ctx* ctx) { return ctx ? ctx->err : "null context"; }
 
+int32_t dci_set_option(dci_ctx* ctx, int32_t option, int64_t value) {
+  if (!ctx) return DCI_ERR_INVALID_ARG;
+  if (option == DCI_OPT_LINEAR_KERNEL) {
+    if (value < 0 || value > 2) return dci::fail(ctx, DCI_ERR_INVALID_ARG, "DCI_OPT_LINEAR_KERNEL takes 0, 1 or 2, not %lld", (long long)value);
+    ctx->linear_kernel = (int)value;
+    return DCI_OK;
+  }
+  return dci::fail(ctx, DCI_ERR_INVALID_ARG, "unknown option %d", option);
+}
+
 int32_t dci_blocks_bounds(int64_t num_nodes, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
                           int64_t* cap_nodes, int64_t* cap_edges) {
   if (num_nodes < 1 || n_seeds < 0 || !fanouts || n_hops < 1 || n_hops > DCI_MAX_HOPS || !cap_nodes || !cap_edges)

@@ -245,6 +245,302 @@ __global__ __launch_bounds__(kGemmThreads, 6) void k_sage_linear(LinearArgs a) {
   }
 }
 
+// ---- wide variant of the dense layer ----------------------------------------------------------
+// Same product, for outputs whose width is a multiple of 128 and enough rows to matter.  One
+// workgroup of eight wavefronts per compute unit (its LDS allotment admits no second one); a
+// workgroup owns one 128-column tile and a contiguous share of the 32-row blocks, sized on the device
+// from the row count, and walks its share in passes of up to six row blocks (192 x 128 outputs).
+// Wave w multiplies columns 32*(w&3); the row blocks of a pass are split between w>>2 = 0 and 1, so
+// the two wavefronts that share a SIMD also share the B fragment values and differ in A.
+//
+// Data movement is what limits this layer (a 64x64 tile moves 8 KB from L2 per 131 kflop and every
+// vector-ALU instruction displaces a matrix instruction), so here
+//  * operands go global -> LDS directly (16 bytes per lane, no registers, no address arithmetic on
+//    the vector ALU: a scalar base per k-slab plus a constant lane offset);
+//  * three stages of 16-deep k-slabs ring through LDS; slab i+3 is requested while slab i is
+//    multiplied, and the fragments of slab i+1 are read into a second register set meanwhile;
+//  * A is stored [row][4 chunks of 4 k] with the chunk index xor-ed by row bits, so a 16-byte
+//    fragment read (four consecutive k of one row = four matrix instructions) is conflict free;
+//    the contraction index is permuted consistently on both operands: matrix step (t, j) takes
+//    k = 8t + j from lanes 0..31 and k = 8t + 4 + j from lanes 32..63;
+//  * the loop is unrolled over (stage x register set) = 6 so that all LDS offsets are immediates;
+//  * loads, fragment reads and matrix instructions are interleaved in a fixed order
+//    (sched_barrier) so that the non-matrix issue slots hide behind the 64-cycle matrix ops.
+// Fragment reads are inline assembly: the compiler would otherwise order every LDS read behind all
+// outstanding global->LDS loads.  The columns K % 16 left over per operand go through registers
+// with masks after the pipelined loop.
+typedef float float2v __attribute__((ext_vector_type(2)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+constexpr long long kWideMinRows = 2048;  // below this capacity the 64x64 kernel fills the chip better
+constexpr int kWideThreads = 512, kWideCols = 128, kWideStages = 3, kWideMaxBlocks = 6;
+constexpr int kWideABytes = kWideMaxBlocks * 32 * 64;           // 192 rows x 16 k x 4 B
+constexpr int kWideBBytes = TK * kWideCols * 4;                 // 16 k x 128 columns x 4 B
+constexpr int kWideStageBytes = kWideABytes + kWideBBytes;      // 20 KB
+constexpr int kWideLdsBytes = 84 * 1024;                        // > half of the 160 KB: one workgroup per CU
+static_assert(kWideStages * kWideStageBytes <= 65536, "LDS offsets must fit the 16-bit immediates");
+static_assert(kWideStages * kWideStageBytes <= kWideLdsBytes, "stages must fit the allocation");
+
+struct FragW {
+  float4v a[3][2];  // [row block][t]: four consecutive k of this lane's row
+  float2v b[4];     // steps (t=0: j=0,1), (0: 2,3), (1: 0,1), (1: 2,3) of this lane's column
+};
+
+#define DCI_DS_READ_A2(x0, x1, a0_, a1_, OFF)                                     \
+  asm volatile("ds_read_b128 %0, %2 offset:%4\n\tds_read_b128 %1, %3 offset:%4"  \
+               : "=&v"(x0), "=&v"(x1)                                             \
+               : "v"(a0_), "v"(a1_), "n"(OFF)                                     \
+               : "memory")
+#define DCI_DS_READ_B4(y0, y1, y2, y3, b_, U0)                                                                       \
+  asm volatile("ds_read2st64_b32 %0, %4 offset0:%5 offset1:%6\n\tds_read2st64_b32 %1, %4 offset0:%7 offset1:%8\n\t" \
+               "ds_read2st64_b32 %2, %4 offset0:%9 offset1:%10\n\tds_read2st64_b32 %3, %4 offset0:%11 offset1:%12"  \
+               : "=&v"(y0), "=&v"(y1), "=&v"(y2), "=&v"(y3)                                                          \
+               : "v"(b_), "n"((U0) + 0), "n"((U0) + 2), "n"((U0) + 4), "n"((U0) + 6), "n"((U0) + 16),                \
+                 "n"((U0) + 18), "n"((U0) + 20), "n"((U0) + 22)                                                      \
+               : "memory")
+// waits until at most VM of this wave's global->LDS loads are outstanding and all its LDS reads have
+// returned; the second statement ties every fragment register to the wait
+#define DCI_WAIT_FRAG(f, VM)                                                                                         \
+  do {                                                                                                               \
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(VM) : "memory");                                             \
+    asm volatile("" : "+v"(f.a[0][0]), "+v"(f.a[0][1]), "+v"(f.a[1][0]), "+v"(f.a[1][1]), "+v"(f.a[2][0]),           \
+                      "+v"(f.a[2][1]), "+v"(f.b[0]), "+v"(f.b[1]), "+v"(f.b[2]), "+v"(f.b[3])::"memory");            \
+  } while (0)
+
+__global__ __launch_bounds__(kWideThreads, 1) void k_sage_linear_wide(LinearArgs a, int g_n) {
+  constexpr int NS = kWideStages, ST = kWideStageBytes, LPW = 3;  // LPW: global->LDS loads per wave and slab
+  __shared__ __attribute__((aligned(1024))) char lds[kWideLdsBytes];
+  const long long M = a.counts[a.hop];
+  const int id = (int)blockIdx.x;
+  const int xcd = id & 7, jj = id >> 3;
+  const int nt = jj % a.n_tiles_n;
+  const int slot = (jj / a.n_tiles_n) * 8 + xcd;   // the column tiles of one row share run on one XCD
+  if (slot >= g_n) return;
+  const long long n_rb = (M + 31) / 32;
+  const long long chunk = (n_rb + g_n - 1) / g_n;
+  const long long rb_begin = (long long)slot * chunk;
+  long long rb_end = rb_begin + chunk;
+  if (rb_end > n_rb) rb_end = n_rb;
+  if (rb_begin >= rb_end) return;
+  const int col0 = nt * kWideCols;
+  const int tid = (int)threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wc = wave & 3, wr = wave >> 2;
+  const int K = a.K, N = a.N;
+  const int Sf = K / TK;                   // full slabs per operand
+  const int n = a.single ? Sf : 2 * Sf;    // slabs of the pipelined loop
+  const int k_tail = K - Sf * TK;
+  const int c_a = (lane & 3) ^ ((lane >> 4) & 3);
+  const int h = lane >> 5, ll = lane & 31;
+  const unsigned lds0 = (unsigned)(size_t)(lptr_t)lds;
+  const unsigned lb0 = lds0 + 4 * h * kWideCols * 4 + (((wc * 32 + ll) ^ (32 * h)) * 4);
+  const int krB = 2 * wave + (lane >> 5);  // this lane's k row of the B slab
+  const unsigned voffB = (unsigned)((krB * N + (((lane & 31) ^ (8 * ((krB >> 2) & 1))) * 4)) * 4);
+  const float* pW0 = (a.single ? a.w_neigh : a.w_self) + col0;
+  const float* pW1 = a.w_neigh + col0;
+  const int col = col0 + wc * 32 + ll;
+  const float bias = a.bias[col];
+  const int ldsA1 = (wave + 8 > 2 * kWideMaxBlocks - 1 ? 2 * kWideMaxBlocks - 1 : wave + 8) * 1024;
+
+  const int cnt = (int)(rb_end - rb_begin);
+  const int n_pass = (cnt + kWideMaxBlocks - 1) / kWideMaxBlocks;
+  const int per = (cnt + n_pass - 1) / n_pass;
+  for (long long prb = rb_begin; prb < rb_end; prb += per) {
+    const int r_eff = (int)((rb_end - prb) < per ? (rb_end - prb) : per);  // 1..6 row blocks in this pass
+    const int rw0 = (r_eff + 1) / 2;
+    const int rw = wr == 0 ? rw0 : r_eff - rw0;                             // row blocks of this wave (0..3)
+    const long long row0 = prb * 32;
+    // the 16-row groups this wave fetches (wave and wave + 8, the latter clamped: four waves repeat
+    // group 11); rows past M repeat row M-1 and are never stored
+    unsigned voffA[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      int i = wave + 8 * q;
+      if (i > 2 * kWideMaxBlocks - 1) i = 2 * kWideMaxBlocks - 1;
+      long long r = row0 + 16 * i + (lane >> 2);
+      if (r > M - 1) r = M - 1;
+      voffA[q] = (unsigned)(((r - row0) * K + c_a * 4) * 4);
+    }
+    const float* pA0 = (a.single ? a.a_neigh : a.a_self) + row0 * K;
+    const float* pA1 = a.a_neigh + row0 * K;
+    const unsigned la0 = lds0 + (wr * rw0 * 32 + ll) * 64 + ((h ^ ((ll >> 2) & 3)) * 16);
+    const unsigned la1 = la0 ^ 32u;
+    floatx16 acc[3];
+#pragma unroll
+    for (int rb = 0; rb < 3; ++rb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[rb][r] = 0.f;
+
+#define DCI_SLAB_PTRS(s_)                                                                            \
+  const bool second_ = (s_) >= Sf && !a.single;                                                      \
+  const int ks_ = second_ ? (s_) - Sf : (s_);                                                        \
+  const char* ga_ = reinterpret_cast<const char*>((second_ ? pA1 : pA0) + ks_ * TK);                 \
+  const char* gw_ = reinterpret_cast<const char*>((second_ ? pW1 : pW0) + (size_t)ks_ * TK * N)
+#define DCI_LOAD_A0(STG) \
+  __builtin_amdgcn_global_load_lds((gptr_t)(ga_ + voffA[0]), (lptr_t)(lds + (STG)*ST + wave * 1024), 16, 0, 0)
+#define DCI_LOAD_A1(STG) \
+  __builtin_amdgcn_global_load_lds((gptr_t)(ga_ + voffA[1]), (lptr_t)(lds + (STG)*ST + ldsA1), 16, 0, 0)
+#define DCI_LOAD_B(STG) \
+  __builtin_amdgcn_global_load_lds((gptr_t)(gw_ + voffB), (lptr_t)(lds + (STG)*ST + kWideABytes + wave * 1024), 16, 0, 0)
+#define DCI_ISSUE(s_, STG) \
+  do {                     \
+    DCI_SLAB_PTRS(s_);     \
+    DCI_LOAD_A0(STG);      \
+    DCI_LOAD_A1(STG);      \
+    DCI_LOAD_B(STG);       \
+  } while (0)
+#define DCI_READ(f, STG)                                                                  \
+  do {                                                                                    \
+    DCI_DS_READ_A2(f.a[0][0], f.a[0][1], la0, la1, (STG)*ST + 0 * 2048);                  \
+    DCI_DS_READ_A2(f.a[1][0], f.a[1][1], la0, la1, (STG)*ST + 1 * 2048);                  \
+    DCI_DS_READ_A2(f.a[2][0], f.a[2][1], la0, la1, (STG)*ST + 2 * 2048);                  \
+    DCI_DS_READ_B4(f.b[0], f.b[1], f.b[2], f.b[3], lb0, ((STG)*ST + kWideABytes) / 256);  \
+  } while (0)
+// matrix step (t_, j_) of every row block of this wave
+#define DCI_MFMA_G(f, t_, j_)                                                                                          \
+  do {                                                                                                                 \
+    const float bv_ = ((j_) & 1) ? f.b[2 * (t_) + ((j_) >> 1)].y : f.b[2 * (t_) + ((j_) >> 1)].x;                      \
+    _Pragma("unroll") for (int rb_ = 0; rb_ < 3; ++rb_) {                                                              \
+      const float av_ = (j_) == 0 ? f.a[rb_][t_].x : (j_) == 1 ? f.a[rb_][t_].y : (j_) == 2 ? f.a[rb_][t_].z : f.a[rb_][t_].w; \
+      if (rb_ < rw) acc[rb_] = __builtin_amdgcn_mfma_f32_32x32x2f32(av_, bv_, acc[rb_], 0, 0, 0);                      \
+    }                                                                                                                  \
+    __builtin_amdgcn_sched_barrier(0);                                                                                 \
+  } while (0)
+#define DCI_MFMA_SLAB(f)                                       \
+  do {                                                         \
+    __builtin_amdgcn_sched_barrier(0);                         \
+    DCI_MFMA_G(f, 0, 0); DCI_MFMA_G(f, 0, 1); DCI_MFMA_G(f, 0, 2); DCI_MFMA_G(f, 0, 3); \
+    DCI_MFMA_G(f, 1, 0); DCI_MFMA_G(f, 1, 1); DCI_MFMA_G(f, 1, 2); DCI_MFMA_G(f, 1, 3); \
+  } while (0)
+// steady state: slab idx is multiplied from FC while slab idx+3 is requested into the stage it
+// leaves (U % 3) and the fragments of slab idx+1 are read into FN
+#define DCI_STEP(FC, FN, idx, U)                                                      \
+  do {                                                                                \
+    DCI_WAIT_FRAG(FC, LPW * (NS - 2));                                                \
+    __builtin_amdgcn_s_barrier();                                                     \
+    DCI_SLAB_PTRS((idx) + NS);                                                        \
+    __builtin_amdgcn_sched_barrier(0);                                                \
+    DCI_MFMA_G(FC, 0, 0);                                                             \
+    DCI_LOAD_A0((U) % 3);                                                             \
+    __builtin_amdgcn_sched_barrier(0);                                                \
+    DCI_MFMA_G(FC, 0, 1);                                                             \
+    DCI_LOAD_A1((U) % 3);                                                             \
+    __builtin_amdgcn_sched_barrier(0);                                                \
+    DCI_MFMA_G(FC, 0, 2);                                                             \
+    DCI_LOAD_B((U) % 3);                                                              \
+    __builtin_amdgcn_sched_barrier(0);                                                \
+    DCI_MFMA_G(FC, 0, 3);                                                             \
+    DCI_DS_READ_A2(FN.a[0][0], FN.a[0][1], la0, la1, (((U) + 1) % 3) * ST + 0 * 2048); \
+    __builtin_amdgcn_sched_barrier(0);                                                \
+    DCI_MFMA_G(FC, 1, 0);                                                             \
+    DCI_DS_READ_A2(FN.a[1][0], FN.a[1][1], la0, la1, (((U) + 1) % 3) * ST + 1 * 2048); \
+    __builtin_amdgcn_sched_barrier(0);                                                \
+    DCI_MFMA_G(FC, 1, 1);                                                             \
+    DCI_DS_READ_A2(FN.a[2][0], FN.a[2][1], la0, la1, (((U) + 1) % 3) * ST + 2 * 2048); \
+    __builtin_amdgcn_sched_barrier(0);                                                \
+    DCI_MFMA_G(FC, 1, 2);                                                             \
+    DCI_DS_READ_B4(FN.b[0], FN.b[1], FN.b[2], FN.b[3], lb0, ((((U) + 1) % 3) * ST + kWideABytes) / 256); \
+    __builtin_amdgcn_sched_barrier(0);                                                \
+    DCI_MFMA_G(FC, 1, 3);                                                             \
+  } while (0)
+
+    if (n > 0) {
+      FragW fa, fb;
+      if (n > 0) DCI_ISSUE(0, 0);
+      if (n > 1) DCI_ISSUE(1, 1);
+      if (n > 2) DCI_ISSUE(2, 2);
+      if (n >= NS) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPW * (NS - 1)) : "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      DCI_READ(fa, 0);
+      int i = 0;
+      for (; i + 5 + NS < n; i += 6) {  // i % 6 == 0: slab i+u sits in stage u % 3, all indices are valid slabs
+        DCI_STEP(fa, fb, i, 0);
+        DCI_STEP(fb, fa, i + 1, 1);
+        DCI_STEP(fa, fb, i + 2, 2);
+        DCI_STEP(fb, fa, i + 3, 3);
+        DCI_STEP(fa, fb, i + 4, 4);
+        DCI_STEP(fb, fa, i + 5, 5);
+      }
+      // drain (at most eight slabs): stage chosen at run time, every wait is for everything
+      for (; i + 1 < n; ++i) {
+        DCI_WAIT_FRAG(fa, 0);
+        __builtin_amdgcn_s_barrier();
+        if (i + NS < n) {
+          const int st_ = i % NS;
+          if (st_ == 0) DCI_ISSUE(i + NS, 0);
+          else if (st_ == 1) DCI_ISSUE(i + NS, 1);
+          else DCI_ISSUE(i + NS, 2);
+        }
+        const int sn_ = (i + 1) % NS;
+        if (sn_ == 0) DCI_READ(fb, 0);
+        else if (sn_ == 1) DCI_READ(fb, 1);
+        else DCI_READ(fb, 2);
+        DCI_MFMA_SLAB(fa);
+        fa = fb;
+      }
+      DCI_WAIT_FRAG(fa, 0);
+      DCI_MFMA_SLAB(fa);
+    }
+    if (k_tail > 0) {
+      // the last k_tail columns of each operand: masked loads through registers into stage 0
+      const int n_ops = a.single ? 1 : 2;
+      for (int o = 0; o < n_ops; ++o) {
+        const float* A = (o == 1 ? pA1 : pA0) + Sf * TK;
+        const float* W = (o == 1 ? pW1 : pW0) + (size_t)Sf * TK * N;
+        float4 va[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            v[e] = (Sf * TK + 4 * c_a + e < K)
+                       ? *reinterpret_cast<const float*>(reinterpret_cast<const char*>(A + e) + voffA[q])
+                       : 0.f;
+          va[q] = make_float4(v[0], v[1], v[2], v[3]);
+        }
+        const float4 w = (Sf * TK + krB < K) ? *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(W) + voffB)
+                                             : make_float4(0.f, 0.f, 0.f, 0.f);
+        __syncthreads();  // every wave has its fragments of the slab that used stage 0 last
+        *reinterpret_cast<float4*>(lds + wave * 1024 + lane * 16) = va[0];
+        *reinterpret_cast<float4*>(lds + ldsA1 + lane * 16) = va[1];
+        *reinterpret_cast<float4*>(lds + kWideABytes + wave * 1024 + lane * 16) = w;
+        __syncthreads();
+        FragW f;
+        DCI_READ(f, 0);
+        DCI_WAIT_FRAG(f, 0);
+        DCI_MFMA_SLAB(f);
+      }
+    }
+#pragma unroll
+    for (int rb = 0; rb < 3; ++rb) {
+      if (rb < rw) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const long long row = row0 + (wr * rw0 + rb) * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+          if (row < M) {
+            float v = acc[rb][r] + bias;
+            if (a.relu) v = v > 0.f ? v : 0.f;
+            a.y[row * N + col] = v;
+          }
+        }
+      }
+    }
+    __syncthreads();  // the next pass refills the stages
+  }
+#undef DCI_SLAB_PTRS
+#undef DCI_LOAD_A0
+#undef DCI_LOAD_A1
+#undef DCI_LOAD_B
+#undef DCI_ISSUE
+#undef DCI_READ
+#undef DCI_MFMA_G
+#undef DCI_MFMA_SLAB
+#undef DCI_STEP
+}
+
 struct SageWs {
   float* m;
   float* y[2];
@@ -359,9 +655,20 @@ int32_t dci_gnn_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_i
     else if (D % 2 == 0 && aligned(x, 8) && aligned(ws.m, 8)) va = 2;
     const int vb = (Do % 4 == 0 && aligned(la.w_self, 16) && aligned(w_neigh[l], 16)) ? 4 : 1;
     dim3 grid((unsigned)n_blocks);
+    // wide kernel: 128-column tiles, 16-byte global->LDS loads (rows at least 8-byte aligned, weights
+    // 16-byte aligned), one workgroup per compute unit; worth it once there are a few thousand rows
+    const int n_tiles_w = Do / kWideCols;
+    const int g_n = n_tiles_w > 0 ? (ctx->num_cus / 8 / n_tiles_w) * 8 : 0;
+    const bool wide_ok = Do % kWideCols == 0 && D % 2 == 0 && g_n >= 8 && vb == 4 && aligned(x, 8) &&
+                         aligned(ws.m, 8) && aligned(bias[l], 4);
+    const bool use_wide = wide_ok && ctx->linear_kernel != 1 && (ctx->linear_kernel == 2 || cap >= kWideMinRows);
     {
       Timed timed(ctx, l == 0 ? DCI_K_LINEAR_IN : DCI_K_LINEAR);
-      if (va == 4 && vb == 4)
+      if (use_wide) {
+        la.n_tiles_n = n_tiles_w;
+        hipLaunchKernelGGL(k_sage_linear_wide, dim3((unsigned)(g_n * n_tiles_w)), dim3(kWideThreads), 0, ctx->stream,
+                           la, g_n);
+      } else if (va == 4 && vb == 4)
         hipLaunchKernelGGL((k_sage_linear<4, 4>), grid, dim3(kGemmThreads), 0, ctx->stream, la);
       else if (va == 4)
         hipLaunchKernelGGL((k_sage_linear<4, 1>), grid, dim3(kGemmThreads), 0, ctx->stream, la);

@@ -313,6 +313,82 @@ def test_gnn_forward_with_empty_rows(env, small_graphs, model):
     _logit_check(logits[:len(seeds)].cpu().numpy(), want)
 
 
+def _forward_case(env, dims, fanouts, n_seeds, model, option, batch=3, rng_seed=8):
+    dci, gu, ctx, g, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "graph", "tiny", "w"))
+    seeds = tiny["seeds"][:n_seeds]
+    want_blk = oracle.sample_khop(tiny["indptr"], tiny["indices"], seeds, batch, fanouts, rng_seed)
+    blk = dci.Blocks(ctx, w.num_nodes, n_seeds, fanouts)
+    dci.dci_sample_khop(ctx, g, None, gu.dev(seeds), batch, fanouts, rng_seed, blk)
+    feat = synth.features(w.num_nodes, dims[0], 61)
+    ws, wn, bs = synth.sage_weights(dims, 62)
+    x = feat[want_blk.nodes]
+    want = oracle.gnn_forward(model, want_blk, x, ws, wn, bs)
+    x_dev = torch.zeros(blk.cap_nodes[-1], dims[0], dtype=torch.float32, device="cuda")
+    x_dev[:len(x)] = torch.from_numpy(x).cuda()
+    logits = torch.full((blk.cap_nodes[0], dims[-1]), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, option)
+    try:
+        dci.dci_gnn_forward(ctx, blk, x_dev, model, [gu.dev(a) for a in ws], [gu.dev(a) for a in wn],
+                            [gu.dev(a) for a in bs], logits)
+        ctx.sync()
+    finally:
+        ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, 0)
+    _logit_check(logits[:n_seeds].cpu().numpy(), want)
+    return [int(v) for v in want_blk.n_nodes]
+
+
+@pytest.mark.parametrize("model", [0, 2])
+@pytest.mark.parametrize("dims,fanouts,n_seeds", [((602, 256, 128), (3, 4), 70), ((100, 128, 256, 47), (2, 3, 4), 33),
+                                                  ((8, 128), (7,), 129), ((16, 128), (5,), 1), ((48, 128, 128), (5, 5), 300),
+                                                  ((256, 512, 384), (10, 25), 40)])
+def test_wide_linear_kernel_matches_oracle(env, model, dims, fanouts, n_seeds):
+    """The wide dense-layer kernel forced on at small sizes: input widths with and without a k tail (602, 100, 8),
+    fewer k-slabs than pipeline stages (8, 16, 48), one to four column tiles, both operand counts."""
+    _forward_case(env, dims, fanouts, n_seeds, model, option=2)
+
+
+@pytest.mark.parametrize("option", [0, 1])
+def test_forward_many_rows(env, option):
+    """A layer tall enough for the default choice to take the wide kernel with several row blocks per workgroup
+    (option 0), against the same through the tile kernel (option 1)."""
+    n_nodes = _forward_case(env, (64, 256, 128, 16), (8, 8, 8), 2048, 0, option)
+    assert n_nodes[2] > 4096      # more than one 32-row block for each of the 128 workgroups of a column tile
+
+
+def test_wide_linear_kernel_in_several_passes(env):
+    """More than six 32-row blocks per workgroup: 60,000 rows through one 128-column tile over 256 workgroups.
+    The block has no edges, so the layer is x W_self + b; the neighbour operand (all zeros) still takes the same path."""
+    dci, gu, ctx = env["dci"], env["gu"], env["ctx"]
+    M, K, N = 60000, 40, 128
+    blk = dci.Blocks(ctx, 10**6, M, (1,))
+    assert blk.cap_nodes[0] >= M
+    blk.counts.zero_()
+    blk.counts[0] = M
+    blk.counts[1] = M
+    blk.blk_indptr[0].zero_()
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((M, K), dtype=np.float32)
+    ws, wn, bs = synth.sage_weights((K, N), 63)
+    want_blk = oracle.Blocks(n_nodes=np.array([M, M]), n_edges=np.array([0]), nodes=np.arange(M, dtype=np.int64),
+                             blk_indptr=[np.zeros(M + 1, dtype=np.int64)], blk_src=[np.zeros(0, dtype=np.int32)],
+                             src_global=[np.zeros(0, dtype=np.int64)], src_pos=[np.zeros(0, dtype=np.int64)])
+    want = oracle.gnn_forward(0, want_blk, x, ws, wn, bs)
+    x_dev = torch.zeros(blk.cap_nodes[1], K, dtype=torch.float32, device="cuda")
+    x_dev[:M] = torch.from_numpy(x).cuda()
+    logits = torch.full((blk.cap_nodes[0], N), float("nan"), dtype=torch.float32, device="cuda")
+    dci.dci_sage_forward(ctx, blk, x_dev, [gu.dev(a) for a in ws], [gu.dev(a) for a in wn], [gu.dev(a) for a in bs], logits)
+    ctx.sync()
+    _logit_check(logits[:M].cpu().numpy(), want)
+
+
+def test_set_option_rejects_bad_values(env):
+    dci, ctx = env["dci"], env["ctx"]
+    with pytest.raises(dci.DciError):
+        ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, 3)
+    with pytest.raises(dci.DciError):
+        ctx.set_option(99, 0)
+
+
 def test_gnn_forward_rejects_bad_arguments(env):
     dci, gu, ctx, g, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "graph", "tiny", "w"))
     blk = dci.Blocks(ctx, w.num_nodes, 8, (2,))
