@@ -144,6 +144,10 @@ const char* dci_last_error(const dci_ctx* ctx);
  *       1  always the 64x64 tile kernel
  *       2  the wide kernel whenever width and alignment allow it, whatever the row count */
 #define DCI_OPT_LINEAR_KERNEL 1
+/*   DCI_OPT_LINEAR_SPLIT   upper limit on the workgroups that share one output tile of the 64x64 kernel
+ *       (the contraction is split between them and a second kernel adds the partial sums in a fixed order):
+ *       0  by shape (default): layers with few tiles are split up to 8 ways;  1  never split;  n <= 8  at most n */
+#define DCI_OPT_LINEAR_SPLIT 2
 int32_t dci_set_option(dci_ctx* ctx, int32_t option, int64_t value);
 
 /* Kernel timing, for benchmarks and profiles.  Kernel classes whose bit is set in class_mask are

@@ -312,6 +312,7 @@ def dci_gather_features(ctx: Context, graph: Graph, cache: Optional[Cache], node
 
 DCI_MODEL_SAGE_MEAN, DCI_MODEL_SAGE_SUM, DCI_MODEL_GCN_AVG = 0, 1, 2
 DCI_OPT_LINEAR_KERNEL = 1
+DCI_OPT_LINEAR_SPLIT = 2
 
 
 def dci_sage_forward(ctx: Context, blocks: Blocks, x_in: torch.Tensor, w_self: Sequence[torch.Tensor],

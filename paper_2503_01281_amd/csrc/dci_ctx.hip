@@ -127,6 +127,11 @@ int32_t dci_set_option(dci_ctx* ctx, int32_t option, int64_t value) {
     ctx->linear_kernel = (int)value;
     return DCI_OK;
   }
+  if (option == DCI_OPT_LINEAR_SPLIT) {
+    if (value < 0 || value > 8) return dci::fail(ctx, DCI_ERR_INVALID_ARG, "DCI_OPT_LINEAR_SPLIT takes 0..8, not %lld", (long long)value);
+    ctx->linear_split = (int)value;
+    return DCI_OK;
+  }
   return dci::fail(ctx, DCI_ERR_INVALID_ARG, "unknown option %d", option);
 }
 

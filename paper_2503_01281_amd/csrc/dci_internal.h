@@ -24,6 +24,7 @@ struct dci_ctx {
   hipEvent_t* t_events = nullptr;  // 2 * DCI_TIMING_MAX_LAUNCHES, created on first enable
   int8_t* t_class = nullptr;
   int t_used = 0;
+  int linear_split = 0;   // DCI_OPT_LINEAR_SPLIT: 0 = by shape, n = at most n workgroups per tile
   int linear_kernel = 0;  // DCI_OPT_LINEAR_KERNEL: 0 by shape, 1 tile kernel, 2 wide kernel where the shape allows
 };
 

@@ -112,6 +112,11 @@ struct LinearArgs {
   int K, N, relu;
   int n_tiles_n;
   int single;  // 1: only the (a_neigh, w_neigh) pair is used (GCN)
+  // split of the contraction over several workgroups per tile (tile kernel only; 1 = no split)
+  int split;            // workgroups per tile
+  int n_tiles;          // tiles in the launch (= workgroups / split)
+  long long part_rows;  // row capacity of one partial-sum plane
+  float* part;          // [split][part_rows][N] partial sums
 };
 
 // VA: floats per global access along K for the activations (needs K % VA == 0 and aligned bases)
@@ -121,7 +126,8 @@ __global__ __launch_bounds__(kGemmThreads, 6) void k_sage_linear(LinearArgs a) {
   __shared__ __attribute__((aligned(16))) float As[2][TK][TM + LDS_PAD];
   __shared__ __attribute__((aligned(16))) float Bs[2][TK][TN + LDS_PAD];
   const long long M = a.counts[a.hop];
-  const int id = (int)blockIdx.x;
+  // workgroup -> (tile, part of the contraction); the parts of a tile are n_tiles apart, so they keep its XCD
+  const int id = (int)blockIdx.x % a.n_tiles, part_id = (int)blockIdx.x / a.n_tiles;
   const int xcd = id & 7, j = id >> 3;
   const int nt = j % a.n_tiles_n;
   const long long row0 = ((long long)(j / a.n_tiles_n) * 8 + xcd) * TM;
@@ -134,6 +140,9 @@ __global__ __launch_bounds__(kGemmThreads, 6) void k_sage_linear(LinearArgs a) {
   // the slab loop is unrolled by two; with a single operand pair an odd slab count is rounded up
   // by one slab that lies wholly beyond K and therefore loads zeros
   const int n_kt = a.single ? (kt_per_src + 1) / 2 * 2 : 2 * kt_per_src;
+  // this workgroup's slabs [kt_lo, kt_hi), in whole pairs (the host keeps split <= n_kt / 2)
+  const int kt_lo = (int)((long long)(n_kt / 2) * part_id / a.split) * 2;
+  const int kt_hi = (int)((long long)(n_kt / 2) * (part_id + 1) / a.split) * 2;
 
   // two accumulators (even / odd k pairs) so that consecutive matrix instructions are independent
   floatx16 acc, acc1;
@@ -211,22 +220,36 @@ __global__ __launch_bounds__(kGemmThreads, 6) void k_sage_linear(LinearArgs a) {
   // LDS buffer, slab kt+1 sits in registers on its way to the other buffer and the global loads
   // of slab kt+2 are already in flight, so a slab has two iterations to arrive.
   float ra0[kPer], rb0[kPer], ra1[kPer], rb1[kPer];
-  load_slab(0, ra0, rb0);
-  load_slab(1, ra1, rb1);
+  load_slab(kt_lo, ra0, rb0);
+  load_slab(kt_lo + 1, ra1, rb1);
   store_slab(0, ra0, rb0);
   __syncthreads();
-  for (int kt = 0; kt < n_kt; kt += 2) {
-    if (kt + 2 < n_kt) load_slab(kt + 2, ra0, rb0);
+  for (int kt = kt_lo; kt < kt_hi; kt += 2) {
+    if (kt + 2 < kt_hi) load_slab(kt + 2, ra0, rb0);
     compute(0);
     store_slab(1, ra1, rb1);
     __syncthreads();
-    if (kt + 3 < n_kt) load_slab(kt + 3, ra1, rb1);
+    if (kt + 3 < kt_hi) load_slab(kt + 3, ra1, rb1);
     compute(1);
-    if (kt + 2 < n_kt) store_slab(0, ra0, rb0);
+    if (kt + 2 < kt_hi) store_slab(0, ra0, rb0);
     __syncthreads();
   }
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] += acc1[r];
+
+  if (a.split > 1) {
+    // partial sums go to this part's plane; k_split_reduce adds the planes in plane order
+    const int col = col0 + bn;
+    if (col < N) {
+      float* plane = a.part + (size_t)part_id * a.part_rows * N;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const long long row = row0 + wm * 32 + 8 * (r >> 2) + 4 * kh + (r & 3);
+        if (row < M) plane[row * N + col] = acc[r];
+      }
+    }
+    return;
+  }
 
   // accumulator layout of the 32x32 tile: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4,
   // column l%32.
@@ -242,6 +265,20 @@ __global__ __launch_bounds__(kGemmThreads, 6) void k_sage_linear(LinearArgs a) {
         a.y[row * N + col] = v;
       }
     }
+  }
+}
+
+// y = [relu](bias + sum over the planes, in plane order) for the rows in use
+__global__ __launch_bounds__(256) void k_split_reduce(LinearArgs a) {
+  const long long M = a.counts[a.hop];
+  const long long total = M * a.N;
+  const size_t plane = (size_t)a.part_rows * a.N;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    float v = 0.f;
+    for (int p = 0; p < a.split; ++p) v += a.part[p * plane + i];
+    v += a.bias[i % a.N];
+    if (a.relu) v = v > 0.f ? v : 0.f;
+    a.y[i] = v;
   }
 }
 
@@ -274,7 +311,7 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-constexpr long long kWideMinRows = 2048;  // below this capacity the 64x64 kernel fills the chip better
+constexpr long long kWideMinRows = 16384;  // below this capacity the 64x64 kernel (with its split contraction) fills the chip better
 constexpr int kWideThreads = 512, kWideCols = 128, kWideStages = 3, kWideMaxBlocks = 6;
 constexpr int kWideABytes = kWideMaxBlocks * 32 * 64;           // 192 rows x 16 k x 4 B
 constexpr int kWideBBytes = TK * kWideCols * 4;                 // 16 k x 128 columns x 4 B
@@ -309,6 +346,8 @@ struct FragW {
                       "+v"(f.a[2][1]), "+v"(f.b[0]), "+v"(f.b[1]), "+v"(f.b[2]), "+v"(f.b[3])::"memory");            \
   } while (0)
 
+// kInputLayer only gives the first layer's launches a kernel name of their own in traces; the code is the same.
+template <bool kInputLayer>
 __global__ __launch_bounds__(kWideThreads, 1) void k_sage_linear_wide(LinearArgs a, int g_n) {
   constexpr int NS = kWideStages, ST = kWideStageBytes, LPW = 3;  // LPW: global->LDS loads per wave and slab
   __shared__ __attribute__((aligned(1024))) char lds[kWideLdsBytes];
@@ -544,19 +583,45 @@ __global__ __launch_bounds__(kWideThreads, 1) void k_sage_linear_wide(LinearArgs
 struct SageWs {
   float* m;
   float* y[2];
+  float* part;         // partial sums of split dense layers
 };
 
+// How many workgroups share a tile of the 64x64 kernel: a layer with fewer tiles than compute units
+// (small batches, narrow outputs) would walk the whole contraction in a handful of workgroups while
+// the rest of the chip idles, so the contraction is cut into enough parts to put one workgroup on
+// every compute unit.  More parts than that gain nothing: the kernel is bound by instruction issue,
+// not by the latency of its slab chain.  tiles = launch size for the capacity, pairs = slab pairs.
+constexpr int kSplitMaxTiles = 1024;  // no split beyond this many tiles (bounds the partial-sum planes)
+static int split_for(int64_t tiles, int pairs, int num_cus) {
+  if (tiles > kSplitMaxTiles) return 1;
+  int64_t s = num_cus / tiles;
+  if (s > 8) s = 8;
+  if (s > pairs / 2) s = pairs / 2;  // at least two slab pairs per workgroup
+  return s < 1 ? 1 : (int)s;
+}
+
+constexpr int kMaxCus = 304;  // upper bound used when sizing the workspace without a device at hand
+
+static int64_t tile_rows8(int64_t cap) { return ((cap + TM - 1) / TM + 7) / 8 * 8; }
+
 static void carve_sage_ws(Arena& ar, const int64_t* cap_rows, int32_t n_layers, const int32_t* dims, SageWs* ws) {
-  size_t max_m = 1, max_y = 1;
+  size_t max_m = 1, max_y = 1, max_part = 1;
   for (int32_t l = 0; l < n_layers; ++l) {
     const int32_t h = n_layers - 1 - l;
     const size_t rows = (size_t)(cap_rows[h] > 0 ? cap_rows[h] : 1);
     if (rows * (size_t)dims[l] > max_m) max_m = rows * (size_t)dims[l];
     if (l != n_layers - 1 && rows * (size_t)dims[l + 1] > max_y) max_y = rows * (size_t)dims[l + 1];
+    const int64_t tiles = tile_rows8((int64_t)rows) * ((dims[l + 1] + TN - 1) / TN);
+    const int split = split_for(tiles, (dims[l] + TK - 1) / TK, kMaxCus);  // pairs of the two-operand layer; GCN has fewer and splits less
+    if (split > 1) {
+      const size_t need = (size_t)split * (size_t)tile_rows8((int64_t)rows) * TM * (size_t)dims[l + 1];
+      if (need > max_part) max_part = need;
+    }
   }
   ws->m = ar.take<float>(max_m);
   ws->y[0] = ar.take<float>(max_y);
   ws->y[1] = ar.take<float>(max_y);
+  ws->part = ar.take<float>(max_part);
 }
 
 }  // namespace dci
@@ -647,14 +712,21 @@ int32_t dci_gnn_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_i
     la.N = Do;
     la.relu = l != n_layers - 1;
     la.n_tiles_n = (Do + TN - 1) / TN;
-    const int64_t m_tiles8 = ((cap + TM - 1) / TM + 7) / 8 * 8;  // row tiles, rounded up to whole XCD rounds
-    const int64_t n_blocks = m_tiles8 * la.n_tiles_n;
+    const int64_t m_tiles8 = tile_rows8(cap);  // row tiles, rounded up to whole XCD rounds
+    const int64_t n_tiles = m_tiles8 * la.n_tiles_n;
+    const int n_pairs = gcn ? ((D + TK - 1) / TK + 1) / 2 : (D + TK - 1) / TK;
+    la.split = split_for(n_tiles, n_pairs, ctx->num_cus < kMaxCus ? ctx->num_cus : kMaxCus);
+    if (ctx->linear_split > 0 && ctx->linear_split <= la.split) la.split = ctx->linear_split;
+    la.n_tiles = (int)n_tiles;
+    la.part_rows = m_tiles8 * TM;
+    la.part = ws.part;
+    const int64_t n_blocks = n_tiles * la.split;
     if (n_blocks >= ((int64_t)1 << 31)) return fail(ctx, DCI_ERR_UNSUPPORTED, "sage_forward: too many tiles");
     int va = 1;
     if (D % 4 == 0 && aligned(x, 16) && aligned(ws.m, 16)) va = 4;
     else if (D % 2 == 0 && aligned(x, 8) && aligned(ws.m, 8)) va = 2;
     const int vb = (Do % 4 == 0 && aligned(la.w_self, 16) && aligned(w_neigh[l], 16)) ? 4 : 1;
-    dim3 grid((unsigned)n_blocks);
+    dim3 grid((unsigned)n_blocks);  // tile kernel: tiles x parts of the contraction
     // wide kernel: 128-column tiles, 16-byte global->LDS loads (rows at least 8-byte aligned, weights
     // 16-byte aligned), one workgroup per compute unit; worth it once there are a few thousand rows
     const int n_tiles_w = Do / kWideCols;
@@ -666,8 +738,12 @@ int32_t dci_gnn_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_i
       Timed timed(ctx, l == 0 ? DCI_K_LINEAR_IN : DCI_K_LINEAR);
       if (use_wide) {
         la.n_tiles_n = n_tiles_w;
-        hipLaunchKernelGGL(k_sage_linear_wide, dim3((unsigned)(g_n * n_tiles_w)), dim3(kWideThreads), 0, ctx->stream,
-                           la, g_n);
+        if (l == 0)
+          hipLaunchKernelGGL(k_sage_linear_wide<true>, dim3((unsigned)(g_n * n_tiles_w)), dim3(kWideThreads), 0,
+                             ctx->stream, la, g_n);
+        else
+          hipLaunchKernelGGL(k_sage_linear_wide<false>, dim3((unsigned)(g_n * n_tiles_w)), dim3(kWideThreads), 0,
+                             ctx->stream, la, g_n);
       } else if (va == 4 && vb == 4)
         hipLaunchKernelGGL((k_sage_linear<4, 4>), grid, dim3(kGemmThreads), 0, ctx->stream, la);
       else if (va == 4)
@@ -680,6 +756,11 @@ int32_t dci_gnn_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_i
         hipLaunchKernelGGL((k_sage_linear<1, 4>), grid, dim3(kGemmThreads), 0, ctx->stream, la);
       else
         hipLaunchKernelGGL((k_sage_linear<1, 1>), grid, dim3(kGemmThreads), 0, ctx->stream, la);
+      if (!use_wide && la.split > 1) {
+        int64_t rb = (cap * Do + 255) / 256;
+        if (rb > (int64_t)ctx->num_cus * 8) rb = (int64_t)ctx->num_cus * 8;
+        hipLaunchKernelGGL(k_split_reduce, dim3((unsigned)rb), dim3(256), 0, ctx->stream, la);
+      }
     }
     DCI_LAUNCH_CHECK(ctx);
     x = y;

@@ -381,10 +381,26 @@ def test_wide_linear_kernel_in_several_passes(env):
     _logit_check(logits[:M].cpu().numpy(), want)
 
 
+@pytest.mark.parametrize("split", [1, 2, 0])
+def test_split_contraction_matches_oracle(env, split):
+    """Few tiles: by default (0) the 64x64 kernel shares each tile between up to eight workgroups and a second
+    kernel adds their partial sums; 1 switches that off, 2 limits it to two."""
+    dci, ctx = env["dci"], env["ctx"]
+    ctx.set_option(dci.DCI_OPT_LINEAR_SPLIT, split)
+    try:
+        for model in (0, 2):
+            _forward_case(env, (602, 256, 41), (3, 4), 70, model, option=1)
+            _forward_case(env, (100, 130, 47), (5, 5), 256, model, option=1)
+    finally:
+        ctx.set_option(dci.DCI_OPT_LINEAR_SPLIT, 0)
+
+
 def test_set_option_rejects_bad_values(env):
     dci, ctx = env["dci"], env["ctx"]
     with pytest.raises(dci.DciError):
         ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, 3)
+    with pytest.raises(dci.DciError):
+        ctx.set_option(dci.DCI_OPT_LINEAR_SPLIT, 9)
     with pytest.raises(dci.DciError):
         ctx.set_option(99, 0)
 
