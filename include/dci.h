@@ -138,9 +138,9 @@ const char* dci_last_error(const dci_ctx* ctx);
  * in the order of the floating-point sums).  DCI_ERR_INVALID_ARG for an unknown option or value.
  *   DCI_OPT_LINEAR_KERNEL  which dense-layer kernel dci_sage_forward / dci_gnn_forward launch:
  *       0  by shape (default): the wide kernel (128-column tiles, one workgroup per compute unit)
- *          when the layer is at least 2048 rows tall by capacity, its output width is a multiple
- *          of 128, its input width is even and the operands are suitably aligned; else the 64x64
- *          tile kernel
+ *          when the layer is at least 16384 rows tall by capacity, its input width is even and
+ *          at least 160, its output width is a multiple of 128 and the operands are suitably
+ *          aligned; else the 64x64 tile kernel
  *       1  always the 64x64 tile kernel
  *       2  the wide kernel whenever width and alignment allow it, whatever the row count */
 #define DCI_OPT_LINEAR_KERNEL 1

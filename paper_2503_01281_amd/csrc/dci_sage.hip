@@ -312,6 +312,7 @@ typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
 constexpr long long kWideMinRows = 16384;  // below this capacity the 64x64 kernel (with its split contraction) fills the chip better
+constexpr int kWideMinWidth = 160;  // narrower inputs spend the kernel in its pipeline fill and drain (measured cross-over)
 constexpr int kWideThreads = 512, kWideCols = 128, kWideStages = 3, kWideMaxBlocks = 6;
 constexpr int kWideABytes = kWideMaxBlocks * 32 * 64;           // 192 rows x 16 k x 4 B
 constexpr int kWideBBytes = TK * kWideCols * 4;                 // 16 k x 128 columns x 4 B
@@ -733,7 +734,7 @@ int32_t dci_gnn_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_i
     const int g_n = n_tiles_w > 0 ? (ctx->num_cus / 8 / n_tiles_w) * 8 : 0;
     const bool wide_ok = Do % kWideCols == 0 && D % 2 == 0 && g_n >= 8 && vb == 4 && aligned(x, 8) &&
                          aligned(ws.m, 8) && aligned(bias[l], 4);
-    const bool use_wide = wide_ok && ctx->linear_kernel != 1 && (ctx->linear_kernel == 2 || cap >= kWideMinRows);
+    const bool use_wide = wide_ok && ctx->linear_kernel != 1 && (ctx->linear_kernel == 2 || (cap >= kWideMinRows && D >= kWideMinWidth));
     {
       Timed timed(ctx, l == 0 ? DCI_K_LINEAR_IN : DCI_K_LINEAR);
       if (use_wide) {

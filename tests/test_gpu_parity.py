@@ -351,7 +351,7 @@ def test_wide_linear_kernel_matches_oracle(env, model, dims, fanouts, n_seeds):
 def test_forward_many_rows(env, option):
     """A layer tall enough for the default choice to take the wide kernel with several row blocks per workgroup
     (option 0), against the same through the tile kernel (option 1)."""
-    n_nodes = _forward_case(env, (64, 256, 128, 16), (8, 8, 8), 2048, 0, option)
+    n_nodes = _forward_case(env, (192, 256, 128, 16), (8, 8, 8), 2048, 0, option)
     assert n_nodes[2] > 4096      # more than one 32-row block for each of the 128 workgroups of a column tile
 
 
