@@ -59,8 +59,11 @@ def _load():
         lib.oracle_gather.restype = None
         lib.oracle_gather_cached.argtypes = [_P, c.c_int32, _P, _P, _P, c.c_int64, _P, _P]
         lib.oracle_gather_cached.restype = None
-        lib.oracle_sample_hop_cached.argtypes = [_P, _P, _P, _P, _P, _P, c.c_int64, c.c_uint64, c.c_int32,
-                                                 c.c_int32, c.c_uint64, _P, _P, _P]
+        lib.oracle_sample_hop_cached.argtypes = [_P, _P, _P, _P, _P, c.c_int64, c.c_int64, _P, c.c_int64,
+                                                 c.c_uint64, c.c_int32, c.c_int32, c.c_uint64, _P, _P, _P]
+        lib.oracle_fill_adj_element.argtypes = [c.c_int64, _P, _P, _P, c.c_uint64, _P, _P, c.c_int64, _P,
+                                                c.c_int64, _P, _P, _P, _P]
+        lib.oracle_fill_adj_element.restype = c.c_int32
         lib.oracle_sample_hop_cached.restype = c.c_int32
         lib.oracle_sage_forward.argtypes = [c.c_int32, _P, _P, _P, _P, _P, _P, _P, _P, _P]
         lib.oracle_sage_forward.restype = None
@@ -238,9 +241,34 @@ def gather_cached(feat, feat_remap, feat_cache, ids):
     return out, int(counts[0]), int(counts[1])
 
 
+def fill_adj_element(indptr, indices, edge_count, C_adj: int):
+    """Element-granular fill.  Returns (adj_remap[N] int32, c_indptr[K+1], c_indices[M], indices_reordered[E],
+    partial_node, partial_deg); the input `indices` is left untouched."""
+    lib = _load()
+    indptr = _i64(indptr)
+    idx = _i64(indices).copy()
+    ec = np.ascontiguousarray(edge_count, dtype=np.uint32)
+    N = len(indptr) - 1
+    remap = np.empty(N, dtype=np.int32)
+    K, M, pn, pd = c.c_int64(0), c.c_int64(0), c.c_int64(0), c.c_int64(0)
+    work = idx.copy()
+    rc = lib.oracle_fill_adj_element(N, indptr.ctypes.data, work.ctypes.data, ec.ctypes.data, C_adj,
+                                     remap.ctypes.data, None, 0, None, 0, c.byref(K), c.byref(M), c.byref(pn),
+                                     c.byref(pd))
+    assert rc == 0
+    cp = np.zeros(K.value + 1, dtype=np.int64)
+    ci = np.zeros(max(M.value, 1), dtype=np.int64)
+    rc = lib.oracle_fill_adj_element(N, indptr.ctypes.data, idx.ctypes.data, ec.ctypes.data, C_adj,
+                                     remap.ctypes.data, cp.ctypes.data, K.value, ci.ctypes.data, M.value,
+                                     c.byref(K), c.byref(M), c.byref(pn), c.byref(pd))
+    assert rc == 0
+    return remap, cp, ci[:M.value], idx, int(pn.value), int(pd.value)
+
+
 def sample_hop_cached(indptr, indices, adj_remap, c_indptr, c_indices, frontier, batch_index: int, hop: int,
-                      fanout: int, rng_seed: int):
-    """Returns (row_count[n], src_global[sum], counts[4] = node hits, node misses, edge hits, edge misses)."""
+                      fanout: int, rng_seed: int, partial_node: int = -1, partial_deg: int = 0):
+    """Returns (row_count[n], src_global[sum], counts[4] = nodes with a slot, without, positions from the cache,
+    from the host)."""
     indptr, indices, frontier = _i64(indptr), _i64(indices), _i64(frontier)
     c_indptr, c_indices = _i64(c_indptr), _i64(c_indices)
     remap = _i32(adj_remap)
@@ -249,9 +277,9 @@ def sample_hop_cached(indptr, indices, adj_remap, c_indptr, c_indices, frontier,
     src = np.zeros(max(n * fanout, 1), dtype=np.int64)
     counts = np.zeros(4, dtype=np.int64)
     _load().oracle_sample_hop_cached(indptr.ctypes.data, indices.ctypes.data, remap.ctypes.data,
-                                     c_indptr.ctypes.data, c_indices.ctypes.data, frontier.ctypes.data, n,
-                                     batch_index, hop, fanout, rng_seed, rows.ctypes.data, src.ctypes.data,
-                                     counts.ctypes.data)
+                                     c_indptr.ctypes.data, c_indices.ctypes.data, partial_node, partial_deg,
+                                     frontier.ctypes.data, n, batch_index, hop, fanout, rng_seed, rows.ctypes.data,
+                                     src.ctypes.data, counts.ctypes.data)
     rows = rows[:n]
     return rows, src[:int(rows.sum())].copy(), counts
 

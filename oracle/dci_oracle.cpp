@@ -14,7 +14,8 @@
 //   * capacity split ............... Eq. (1);
 //   * feature-cache fill ........... Section IV-B, first paragraph ("greater than the
 //     average" first, the rest afterwards, no sort);
-//   * adjacency-cache fill ......... Algorithm 1 and Fig. 6, node-granular reading;
+//   * adjacency-cache fill ......... Algorithm 1 and Fig. 6: node-granular reading (oracle_fill_adj) and the
+//     element-granular form as printed (oracle_fill_adj_element);
 //   * feature gather ............... Section IV, framework paragraph (hit: GPU memory,
 //     miss: host memory; same row either way);
 //   * model ........................ GraphSAGE with mean aggregation (Table III family), plus the
@@ -325,6 +326,85 @@ int32_t oracle_fill_adj(int64_t N, const int64_t* indptr, const int64_t* indices
   return 0;
 }
 
+// Adjacency-cache fill, element-granular (Algorithm 1 and Fig. 6 as printed).  Inputs as above plus
+// the per-element access counts edge_count[E]; `indices` is rewritten in place.
+//   * volume <= C_adj: everything is cached verbatim and nothing is reordered (the algorithm's first branch);
+//   * otherwise node totals are the sums of the element counts; nodes are ordered by total descending
+//     (ties: ascending id); inside EVERY node the elements are reordered by their own count descending
+//     (ties: original order) - the listing's second loop, whose printed statement repeats the node sort, is
+//     read as this per-node sort (Fig. 6: node 0's elements 4, 6, 7 become 7, 6, 4);
+//   * the cache takes the longest prefix of the reorganised element stream that fits: whole nodes cost
+//     8*deg + 8 bytes each (plus 8 for the leading pointer entry), and the first node that does not fit
+//     contributes as many leading elements as the rest of the budget pays for (8 + 8*len, len >= 1).
+// The reordering is applied to the host structure too (indices, in place), so that position p of a node
+// means the same neighbour whether it is read from the cache or from the host.
+// partial_node / partial_deg: the node cached in part and its full length, or -1 / 0.
+// *K_out counts the cached slots including the partial one; c_indptr has *K_out + 1 entries.
+int32_t oracle_fill_adj_element(int64_t N, const int64_t* indptr, int64_t* indices, const uint32_t* edge_count,
+                                uint64_t C_adj, int32_t* adj_remap, int64_t* c_indptr, int64_t cap_K,
+                                int64_t* c_indices, int64_t cap_M, int64_t* K_out, int64_t* M_out,
+                                int64_t* partial_node, int64_t* partial_deg) {
+  const int64_t E = indptr[N];
+  const uint64_t volume = (uint64_t)(N + 1 + E) * 8ull;
+  std::vector<int64_t> order((size_t)N);
+  std::iota(order.begin(), order.end(), (int64_t)0);
+  int64_t K = 0, M = 0, p_node = -1, p_deg = 0, p_len = 0;
+  if (volume <= C_adj) {
+    K = N;
+    M = E;
+  } else {
+    std::vector<uint64_t> totals((size_t)N, 0);
+    for (int64_t v = 0; v < N; ++v)
+      for (int64_t e = indptr[v]; e < indptr[v + 1]; ++e) totals[(size_t)v] += edge_count[e];
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int64_t x, int64_t y) { return totals[(size_t)x] > totals[(size_t)y]; });
+    std::vector<int64_t> perm, tmp;
+    for (int64_t v = 0; v < N; ++v) {
+      const int64_t s0 = indptr[v], deg = indptr[v + 1] - s0;
+      perm.resize((size_t)deg);
+      std::iota(perm.begin(), perm.end(), (int64_t)0);
+      std::stable_sort(perm.begin(), perm.end(),
+                       [&](int64_t x, int64_t y) { return edge_count[s0 + x] > edge_count[s0 + y]; });
+      tmp.assign(indices + s0, indices + s0 + deg);
+      for (int64_t t = 0; t < deg; ++t) indices[s0 + t] = tmp[(size_t)perm[(size_t)t]];
+    }
+    uint64_t used = 8;
+    while (K < N) {
+      const int64_t v = order[(size_t)K];
+      const uint64_t cost = 8ull * (uint64_t)(indptr[v + 1] - indptr[v]) + 8ull;
+      if (used + cost > C_adj) break;
+      used += cost;
+      M += indptr[v + 1] - indptr[v];
+      ++K;
+    }
+    if (C_adj < 8) K = 0;
+    if (K < N && C_adj >= 8 && C_adj - used >= 16) {
+      p_node = order[(size_t)K];
+      p_deg = indptr[p_node + 1] - indptr[p_node];
+      p_len = (int64_t)((C_adj - used - 8) / 8);  // < p_deg, because the whole node did not fit
+      M += p_len;
+      ++K;
+    }
+  }
+  *K_out = K;
+  *M_out = M;
+  *partial_node = p_node;
+  *partial_deg = p_deg;
+  for (int64_t v = 0; v < N; ++v) adj_remap[v] = -1;
+  for (int64_t s = 0; s < K; ++s) adj_remap[order[(size_t)s]] = (int32_t)s;
+  if (!c_indptr || !c_indices) return 0;
+  if (K > cap_K || M > cap_M) return -2;
+  int64_t at = 0;
+  c_indptr[0] = 0;
+  for (int64_t s = 0; s < K; ++s) {
+    const int64_t v = order[(size_t)s];
+    const int64_t len = v == p_node ? p_len : indptr[v + 1] - indptr[v];
+    for (int64_t e = indptr[v]; e < indptr[v] + len; ++e) c_indices[at++] = indices[e];
+    c_indptr[s + 1] = at;
+  }
+  return 0;
+}
+
 // out[i,:] = feat[ids[i],:]
 void oracle_gather(const float* feat, int32_t F, const int64_t* ids, int64_t n, float* out) {
   for (int64_t i = 0; i < n; ++i)
@@ -344,29 +424,34 @@ void oracle_gather_cached(const float* feat, int32_t F, const int32_t* feat_rema
   }
 }
 
-// The same sampler routed through an adjacency cache: a cached node's degree and
-// neighbours come from (c_indptr, c_indices), the others from the host CSR.  Only the
+// The same sampler routed through an adjacency cache.  A node with a slot has cached_len =
+// c_indptr[slot+1] - c_indptr[slot] leading elements of its list in the cache; its full length is
+// cached_len, except for the one node that may be cached in part (partial_node, full length
+// partial_deg; pass -1 / 0 when there is none).  Position p is a hit iff p < cached_len (Section IV-B,
+// third paragraph, 0-based) and is then read from the cache, otherwise from the host CSR.  Only the
 // frontier list and the global neighbour ids are produced; tests compare them with
-// oracle_sample_khop.  counts (nullable): [0] += node hits, [1] += node misses,
-// [2] += edge hits, [3] += edge misses.
+// oracle_sample_khop.  counts (nullable): [0] += nodes with a slot, [1] += nodes without,
+// [2] += positions read from the cache, [3] += positions read from the host.
 int32_t oracle_sample_hop_cached(const int64_t* indptr, const int64_t* indices, const int32_t* adj_remap,
-                                 const int64_t* c_indptr, const int64_t* c_indices, const int64_t* frontier,
-                                 int64_t n_frontier, uint64_t batch_index, int32_t hop, int32_t fanout,
-                                 uint64_t rng_seed, int64_t* row_count, int64_t* src_global, int64_t* counts) {
+                                 const int64_t* c_indptr, const int64_t* c_indices, int64_t partial_node,
+                                 int64_t partial_deg, const int64_t* frontier, int64_t n_frontier,
+                                 uint64_t batch_index, int32_t hop, int32_t fanout, uint64_t rng_seed,
+                                 int64_t* row_count, int64_t* src_global, int64_t* counts) {
   std::vector<int64_t> pos((size_t)std::max(fanout, 1));
   int64_t at = 0;
   for (int64_t i = 0; i < n_frontier; ++i) {
     const int64_t v = frontier[i];
     const int32_t r = adj_remap[v];
-    const int64_t* list = r >= 0 ? c_indices + c_indptr[r] : indices + indptr[v];
-    const int64_t deg = r >= 0 ? c_indptr[r + 1] - c_indptr[r] : indptr[v + 1] - indptr[v];
+    const int64_t cached_len = r >= 0 ? c_indptr[r + 1] - c_indptr[r] : 0;
+    const int64_t deg = r < 0 ? indptr[v + 1] - indptr[v] : v == partial_node ? partial_deg : cached_len;
     const int32_t c = sample_positions(rng_seed, batch_index, hop, v, deg, fanout, pos.data());
-    for (int32_t s = 0; s < c; ++s) src_global[at++] = list[pos[s]];
-    row_count[i] = c;
-    if (counts) {
-      counts[r >= 0 ? 0 : 1] += 1;
-      counts[r >= 0 ? 2 : 3] += c;
+    for (int32_t s = 0; s < c; ++s) {
+      const bool hit = pos[s] < cached_len;
+      src_global[at++] = hit ? c_indices[c_indptr[r] + pos[s]] : indices[indptr[v] + pos[s]];
+      if (counts) counts[hit ? 2 : 3] += 1;
     }
+    row_count[i] = c;
+    if (counts) counts[r >= 0 ? 0 : 1] += 1;
   }
   return 0;
 }

@@ -250,3 +250,138 @@ def test_cached_routes_return_identical_results(tiny):
     plain = oracle.gather(feat, blk.nodes)
     assert rows.tobytes() == plain.tobytes() == feat[blk.nodes].tobytes()
     assert hits == (feat_remap[blk.nodes] >= 0).sum() and hits > 0 and misses > 0
+
+
+# ---- element-granular adjacency cache (Algorithm 1 / Fig. 6 as printed) --------------------------------------
+
+def test_element_fill_worked_example():
+    """Fig. 6 narrative: node 0 (22 visits) before node 1 (12); node 0's elements 4, 6, 7 reorder to 7, 6, 4;
+    node 2 has two elements of which one is cached; position n of node 2 hits iff n <= 1 (1-based)."""
+    indptr, indices, edge_count = _read_toy()
+    # nodes 0, 3, 1 whole (88 bytes, see above) + node 2's pointer entry and one element (16 bytes)
+    remap, cp, ci, idx, pn, pd = oracle.fill_adj_element(indptr, indices, edge_count, 104)
+    assert remap.tolist() == [0, 2, 3, 1, -1, -1, -1, -1]
+    assert idx.tolist() == [7, 6, 4, 2, 5, 0, 3, 1, 2]             # every node reordered by element count
+    assert cp.tolist() == [0, 3, 5, 7, 8] and ci.tolist() == [7, 6, 4, 1, 2, 2, 5, 0]
+    assert (pn, pd) == (2, 2)
+    # the hit rule on node 2: a fan-out of 2 takes both positions; the first is served by the cache
+    rows, src, counts = oracle.sample_hop_cached(indptr, idx, remap, cp, ci, np.array([2]), 0, 0, 2, 1, pn, pd)
+    assert rows.tolist() == [2] and src.tolist() == [0, 3] and counts.tolist() == [1, 0, 1, 1]
+    # one byte less: no room for pointer entry + element of node 2 (needs 16), the slice ends with node 1
+    remap, cp, ci, idx, pn, pd = oracle.fill_adj_element(indptr, indices, edge_count, 103)
+    assert remap.tolist() == [0, 2, -1, 1, -1, -1, -1, -1] and cp.tolist() == [0, 3, 5, 7] and (pn, pd) == (-1, 0)
+    # 8 bytes short of node 1 as a whole: node 1 becomes the partial node with one of its two elements
+    remap, cp, ci, idx, pn, pd = oracle.fill_adj_element(indptr, indices, edge_count, 80)
+    assert remap.tolist() == [0, 2, -1, 1, -1, -1, -1, -1] and cp.tolist() == [0, 3, 5, 6] and ci.tolist()[-1] == 2
+    assert (pn, pd) == (1, 2)
+    # the whole structure fits: verbatim, nothing reordered
+    n = len(indptr) - 1
+    remap, cp, ci, idx, pn, pd = oracle.fill_adj_element(indptr, indices, edge_count, (n + 1 + len(indices)) * 8)
+    assert remap.tolist() == list(range(n)) and np.array_equal(ci, indices) and np.array_equal(idx, indices) and pn == -1
+
+
+def _element_fill_by_hand(indptr, indices, edge_count, C_adj):
+    """Independent restatement with Python lists and sorted()."""
+    n = len(indptr) - 1
+    lists = [list(indices[indptr[v]:indptr[v + 1]]) for v in range(n)]
+    cnts = [list(edge_count[indptr[v]:indptr[v + 1]]) for v in range(n)]
+    if (n + 1 + len(indices)) * 8 <= C_adj:
+        return list(range(n)), lists, [len(l) for l in lists], lists
+    totals = [sum(int(c) for c in cs) for cs in cnts]
+    order = sorted(range(n), key=lambda v: (-totals[v], v))
+    new_lists = []
+    for v in range(n):
+        perm = sorted(range(len(lists[v])), key=lambda t: (-int(cnts[v][t]), t))
+        new_lists.append([lists[v][t] for t in perm])
+    stream_budget = C_adj - 8
+    slots, lens = [], []
+    for v in order:
+        need = 8 + 8 * len(new_lists[v])
+        if stream_budget >= need:
+            slots.append(v); lens.append(len(new_lists[v])); stream_budget -= need
+        else:
+            if stream_budget >= 16:
+                slots.append(v); lens.append((stream_budget - 8) // 8)
+            break
+    if C_adj < 8:
+        slots, lens = [], []
+    return slots, [new_lists[v][:l] for v, l in zip(slots, lens)], lens, new_lists
+
+
+def test_element_fill_against_restatement(small_graphs):
+    rng = np.random.default_rng(21)
+    for indptr, indices in small_graphs:
+        n, e = len(indptr) - 1, len(indices)
+        for trial in range(6):
+            edge_count = (rng.integers(0, 4, e) * rng.integers(0, 2, e)).astype(np.uint32)   # many zeros and ties
+            for C_adj in [0, 7, 8, 24, 8 * (n // 2), 8 * (e // 3) + 4, 8 * e, (n + 1 + e) * 8 - 1, (n + 1 + e) * 8]:
+                remap, cp, ci, idx, pn, pd = oracle.fill_adj_element(indptr, indices, edge_count, C_adj)
+                slots, cached, lens, new_lists = _element_fill_by_hand(indptr, indices, edge_count, C_adj)
+                want_remap = -np.ones(n, dtype=np.int64)
+                for s, v in enumerate(slots):
+                    want_remap[v] = s
+                assert np.array_equal(remap, want_remap)
+                assert np.array_equal(np.diff(cp), lens) and ci.tolist() == [u for l in cached for u in l]
+                assert idx.tolist() == [u for l in new_lists for u in l]
+                partial = [v for v, l in zip(slots, lens) if l < indptr[v + 1] - indptr[v]]
+                assert ([pn] if pn >= 0 else []) == partial
+                if pn >= 0:
+                    assert pd == indptr[pn + 1] - indptr[pn]
+                # the budget is respected and used to the last whole element
+                used = 8 * (len(slots) + 1) + 8 * len(ci) if C_adj >= 8 else 0
+                assert used <= max(C_adj, 0)
+
+
+def test_element_fill_reduces_to_node_fill_when_counts_are_flat(tiny):
+    """With the same count on every element of a node the in-node order is unchanged; on a budget that ends at a
+    node boundary the element-granular cache is the node-granular one."""
+    indptr, indices = tiny["indptr"], tiny["indices"]
+    n = len(indptr) - 1
+    rng = np.random.default_rng(5)
+    per_node = rng.integers(0, 5, n).astype(np.uint32)
+    deg = np.diff(indptr)
+    edge_count = np.repeat(per_node, deg)
+    totals = (per_node.astype(np.uint64) * deg.astype(np.uint64)).astype(np.uint32)
+    remap0, cp0, ci0 = oracle.fill_adj(indptr, indices, totals, 200_000)
+    boundary = 8 * (len(cp0) + len(ci0))                      # bytes used by the node-granular cache
+    remap, cp, ci, idx, pn, pd = oracle.fill_adj_element(indptr, indices, edge_count, boundary + 15)
+    assert pn == -1 and np.array_equal(idx, indices)
+    assert np.array_equal(remap, remap0) and np.array_equal(cp, cp0) and np.array_equal(ci, ci0)
+    # sixteen more bytes buy the pointer entry and the first element of the next node
+    remap, cp, ci, idx, pn, pd = oracle.fill_adj_element(indptr, indices, edge_count, boundary + 16)
+    assert pn >= 0 and remap[pn] == len(cp0) - 1 and len(ci) == len(ci0) + 1 and ci[-1] == indices[indptr[pn]]
+
+
+def test_element_cache_is_transparent_to_sampling(tiny):
+    """Hit and miss paths return the same bytes: sampling through the element-granular cache equals sampling
+    the reordered host structure without a cache, and the hit counters follow the per-position rule."""
+    w = tiny["w"]
+    indptr, indices = tiny["indptr"], tiny["indices"]
+    _, ac, ec, _ = oracle.presample_count(indptr, indices, tiny["seeds"], w.batch_size, w.n_presample, w.fanouts,
+                                          w.rng_seed, w.presample_first_batch, with_edge_count=True)
+    assert ec.sum() == ac.sum()
+    remap, cp, ci, idx, pn, pd = oracle.fill_adj_element(indptr, indices, ec, 300_000 + 8 * 3)
+    assert pn >= 0 and 0 < cp[remap[pn] + 1] - cp[remap[pn]] < pd
+    # every list is a permutation of the old one, ordered by non-increasing count, ties in the old order
+    for v in np.flatnonzero(ac)[:200]:
+        s0, s1 = indptr[v], indptr[v + 1]
+        perm = sorted(range(s1 - s0), key=lambda t: (-int(ec[s0 + t]), t))
+        assert idx[s0:s1].tolist() == indices[s0:s1][perm].tolist()
+    seeds = np.concatenate([tiny["seeds"][512:767], [pn]])      # make sure the partial node is sampled
+    blk = oracle.sample_khop(indptr, idx, seeds, 2, w.fanouts, w.rng_seed)
+    saw_partial_miss = False
+    for h in range(w.n_hops):
+        frontier = blk.nodes[:blk.n_nodes[h]]
+        rows, src, counts = oracle.sample_hop_cached(indptr, idx, remap, cp, ci, frontier, 2, h, w.fanouts[h],
+                                                     w.rng_seed, pn, pd)
+        assert np.array_equal(rows, np.diff(blk.blk_indptr[h])) and np.array_equal(src, blk.src_global[h])
+        slot = remap[frontier]
+        clen = np.where(slot >= 0, cp[np.maximum(slot, 0) + 1] - cp[np.maximum(slot, 0)], 0)
+        hits = sum(int((blk.src_pos[h][blk.blk_indptr[h][i]:blk.blk_indptr[h][i + 1]] < clen[i]).sum())
+                   for i in range(len(frontier)))
+        assert counts.tolist() == [(slot >= 0).sum(), (slot < 0).sum(), hits, int(rows.sum()) - hits]
+        i_p = np.flatnonzero(frontier == pn)
+        if len(i_p):
+            p = blk.src_pos[h][blk.blk_indptr[h][i_p[0]]:blk.blk_indptr[h][i_p[0] + 1]]
+            saw_partial_miss |= bool((p >= clen[i_p[0]]).any())
+    assert saw_partial_miss
