@@ -48,6 +48,10 @@ extern "C" {
 #define DCI_FILL_STRICT_SPLIT 0x100  /* OR-ed into feat_policy: keep the shares of Eq. (1) as they
                                         are, no spill-over; with t_sample_ns = 0 this is the
                                         single-cache system of Section V-B (no adjacency cache)    */
+#define DCI_FILL_ADJ_ELEMENTS 0x200  /* OR-ed into feat_policy: element-granular adjacency cache, i.e.
+                                        Algorithm 1 with its second-level sort and a last node that
+                                        may be cached in part; needs edge_count and rewrites
+                                        graph->indices in place (see dci_fill_caches)              */
 
 typedef struct dci_ctx dci_ctx;
 
@@ -75,7 +79,10 @@ typedef struct {
   uint64_t cap_feat_bytes;/* C_feat of Eq. (1) after spill-over                         */
   const int32_t* adj_remap;  /* [N] slot in the adjacency cache, or -1                  */
   const int64_t* c_indptr;   /* [K+1]                                                   */
-  const int64_t* c_indices;  /* [M] the cached lists, each in its original order        */
+  const int64_t* c_indices;  /* [M] the cached lists, in the order the host lists have  */
+  int64_t adj_partial_node;  /* the one node whose list is cached only in its leading part
+                                (element-granular fill), or -1; counted in K               */
+  int64_t adj_partial_deg;   /* its full list length (the cached length is in c_indptr)    */
   const int32_t* feat_remap; /* [N] row in the feature cache, or -1                     */
   const float* feat_cache;   /* [k,F]                                                   */
 } dci_cache;
@@ -182,8 +189,12 @@ int32_t dci_blocks_bounds(int64_t num_nodes, int64_t n_seeds, const int32_t* fan
 
 /* Workspace needed by dci_sample_khop / dci_presample_count for batches of up to n_seeds seeds. */
 size_t dci_sample_workspace_bytes(int64_t num_nodes, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops);
-/* Workspace needed by dci_fill_caches. */
+/* Workspace needed by dci_fill_caches.  With DCI_FILL_ADJ_ELEMENTS it needs the larger
+ * dci_fill_elements_workspace_bytes(num_nodes, n_elements), where n_elements bounds the total
+ * list length of the nodes with a non-zero adj_count (num_edges always does; more than 2^31 - 1
+ * such elements are not supported). */
 size_t dci_fill_workspace_bytes(int64_t num_nodes);
+size_t dci_fill_elements_workspace_bytes(int64_t num_nodes, int64_t n_elements);
 /* Workspace needed by dci_sage_forward for blocks with these row capacities. */
 size_t dci_sage_workspace_bytes(const int64_t* cap_rows, int32_t n_layers, const int32_t* dims);
 
@@ -222,10 +233,21 @@ int32_t dci_presample_count(dci_ctx* ctx, const dci_graph* graph, const dci_cach
  *     Otherwise nodes are ordered by adj_count descending (ties: ascending id) and the longest
  *     prefix whose compacted form 8*(K+1) + 8*sum(deg) fits in C_adj is cached, lists
  *     concatenated in that order, each in its original element order.  adj_remap[v] = slot or -1.
+ *     With DCI_FILL_ADJ_ELEMENTS (Algorithm 1 and Fig. 6 as printed) the second branch also
+ *     reorders the elements inside every node by their own edge_count descending (ties: original
+ *     order), in graph->indices itself - which must therefore be writable mapped memory - so
+ *     that position p of a list means the same neighbour in the cache and on the host; and the
+ *     first node that does not fit as a whole is cached in part when at least 16 bytes are left:
+ *     its pointer entry and its floor((left - 8) / 8) leading elements (adj_partial_node /
+ *     adj_partial_deg).  A sampled position p of a node with a slot is served by the cache iff
+ *     p < cached length.  adj_count[v] must be the sum of edge_count over v's list (as
+ *     dci_presample_count leaves them); edge_count (device uint32 [E]) is not modified but no
+ *     longer matches the reordered lists afterwards.  The mode needs additional workspace, see
+ *     dci_fill_elements_workspace_bytes().
  * cache_buf: device, 256-byte aligned, at least budget_bytes + 256 bytes; the cache arrays are
  * carved from it (feature rows first).  adj_remap, feat_remap: device int32 [N], written in
- * full.  edge_count is accepted for symmetry with the counting call and not used by these
- * policies.  *out is filled on return; this call waits for the GPU. */
+ * full.  edge_count is only read with DCI_FILL_ADJ_ELEMENTS (may be NULL otherwise).  *out is
+ * filled on return; this call waits for the GPU. */
 int32_t dci_fill_caches(dci_ctx* ctx, const dci_graph* graph, const uint32_t* feat_count,
                         const uint32_t* adj_count, const uint32_t* edge_count, uint64_t budget_bytes,
                         uint64_t t_sample_ns, uint64_t t_feature_ns, int32_t feat_policy, void* cache_buf,

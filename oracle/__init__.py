@@ -251,17 +251,14 @@ def fill_adj_element(indptr, indices, edge_count, C_adj: int):
     N = len(indptr) - 1
     remap = np.empty(N, dtype=np.int32)
     K, M, pn, pd = c.c_int64(0), c.c_int64(0), c.c_int64(0), c.c_int64(0)
-    work = idx.copy()
-    rc = lib.oracle_fill_adj_element(N, indptr.ctypes.data, work.ctypes.data, ec.ctypes.data, C_adj,
-                                     remap.ctypes.data, None, 0, None, 0, c.byref(K), c.byref(M), c.byref(pn),
-                                     c.byref(pd))
-    assert rc == 0
-    cp = np.zeros(K.value + 1, dtype=np.int64)
-    ci = np.zeros(max(M.value, 1), dtype=np.int64)
+    cap_M = int(min(len(idx), C_adj // 8))
+    cp = np.zeros(N + 1, dtype=np.int64)
+    ci = np.zeros(max(cap_M, 1), dtype=np.int64)
     rc = lib.oracle_fill_adj_element(N, indptr.ctypes.data, idx.ctypes.data, ec.ctypes.data, C_adj,
-                                     remap.ctypes.data, cp.ctypes.data, K.value, ci.ctypes.data, M.value,
+                                     remap.ctypes.data, cp.ctypes.data, N, ci.ctypes.data, cap_M,
                                      c.byref(K), c.byref(M), c.byref(pn), c.byref(pd))
     assert rc == 0
+    cp = cp[:K.value + 1].copy()
     return remap, cp, ci[:M.value], idx, int(pn.value), int(pd.value)
 
 

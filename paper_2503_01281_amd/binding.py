@@ -39,7 +39,8 @@ class _Cache(C.Structure):
     _fields_ = [("adj_nodes", C.c_int64), ("adj_edges", C.c_int64), ("feat_rows", C.c_int64),
                 ("adj_bytes", C.c_uint64), ("feat_bytes", C.c_uint64), ("cap_adj_bytes", C.c_uint64),
                 ("cap_feat_bytes", C.c_uint64), ("adj_remap", C.c_void_p), ("c_indptr", C.c_void_p),
-                ("c_indices", C.c_void_p), ("feat_remap", C.c_void_p), ("feat_cache", C.c_void_p)]
+                ("c_indices", C.c_void_p), ("adj_partial_node", C.c_int64), ("adj_partial_deg", C.c_int64),
+                ("feat_remap", C.c_void_p), ("feat_cache", C.c_void_p)]
 
 
 class _Blocks(C.Structure):
@@ -74,6 +75,8 @@ def load_library():
     lib.dci_sample_workspace_bytes.restype = sz
     lib.dci_fill_workspace_bytes.argtypes = [i64]
     lib.dci_fill_workspace_bytes.restype = sz
+    lib.dci_fill_elements_workspace_bytes.argtypes = [i64, i64]
+    lib.dci_fill_elements_workspace_bytes.restype = sz
     lib.dci_sage_workspace_bytes.argtypes = [P, i32, P]
     lib.dci_sage_workspace_bytes.restype = sz
     lib.dci_presample_count.argtypes = [P, P, P, P, i64, i32, i64, i64, u64, P, i32, u64, P, P, P, P, P]
@@ -207,14 +210,17 @@ class Cache:
     feat_bytes = property(lambda s: s.c.feat_bytes)
     cap_adj_bytes = property(lambda s: s.c.cap_adj_bytes)
     cap_feat_bytes = property(lambda s: s.c.cap_feat_bytes)
+    adj_partial_node = property(lambda s: s.c.adj_partial_node)
+    adj_partial_deg = property(lambda s: s.c.adj_partial_deg)
 
     @staticmethod
-    def from_arrays(adj_remap, c_indptr, c_indices, feat_remap, feat_cache) -> "Cache":
+    def from_arrays(adj_remap, c_indptr, c_indices, feat_remap, feat_cache, partial_node: int = -1,
+                    partial_deg: int = 0) -> "Cache":
         """Wraps cache arrays built elsewhere (device tensors)."""
         K, M, k = c_indptr.numel() - 1, c_indices.numel(), feat_cache.shape[0]
         F = feat_cache.shape[1]
         c = _Cache(K, M, k, 8 * (K + 1) + 8 * M, 4 * F * k, 0, 0, _ptr(adj_remap), _ptr(c_indptr),
-                   _ptr(c_indices), _ptr(feat_remap), _ptr(feat_cache))
+                   _ptr(c_indices), partial_node, partial_deg, _ptr(feat_remap), _ptr(feat_cache))
         return Cache(c, (adj_remap, c_indptr, c_indices, feat_remap, feat_cache))
 
 
@@ -274,7 +280,10 @@ def dci_fill_caches(ctx: Context, graph: Graph, feat_count: torch.Tensor, adj_co
                     budget_bytes: int, t_sample_ns: int, t_feature_ns: int, feat_policy: int = 0,
                     edge_count: Optional[torch.Tensor] = None) -> Cache:
     dev = ctx.device
-    ctx.ensure_workspace(ctx.lib.dci_fill_workspace_bytes(graph.num_nodes))
+    if feat_policy & DCI_FILL_ADJ_ELEMENTS:
+        ctx.ensure_workspace(ctx.lib.dci_fill_elements_workspace_bytes(graph.num_nodes, graph.num_edges))
+    else:
+        ctx.ensure_workspace(ctx.lib.dci_fill_workspace_bytes(graph.num_nodes))
     total = (graph.num_nodes + 1 + graph.num_edges) * 8 + graph.num_nodes * graph.feat_dim * 4
     buf = torch.empty(min(int(budget_bytes), total) + 512, dtype=torch.uint8, device=dev)
     off = (-buf.data_ptr()) % 256
@@ -311,6 +320,7 @@ def dci_gather_features(ctx: Context, graph: Graph, cache: Optional[Cache], node
 
 
 DCI_MODEL_SAGE_MEAN, DCI_MODEL_SAGE_SUM, DCI_MODEL_GCN_AVG = 0, 1, 2
+DCI_FILL_STRICT_SPLIT, DCI_FILL_ADJ_ELEMENTS = 0x100, 0x200
 DCI_OPT_LINEAR_KERNEL = 1
 DCI_OPT_LINEAR_SPLIT = 2
 

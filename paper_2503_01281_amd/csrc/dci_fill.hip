@@ -106,16 +106,18 @@ static int32_t device_scan(dci_ctx* ctx, long long n, In in, Out out, u64* tile_
 static inline long long scan_tiles_for(long long n) { return (n + kScanTile - 1) / kScanTile + 1; }
 
 // ---- reductions -----------------------------------------------------------------------------
-// scal[0] += sum(count), scal[1] = max(scal[1], max(count))
+// scal[0] += sum(count), scal[1] = max(scal[1], max(count)), scal[3] += number of non-zero counts
 __global__ __launch_bounds__(kFillBlock) void k_sum_max(const u32* __restrict__ count, long long n, u64* scal) {
-  u64 s = 0;
+  u64 s = 0, nz = 0;
   u32 m = 0;
   for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x) {
     const u32 c = count[i];
     s += c;
+    nz += c != 0;
     m = c > m ? c : m;
   }
   s = wave_sum_u64(s);
+  nz = wave_sum_u64(nz);
 #pragma unroll
   for (int d = kWave / 2; d >= 1; d >>= 1) {
     const u32 o = __shfl_down(m, d, kWave);
@@ -124,6 +126,7 @@ __global__ __launch_bounds__(kFillBlock) void k_sum_max(const u32* __restrict__ 
   if (lane_id() == 0) {
     if (s) atomicAdd(&scal[0], s);
     if (m) atomicMax(&scal[1], (u64)m);
+    if (nz) atomicAdd(&scal[3], nz);
   }
 }
 
@@ -145,10 +148,14 @@ struct RadixSrc {
   const int* ids;
   const u32* count;
   u32 max_count;
+  const u32* by_id;  // first pass of a re-sort of existing ids: key = by_id[ids[idx]]
   __device__ __forceinline__ void get(long long idx, u32* key, int* id) const {
     if (keys) {
       *key = keys[idx];
       *id = ids[idx];
+    } else if (by_id) {
+      *id = ids[idx];
+      *key = by_id[*id];
     } else {
       *key = max_count - count[idx];
       *id = (int)idx;
@@ -262,6 +269,7 @@ static int32_t sort_by_count_desc(dci_ctx* ctx, const u32* count, long long n, u
   src.ids = nullptr;
   src.count = count;
   src.max_count = max_count;
+  src.by_id = nullptr;
   int cur = 0;
   for (int p = 0; p < passes; ++p) {
     const int shift = 8 * p;
@@ -285,6 +293,41 @@ static int32_t sort_by_count_desc(dci_ctx* ctx, const u32* count, long long n, u
 
 // ---- feature cache ----------------------------------------------------------------------------
 // Paper's rule: above-average nodes (count * N > total) in id order, then the others in id order.
+// Stable re-sort of an id array produced by sort_by_count_desc (it lives in one of ws.ids) by
+// key[id] ascending, keys below 2^key_bits.  The two stages together order ids by (key ascending,
+// count descending, id ascending).
+static int32_t resort_by_key(dci_ctx* ctx, const int* ids_in, const u32* key_by_id, long long n, int key_bits,
+                             const SortWs& ws, const int** out) {
+  const long long n_blocks = (n + kRadixTile - 1) / kRadixTile;
+  const int passes = (key_bits + 7) / 8;
+  RadixSrc src;
+  src.keys = nullptr;
+  src.ids = ids_in;
+  src.count = nullptr;
+  src.max_count = 0;
+  src.by_id = key_by_id;
+  int cur = ids_in == ws.ids[0] ? 1 : 0;  // write into the buffer the input is not in
+  for (int p = 0; p < passes; ++p) {
+    const int shift = 8 * p;
+    hipLaunchKernelGGL(k_radix_hist, dim3((unsigned)n_blocks), dim3(kFillBlock), 0, ctx->stream, src, n, shift,
+                       n_blocks, ws.hist);
+    DCI_LAUNCH_CHECK(ctx);
+    HistIn in{ws.hist};
+    HistOut o{ws.hist};
+    int32_t rc = device_scan(ctx, 256 * n_blocks, in, o, ws.tile_sums);
+    if (rc != DCI_OK) return rc;
+    hipLaunchKernelGGL(k_radix_scatter, dim3((unsigned)n_blocks), dim3(kFillBlock), 0, ctx->stream, src, n, shift,
+                       n_blocks, (const u32*)ws.hist, ws.keys[cur], ws.ids[cur]);
+    DCI_LAUNCH_CHECK(ctx);
+    src.keys = ws.keys[cur];
+    src.ids = ws.ids[cur];
+    src.by_id = nullptr;
+    cur ^= 1;
+  }
+  *out = src.ids;
+  return DCI_OK;
+}
+
 struct AboveIn {
   const u32* count;
   const u64* scal;  // [0] = total
@@ -368,8 +411,8 @@ struct AdjOut {
   }
 };
 
-// One wavefront per cached node copies its list.
-__global__ __launch_bounds__(kFillBlock) void k_copy_lists(const int* __restrict__ order, long long K,
+// One wavefront per cached slot s0 <= s < K copies the cached (leading) part of its node's list.
+__global__ __launch_bounds__(kFillBlock) void k_copy_lists(const int* __restrict__ order, long long s0, long long K,
                                                            const long long* __restrict__ indptr,
                                                            const long long* __restrict__ indices,
                                                            const long long* __restrict__ c_indptr,
@@ -377,9 +420,9 @@ __global__ __launch_bounds__(kFillBlock) void k_copy_lists(const int* __restrict
   const int lane = lane_id();
   const long long wave0 = (blockIdx.x * (long long)blockDim.x + threadIdx.x) / kWave;
   const long long n_waves = (long long)gridDim.x * blockDim.x / kWave;
-  for (long long s = wave0; s < K; s += n_waves) {
+  for (long long s = s0 + wave0; s < K; s += n_waves) {
     const long long v = order ? order[s] : s;
-    const long long src0 = indptr[v], len = indptr[v + 1] - src0, dst0 = c_indptr[s];
+    const long long src0 = indptr[v], dst0 = c_indptr[s], len = c_indptr[s + 1] - dst0;
     long long e = lane;
     for (; e + 3 * kWave < len; e += 4 * kWave) {
       const long long a = indices[src0 + e], b = indices[src0 + e + kWave], c = indices[src0 + e + 2 * kWave],
@@ -418,6 +461,93 @@ static int grid_1d(const dci_ctx* ctx, long long n, int per_block = kFillBlock) 
   return (int)b;
 }
 
+// ---- element-granular mode: second-level sort inside the nodes -------------------------------
+// The nodes with a non-zero total are the first n_nz of `order`; their lists, E_nz elements in all,
+// are laid out one after the other (segment s at off[s]) for a stable sort by (segment, element
+// count descending).  Nodes without any counted access keep their order.
+struct SegLenIn {
+  const int* order;
+  const u32* deg;
+  __device__ __forceinline__ u64 operator()(long long s) const { return deg[order[s]]; }
+};
+struct SegOffOut {
+  long long* off;  // [n_nz + 1]
+  long long n_nz;
+  __device__ __forceinline__ void operator()(long long s, u64 excl, u64 len) const {
+    off[s] = (long long)excl;
+    if (s == n_nz - 1) off[n_nz] = (long long)(excl + len);
+  }
+};
+
+// one wavefront per segment: neighbour ids (read from the host), their counts and the segment number
+__global__ __launch_bounds__(kFillBlock) void k_gather_elems(const int* __restrict__ order, long long n_nz,
+                                                             const long long* __restrict__ indptr,
+                                                             const long long* __restrict__ indices,
+                                                             const u32* __restrict__ edge_count,
+                                                             const long long* __restrict__ off,
+                                                             long long* __restrict__ vals, u32* __restrict__ cnt,
+                                                             u32* __restrict__ seg) {
+  const int lane = lane_id();
+  const long long wave0 = (blockIdx.x * (long long)blockDim.x + threadIdx.x) / kWave;
+  const long long n_waves = (long long)gridDim.x * blockDim.x / kWave;
+  for (long long s = wave0; s < n_nz; s += n_waves) {
+    const long long v = order[s];
+    const long long h0 = indptr[v], o = off[s], len = off[s + 1] - o;
+    for (long long t = lane; t < len; t += kWave) {
+      vals[o + t] = indices[h0 + t];
+      cnt[o + t] = edge_count[h0 + t];
+      seg[o + t] = (u32)s;
+    }
+  }
+}
+
+// one wavefront per segment: the reordered list goes back to the host structure (only where it changed)
+// and, for the first n_cached segments, its cached leading part into the cache
+__global__ __launch_bounds__(kFillBlock) void k_scatter_elems(const int* __restrict__ order, long long n_nz,
+                                                              long long n_cached,
+                                                              const long long* __restrict__ indptr,
+                                                              long long* __restrict__ host_indices,
+                                                              const long long* __restrict__ off,
+                                                              const long long* __restrict__ vals,
+                                                              const int* __restrict__ sorted,
+                                                              const long long* __restrict__ c_indptr,
+                                                              long long* __restrict__ c_indices) {
+  const int lane = lane_id();
+  const long long wave0 = (blockIdx.x * (long long)blockDim.x + threadIdx.x) / kWave;
+  const long long n_waves = (long long)gridDim.x * blockDim.x / kWave;
+  for (long long s = wave0; s < n_nz; s += n_waves) {
+    const long long v = order[s];
+    const long long h0 = indptr[v], o = off[s], len = off[s + 1] - o;
+    long long c0 = 0, clen = 0;
+    if (s < n_cached) {
+      c0 = c_indptr[s];
+      clen = c_indptr[s + 1] - c0;
+    }
+    for (long long t = lane; t < len; t += kWave) {
+      const long long j = sorted[o + t];
+      const long long u = vals[j];
+      if (j != o + t) host_indices[h0 + t] = u;
+      if (t < clen) c_indices[c0 + t] = u;
+    }
+  }
+}
+
+struct ElemWs {
+  long long* off;
+  long long* vals;
+  u32* cnt;
+  u32* seg;
+  SortWs sort;
+};
+
+static void carve_elem_ws(Arena& ar, long long n_nodes, long long n_elems, ElemWs* ws) {
+  ws->off = ar.take<long long>((size_t)(n_nodes + 1));
+  ws->vals = ar.take<long long>((size_t)n_elems);
+  ws->cnt = ar.take<u32>((size_t)n_elems);
+  ws->seg = ar.take<u32>((size_t)n_elems);
+  carve_sort_ws(ar, n_elems > 0 ? n_elems : 1, &ws->sort);
+}
+
 struct FillWs {
   u64* scal;  // [0] sum, [1] max, [2] cached-node counter, [3] spare
   u32* deg;
@@ -450,11 +580,20 @@ size_t dci_fill_workspace_bytes(int64_t num_nodes) {
   return ar.off;
 }
 
+size_t dci_fill_elements_workspace_bytes(int64_t num_nodes, int64_t n_elements) {
+  if (num_nodes < 1 || n_elements < 0) return 0;
+  Arena ar(nullptr, 0);
+  FillWs ws;
+  carve_fill_ws(ar, num_nodes, &ws);
+  ElemWs ew;
+  carve_elem_ws(ar, num_nodes, n_elements, &ew);
+  return ar.off;
+}
+
 int32_t dci_fill_caches(dci_ctx* ctx, const dci_graph* g, const uint32_t* feat_count, const uint32_t* adj_count,
                         const uint32_t* edge_count, uint64_t budget_bytes, uint64_t t_sample_ns,
                         uint64_t t_feature_ns, int32_t feat_policy, void* cache_buf, int32_t* adj_remap,
                         int32_t* feat_remap, dci_cache* out) {
-  (void)edge_count;
   if (!ctx) return DCI_ERR_INVALID_ARG;
   if (!g || !g->indptr || !g->indices || !g->feat || g->num_nodes < 1 || g->num_edges < 0 || g->feat_dim < 1)
     return fail(ctx, DCI_ERR_INVALID_ARG, "graph: null arrays or bad sizes");
@@ -462,7 +601,10 @@ int32_t dci_fill_caches(dci_ctx* ctx, const dci_graph* g, const uint32_t* feat_c
   if (!feat_count || !adj_count || !adj_remap || !feat_remap || !out || (!cache_buf && budget_bytes > 0))
     return fail(ctx, DCI_ERR_INVALID_ARG, "fill_caches: null argument");
   const bool strict_split = (feat_policy & DCI_FILL_STRICT_SPLIT) != 0;
-  feat_policy &= ~DCI_FILL_STRICT_SPLIT;
+  const bool elements = (feat_policy & DCI_FILL_ADJ_ELEMENTS) != 0;
+  feat_policy &= ~(DCI_FILL_STRICT_SPLIT | DCI_FILL_ADJ_ELEMENTS);
+  if (elements && !edge_count)
+    return fail(ctx, DCI_ERR_INVALID_ARG, "fill_caches: DCI_FILL_ADJ_ELEMENTS needs edge_count");
   if (feat_policy != DCI_FEAT_POLICY_PAPER_MEAN && feat_policy != DCI_FEAT_POLICY_TOPK)
     return fail(ctx, DCI_ERR_INVALID_ARG, "fill_caches: unknown feature policy %d", feat_policy);
   if (reinterpret_cast<uintptr_t>(cache_buf) % kAlign)
@@ -539,7 +681,7 @@ int32_t dci_fill_caches(dci_ctx* ctx, const dci_graph* g, const uint32_t* feat_c
   }
 
   // 3. adjacency cache
-  long long K = 0, M = 0;
+  long long K = 0, M = 0, partial_node = -1, partial_deg = 0;
   const long long* indptr = reinterpret_cast<const long long*>(g->indptr);
   const long long* indices = reinterpret_cast<const long long*>(g->indices);
   long long* c_indices = nullptr;
@@ -553,7 +695,7 @@ int32_t dci_fill_caches(dci_ctx* ctx, const dci_graph* g, const uint32_t* feat_c
     DCI_LAUNCH_CHECK(ctx);
     hipLaunchKernelGGL(k_copy_i64, dim3(grid_1d(ctx, E)), dim3(kFillBlock), 0, ctx->stream, indices, E, c_indices);
     DCI_LAUNCH_CHECK(ctx);
-  } else if (c_adj < 16) {
+  } else if (c_adj < 16 && !elements) {
     // not even an empty list fits: nothing is cached
     hipLaunchKernelGGL(k_fill_i32, dim3(grid_1d(ctx, N)), dim3(kFillBlock), 0, ctx->stream, adj_remap, N, -1);
     DCI_LAUNCH_CHECK(ctx);
@@ -563,27 +705,107 @@ int32_t dci_fill_caches(dci_ctx* ctx, const dci_graph* g, const uint32_t* feat_c
     DCI_LAUNCH_CHECK(ctx);
     hipLaunchKernelGGL(k_degrees, dim3(grid_1d(ctx, N)), dim3(kFillBlock), 0, ctx->stream, indptr, N, ws.deg);
     DCI_LAUNCH_CHECK(ctx);
-    u64 h[2];
-    if ((rc = read_scal(ctx, ws.scal, h, 2)) != DCI_OK) return rc;
+    u64 h[4];
+    if ((rc = read_scal(ctx, ws.scal, h, 4)) != DCI_OK) return rc;
+    const long long n_nz = (long long)h[3];  // nodes with a non-zero total: the first n_nz of the order
     const int* order = nullptr;
     if ((rc = sort_by_count_desc(ctx, adj_count, N, (u32)h[1], ws.sort, &order)) != DCI_OK) return rc;
-    CostIn in{order, ws.deg};
-    AdjOut o{order, adj_remap, c_indptr, c_adj, ws.scal, ws.deg, N};
-    if ((rc = device_scan(ctx, N, in, o, ws.sort.tile_sums)) != DCI_OK) return rc;
-    u64 hk[3];
-    if ((rc = read_scal(ctx, ws.scal, hk, 3)) != DCI_OK) return rc;
-    K = (long long)hk[2];
-    // c_indptr[0] = 0, then read M = c_indptr[K]
-    long long zero = 0;
-    DCI_HIP(ctx, hipMemcpyAsync(c_indptr, &zero, sizeof(zero), hipMemcpyHostToDevice, ctx->stream));
-    DCI_HIP(ctx, hipMemcpyAsync(&M, c_indptr + K, sizeof(M), hipMemcpyDeviceToHost, ctx->stream));
-    DCI_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (c_adj >= 16) {
+      CostIn in{order, ws.deg};
+      AdjOut o{order, adj_remap, c_indptr, c_adj, ws.scal, ws.deg, N};
+      if ((rc = device_scan(ctx, N, in, o, ws.sort.tile_sums)) != DCI_OK) return rc;
+      u64 hk[3];
+      if ((rc = read_scal(ctx, ws.scal, hk, 3)) != DCI_OK) return rc;
+      K = (long long)hk[2];
+      // c_indptr[0] = 0, then read M = c_indptr[K]
+      long long zero = 0;
+      DCI_HIP(ctx, hipMemcpyAsync(c_indptr, &zero, sizeof(zero), hipMemcpyHostToDevice, ctx->stream));
+      DCI_HIP(ctx, hipMemcpyAsync(&M, c_indptr + K, sizeof(M), hipMemcpyDeviceToHost, ctx->stream));
+      DCI_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    } else {
+      hipLaunchKernelGGL(k_fill_i32, dim3(grid_1d(ctx, N)), dim3(kFillBlock), 0, ctx->stream, adj_remap, N, -1);
+      DCI_LAUNCH_CHECK(ctx);
+    }
+    if (elements && c_adj >= 16 && K < N) {
+      // the first node that does not fit as a whole: its pointer entry and as many leading elements as
+      // the rest of the budget pays for
+      const u64 used = 8ull * (u64)(K + 1) + 8ull * (u64)M;
+      if (c_adj - used >= 16) {
+        int b = 0;
+        u32 deg_b = 0;
+        DCI_HIP(ctx, hipMemcpyAsync(&b, order + K, sizeof(b), hipMemcpyDeviceToHost, ctx->stream));
+        DCI_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        DCI_HIP(ctx, hipMemcpyAsync(&deg_b, ws.deg + b, sizeof(deg_b), hipMemcpyDeviceToHost, ctx->stream));
+        DCI_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        const long long len = (long long)((c_adj - used - 8ull) / 8ull);  // < deg_b: the whole node did not fit
+        const int slot = (int)K;
+        const long long end = M + len;
+        DCI_HIP(ctx, hipMemcpyAsync(adj_remap + b, &slot, sizeof(slot), hipMemcpyHostToDevice, ctx->stream));
+        DCI_HIP(ctx, hipMemcpyAsync(c_indptr + K + 1, &end, sizeof(end), hipMemcpyHostToDevice, ctx->stream));
+        DCI_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        partial_node = b;
+        partial_deg = (long long)deg_b;
+        K += 1;
+        M = end;
+      }
+    }
     c_indices = c_indptr + (K + 1);
-    if (K > 0) {
+    long long first_plain = 0;  // cached slots below this one get their lists from the element sort
+    if (elements && n_nz > 0) {
+      Arena ar2(ctx->ws, ctx->ws_bytes);
+      FillWs ws2;
+      carve_fill_ws(ar2, N, &ws2);  // same layout as ws: the element arrays follow it
+      long long* off = ar2.take<long long>((size_t)(N + 1));
+      if (!ar2.ok())
+        return fail(ctx, DCI_ERR_CAPACITY, "workspace holds %zu bytes, the element-granular fill needs more (see dci_fill_elements_workspace_bytes)", ctx->ws_bytes);
+      SegLenIn sin{order, ws.deg};
+      SegOffOut sout{off, n_nz};
+      // the node sort is finished with its scan scratch; `order` itself stays in use
+      if ((rc = device_scan(ctx, n_nz, sin, sout, ws.sort.tile_sums)) != DCI_OK) return rc;
+      long long e_nz = 0;
+      DCI_HIP(ctx, hipMemcpyAsync(&e_nz, off + n_nz, sizeof(e_nz), hipMemcpyDeviceToHost, ctx->stream));
+      DCI_HIP(ctx, hipStreamSynchronize(ctx->stream));
+      if (e_nz >= ((long long)1 << 31))
+        return fail(ctx, DCI_ERR_UNSUPPORTED, "element-granular fill: %lld list elements of counted nodes (limit 2^31-1)", e_nz);
+      if (e_nz > 0) {
+        Arena ar3(ctx->ws, ctx->ws_bytes);
+        FillWs ws3;
+        carve_fill_ws(ar3, N, &ws3);
+        ElemWs ew;
+        carve_elem_ws(ar3, N, e_nz, &ew);
+        if (!ar3.ok())
+          return fail(ctx, DCI_ERR_CAPACITY, "workspace holds %zu bytes, the element-granular fill of %lld elements needs %zu",
+                      ctx->ws_bytes, e_nz, ar3.off);
+        // ew.off is the array `off` carved above (same position)
+        const int wpb = kFillBlock / kWave;
+        hipLaunchKernelGGL(k_gather_elems, dim3(grid_1d(ctx, n_nz, wpb)), dim3(kFillBlock), 0, ctx->stream, order, n_nz,
+                           indptr, indices, edge_count, (const long long*)ew.off, ew.vals, ew.cnt, ew.seg);
+        DCI_LAUNCH_CHECK(ctx);
+        if ((rc = fill_bytes(ctx, ws.scal, 64, 0u)) != DCI_OK) return rc;
+        hipLaunchKernelGGL(k_sum_max, dim3(grid_1d(ctx, e_nz)), dim3(kFillBlock), 0, ctx->stream, (const u32*)ew.cnt, e_nz,
+                           ws.scal);
+        DCI_LAUNCH_CHECK(ctx);
+        u64 he[2];
+        if ((rc = read_scal(ctx, ws.scal, he, 2)) != DCI_OK) return rc;
+        const int* by_count = nullptr;
+        if ((rc = sort_by_count_desc(ctx, ew.cnt, e_nz, (u32)he[1], ew.sort, &by_count)) != DCI_OK) return rc;
+        const int* sorted = by_count;
+        int seg_bits = 0;
+        while (seg_bits < 32 && ((u64)(n_nz - 1) >> seg_bits) != 0) ++seg_bits;
+        if (seg_bits > 0 && (rc = resort_by_key(ctx, by_count, ew.seg, e_nz, seg_bits, ew.sort, &sorted)) != DCI_OK) return rc;
+        const long long n_cached = n_nz < K ? n_nz : K;
+        hipLaunchKernelGGL(k_scatter_elems, dim3(grid_1d(ctx, n_nz, wpb)), dim3(kFillBlock), 0, ctx->stream, order, n_nz,
+                           n_cached, indptr, const_cast<long long*>(indices), (const long long*)ew.off,
+                           (const long long*)ew.vals, sorted, (const long long*)c_indptr, c_indices);
+        DCI_LAUNCH_CHECK(ctx);
+        first_plain = n_cached;
+      }
+    }
+    if (K > first_plain) {
       // Entries of c_indptr beyond K+1 were never written; the lists start right after entry K.
       const long long waves_per_block = kFillBlock / kWave;
-      hipLaunchKernelGGL(k_copy_lists, dim3(grid_1d(ctx, K, (int)waves_per_block)), dim3(kFillBlock), 0, ctx->stream,
-                         order, K, indptr, indices, (const long long*)c_indptr, c_indices);
+      hipLaunchKernelGGL(k_copy_lists, dim3(grid_1d(ctx, K - first_plain, (int)waves_per_block)), dim3(kFillBlock), 0,
+                         ctx->stream, order, first_plain, K, indptr, indices, (const long long*)c_indptr, c_indices);
       DCI_LAUNCH_CHECK(ctx);
     }
   }
@@ -602,6 +824,8 @@ int32_t dci_fill_caches(dci_ctx* ctx, const dci_graph* g, const uint32_t* feat_c
   out->c_indices = reinterpret_cast<const int64_t*>(c_indices);
   out->feat_remap = feat_remap;
   out->feat_cache = feat_cache;
+  out->adj_partial_node = partial_node;
+  out->adj_partial_deg = partial_deg;
   return DCI_OK;
 }
 

@@ -30,8 +30,11 @@ typedef unsigned long long HashEntry;
 constexpr unsigned int kTentative = 0x80000000u;
 constexpr HashEntry kEmptyEntry = ~0ull;
 constexpr int kBlock = 256;
-constexpr int kRowHitBit = 1 << 30;   // row_cnt[i] = sampled edges of row i | this bit if the list was cached
-constexpr int kRowCntMask = kRowHitBit - 1;
+// row_cnt[i]: bits 0..7 sampled edges of row i; bits 8..15 how many of them were read from the host although
+// the node has a cache slot (only the node cached in part has any); bit 30 set if the node has a slot
+constexpr int kRowHitBit = 1 << 30;
+constexpr int kRowCntMask = 0xFF;
+constexpr int kRowHostShift = 8;
 
 __device__ __forceinline__ unsigned entry_val(const HashEntry* table, unsigned slot) {
   return reinterpret_cast<const unsigned*>(table)[2 * (size_t)slot];  // low half (little endian)
@@ -110,6 +113,8 @@ struct HopArgs {
   const int* adj_remap;
   const long long* c_indptr;
   const long long* c_indices;
+  long long partial_node;  // the node whose list is cached in part (-1: none) and its full length
+  long long partial_deg;
   unsigned k0, k1, batch;
   long long* tmp_u;
   int* tmp_slot;
@@ -181,7 +186,7 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
   for (long long base = (long long)block * kGroups; base < n_rows; base += (long long)n_blocks * kGroups) {
     const long long i = base + grp_in_block;
     const bool row_ok = i < n_rows;
-    long long v = 0, start = 0, d = 0;
+    long long v = 0, start = 0, d = 0, cached_len = 0;
     const long long* list = a.indices;
     bool hit = false;
     if (row_ok) {
@@ -198,7 +203,8 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
       hit = r >= 0;
       if (hit) {
         start = a.c_indptr[r];
-        d = a.c_indptr[r + 1] - start;
+        cached_len = a.c_indptr[r + 1] - start;
+        d = v == a.partial_node ? a.partial_deg : cached_len;
         list = a.c_indices;
       } else {
         start = a.indptr[v];
@@ -224,8 +230,12 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
       if (floyd) pos = S;
     }
     const bool active = row_ok && gl < c;
+    // position p of a node with a slot is served by the cache iff p < cached length (Section IV-B, third
+    // paragraph); beyond it - possible only for the one node cached in part - the host list is read
+    const bool from_host = active && hit && pos >= cached_len;
+    const int n_host = __popcll(group_bits<G>(__ballot(from_host), grp_in_wave));
     if (active) {
-      const long long u = list[start + pos];
+      const long long u = from_host ? a.indices[a.indptr[v] + pos] : list[start + pos];
       const int p = (int)(i * f + gl);
       const unsigned slot = table_insert_min(a.table, a.mask, a.shift, u, kTentative | (unsigned)p);
       a.tmp_u[p] = u;
@@ -237,7 +247,7 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
     }
     if (row_ok && gl == 0) {
       // the hit flag rides in bit 30 so that the relabel kernel can total the hit statistics
-      a.row_cnt[i] = c | (hit ? kRowHitBit : 0);
+      a.row_cnt[i] = c | (n_host << kRowHostShift) | (hit ? kRowHitBit : 0);
       if (COUNT && c > 0) atomicAdd(&a.adj_count[v], (unsigned)c);
     }
   }
@@ -338,7 +348,7 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
       s_f[r] = __popcll(bits);
       if (raw[it] & kRowHitBit) {
         hit_rows += 1;
-        hit_edges += (unsigned)c;
+        hit_edges += (unsigned)(c - ((raw[it] >> kRowHostShift) & 0xFF));
       }
     }
   }
@@ -617,6 +627,8 @@ static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* c
     ha.adj_remap = cache ? cache->adj_remap : nullptr;
     ha.c_indptr = cache ? reinterpret_cast<const long long*>(cache->c_indptr) : nullptr;
     ha.c_indices = cache ? reinterpret_cast<const long long*>(cache->c_indices) : nullptr;
+    ha.partial_node = cache ? cache->adj_partial_node : -1;
+    ha.partial_deg = cache ? cache->adj_partial_deg : 0;
     ha.k0 = (unsigned)rng_seed;
     ha.k1 = (unsigned)(rng_seed >> 32);
     ha.batch = (unsigned)batch_index;

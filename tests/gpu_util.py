@@ -20,13 +20,14 @@ def make_graph(indptr, indices, feat, on_device=False) -> dci.Graph:
     return dci.Graph(mv(indptr), mv(indices), None if feat is None else mv(feat))
 
 
-def upload_cache(adj_remap, c_indptr, c_indices, feat_remap, feat_cache) -> dci.Cache:
+def upload_cache(adj_remap, c_indptr, c_indices, feat_remap, feat_cache, partial_node=-1, partial_deg=0) -> dci.Cache:
     if len(c_indices) == 0:
         c_indices = np.zeros(1, dtype=np.int64)[:0]
     return dci.Cache.from_arrays(dev(adj_remap.astype(np.int32)), dev(c_indptr.astype(np.int64)),
                                  torch.from_numpy(np.ascontiguousarray(c_indices, dtype=np.int64)).cuda(),
                                  dev(feat_remap.astype(np.int32)),
-                                 torch.from_numpy(np.ascontiguousarray(feat_cache, dtype=np.float32)).cuda())
+                                 torch.from_numpy(np.ascontiguousarray(feat_cache, dtype=np.float32)).cuda(),
+                                 partial_node, partial_deg)
 
 
 def blocks_to_host(ctx, blk: dci.Blocks):

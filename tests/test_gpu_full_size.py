@@ -121,3 +121,55 @@ def test_presample_fill_and_batches(big):
                 assert st["feat_hits"] > 0 and st["feat_misses"] > 0
                 assert st["adj_edge_hits"] > 0 and st["adj_edge_misses"] > 0
         del cache
+
+
+def test_element_granular_cache_full_size(big):
+    """Algorithm 1 as printed, at full size: second-level sort of every counted node's list (in the pinned host
+    structure too), a last node cached in part, blocks bit for bit and hits counted per position.  The host lists
+    are restored afterwards."""
+    e = big
+    dci, gu, w, ctx, g = e["dci"], e["gu"], e["w"], e["ctx"], e["g"]
+    original = e["indices"].copy()
+    try:
+        fc_w, ac_w, ec_w, _ = oracle.presample_count(e["indptr"], e["indices"], e["seeds"], w.batch_size, w.n_presample,
+                                                     w.fanouts, w.rng_seed, w.presample_first_batch, with_edge_count=True)
+        fc = gu.dev(fc_w.view(np.int32))
+        ac = gu.dev(ac_w.view(np.int32))
+        ec = torch.zeros(w.num_edges, dtype=torch.int32, device="cuda")
+        fz = torch.zeros(w.num_nodes, dtype=torch.int32, device="cuda")
+        az = torch.zeros(w.num_nodes, dtype=torch.int32, device="cuda")
+        dci.dci_presample_count(ctx, g, None, gu.dev(e["seeds"]), w.batch_size, 0, w.n_presample, w.presample_first_batch,
+                                w.fanouts, w.rng_seed, fz, az, ec)
+        ctx.sync()
+        assert np.array_equal(ec.cpu().numpy().view(np.uint32), ec_w)
+        budget = 400_000_000
+        C_adj, C_feat = oracle.split(budget, 3, 7, w.num_nodes, w.num_edges, w.feat_dim)
+        remap, cp, ci, idx, pn, pd = oracle.fill_adj_element(e["indptr"], original, ec_w, C_adj)
+        cache = dci.dci_fill_caches(ctx, g, fc, ac, budget, 3, 7, dci.DCI_FILL_ADJ_ELEMENTS, edge_count=ec)
+        assert cache.cap_adj_bytes == C_adj
+        assert (cache.adj_nodes, cache.adj_edges) == (len(cp) - 1, len(ci))
+        assert (cache.adj_partial_node, cache.adj_partial_deg) == (pn, pd) and pn >= 0
+        assert np.array_equal(cache.adj_remap.cpu().numpy(), remap)
+        assert np.array_equal(e["indices"], idx), "host lists after the fill"
+        base = cache.buf.data_ptr()
+        view = lambda addr, n: cache.buf[addr - base:addr - base + 8 * n].view(torch.int64).cpu().numpy()
+        assert np.array_equal(view(cache.c.c_indptr, len(cp)), cp)
+        assert np.array_equal(view(cache.c.c_indices, len(ci)), ci)
+        # one batch through the cache, the partial node among its seeds
+        b = 1
+        seeds = e["seeds"][b * w.batch_size:(b + 1) * w.batch_size].copy()
+        seeds[-1] = pn
+        want = oracle.sample_khop(e["indptr"], idx, seeds, b, w.fanouts, w.rng_seed)
+        hits = host = 0
+        for h in range(w.n_hops):
+            _, _, c4 = oracle.sample_hop_cached(e["indptr"], idx, remap, cp, ci, want.nodes[:want.n_nodes[h]], b, h,
+                                                w.fanouts[h], w.rng_seed, pn, pd)
+            hits += int(c4[2]); host += int(c4[3])
+        blk = dci.Blocks(ctx, w.num_nodes, w.batch_size, w.fanouts)
+        stats = gu.new_stats()
+        dci.dci_sample_khop(ctx, g, cache, gu.dev(seeds), b, w.fanouts, w.rng_seed, blk, stats)
+        gu.assert_blocks_equal(gu.blocks_to_host(ctx, blk), want)
+        st = gu.stats_dict(ctx, stats)
+        assert (st["adj_edge_hits"], st["adj_edge_misses"]) == (hits, host) and hits > 0 and host > 0
+    finally:
+        e["indices"][:] = original

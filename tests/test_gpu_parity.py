@@ -212,6 +212,81 @@ def test_fill_caches_matches_oracle(env, budget, ts, tf, policy):
     _check_fill(env, budget, ts, tf, policy)
 
 
+def _element_counts(tiny, w):
+    _, ac, ec, _ = oracle.presample_count(tiny["indptr"], tiny["indices"], tiny["seeds"], w.batch_size, w.n_presample,
+                                          w.fanouts, w.rng_seed, w.presample_first_batch, with_edge_count=True)
+    fc = np.zeros(w.num_nodes, dtype=np.uint32)
+    return fc, ac, ec
+
+
+@pytest.mark.parametrize("c_adj", [0, 8, 24, 40_000, 300_000, 300_008, 300_016, 300_024, 900_001, 1_441_799, 1_441_800])
+def test_element_granular_fill_matches_oracle(env, c_adj):
+    """Algorithm 1 as printed: second-level sort inside the nodes (applied to the host lists as well) and a last
+    node cached in part.  Strict split with t_feature = 0 hands the whole budget to the adjacency cache."""
+    dci, gu, ctx, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "tiny", "w"))
+    fc, ac, ec = _element_counts(tiny, w)
+    g = gu.make_graph(tiny["indptr"], tiny["indices"].copy(), tiny["feat"])      # the fill rewrites the lists
+    want = oracle.fill_adj_element(tiny["indptr"], tiny["indices"], ec, c_adj)
+    remap, cp, ci, idx, pn, pd = want
+    cache = dci.dci_fill_caches(ctx, g, gu.dev(fc.view(np.int32)), gu.dev(ac.view(np.int32)), c_adj, 1, 0,
+                                dci.DCI_FILL_STRICT_SPLIT | dci.DCI_FILL_ADJ_ELEMENTS, edge_count=gu.dev(ec.view(np.int32)))
+    ctx.sync()
+    assert cache.cap_adj_bytes == c_adj and cache.feat_rows == 0
+    assert (cache.adj_nodes, cache.adj_edges) == (len(cp) - 1, len(ci))
+    assert (cache.adj_partial_node, cache.adj_partial_deg) == (pn, pd)
+    assert np.array_equal(cache.adj_remap.cpu().numpy(), remap)
+    assert np.array_equal(g.indices.numpy(), idx), "host lists after the fill"
+
+    def view(addr, n):
+        off = addr - cache.buf.data_ptr()
+        return cache.buf[off:off + 8 * n].view(torch.int64).cpu().numpy()
+
+    if cache.adj_nodes:
+        assert np.array_equal(view(cache.c.c_indptr, cache.adj_nodes + 1), cp)
+    if cache.adj_edges:
+        assert np.array_equal(view(cache.c.c_indices, cache.adj_edges), ci)
+    if c_adj in (300_016, 300_024):
+        assert pn >= 0
+
+
+def test_element_granular_cache_is_transparent_and_counts_hits_per_position(env):
+    dci, gu, ctx, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "tiny", "w"))
+    fc, ac, ec = _element_counts(tiny, w)
+    g = gu.make_graph(tiny["indptr"], tiny["indices"].copy(), tiny["feat"])
+    c_adj = 300_024
+    remap, cp, ci, idx, pn, pd = oracle.fill_adj_element(tiny["indptr"], tiny["indices"], ec, c_adj)
+    assert pn >= 0
+    cache = dci.dci_fill_caches(ctx, g, gu.dev(fc.view(np.int32)), gu.dev(ac.view(np.int32)), c_adj, 1, 0,
+                                dci.DCI_FILL_STRICT_SPLIT | dci.DCI_FILL_ADJ_ELEMENTS, edge_count=gu.dev(ec.view(np.int32)))
+    uploaded = gu.upload_cache(remap, cp, ci, np.full(w.num_nodes, -1), np.zeros((0, w.feat_dim), np.float32), pn, pd)
+    seeds = np.concatenate([tiny["seeds"][512:767], [pn]])
+    want = oracle.sample_khop(tiny["indptr"], idx, seeds, 2, w.fanouts, w.rng_seed)
+    hits = host = 0
+    for h in range(w.n_hops):
+        _, _, c4 = oracle.sample_hop_cached(tiny["indptr"], idx, remap, cp, ci, want.nodes[:want.n_nodes[h]], 2, h,
+                                            w.fanouts[h], w.rng_seed, pn, pd)
+        hits += int(c4[2]); host += int(c4[3])
+    assert host > 0
+    for c_ in (cache, uploaded):
+        blk = dci.Blocks(ctx, w.num_nodes, len(seeds), w.fanouts)
+        stats = gu.new_stats()
+        dci.dci_sample_khop(ctx, g, c_, gu.dev(seeds), 2, w.fanouts, w.rng_seed, blk, stats)
+        gu.assert_blocks_equal(gu.blocks_to_host(ctx, blk), want)
+        st = gu.stats_dict(ctx, stats)
+        assert (st["adj_edge_hits"], st["adj_edge_misses"]) == (hits, host)
+    # and the same blocks without any cache, from the reordered host lists alone
+    blk = dci.Blocks(ctx, w.num_nodes, len(seeds), w.fanouts)
+    dci.dci_sample_khop(ctx, g, None, gu.dev(seeds), 2, w.fanouts, w.rng_seed, blk)
+    gu.assert_blocks_equal(gu.blocks_to_host(ctx, blk), want)
+
+
+def test_element_granular_fill_needs_edge_counts(env):
+    dci, gu, ctx, g, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "graph", "tiny", "w"))
+    z = torch.zeros(w.num_nodes, dtype=torch.int32, device="cuda")
+    with pytest.raises(dci.DciError):
+        dci.dci_fill_caches(ctx, g, z, z, 1000, 1, 1, dci.DCI_FILL_ADJ_ELEMENTS)
+
+
 @pytest.mark.parametrize("budget,ts,tf", [(5_636_104, 9, 1), (5_000_000, 1, 9), (3_000_000, 0, 1), (3_000_000, 1, 0)])
 def test_fill_strict_split_and_single_cache(env, budget, ts, tf):
     """Eq. (1) without spill-over; t_sample = 0 gives the single-cache system (no adjacency cache)."""
