@@ -40,7 +40,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=54)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="medium", choices=["tiny", "medium", "large", "huge", "skewed"])
+    ap.add_argument("--workload", default="medium", choices=["tiny", "medium", "large", "huge", "skewed", "yelp", "amazon"])
     ap.add_argument("--features-in-hbm", action="store_true",
                     help="keep the feature matrix in device memory instead of pinned host memory (forced for the "
                          "huge and skewed workloads: the boxes pin at most about 60 GB)")

@@ -137,6 +137,10 @@ WORKLOADS: Dict[str, Workload] = {
                  64_000_000_000),
         Workload("skewed", 65_000_000, 1_800_000_000, 256, (10, 25), 500_000, 8_192, 256, 64,
                  48_000_000_000, rmat=(0.65, 0.15, 0.15)),
+        # the paper's two other datasets by shape (Table II), with the three-layer, hidden-128 models of
+        # Table III; run with the sum-aggregate GraphSAGE or the GCN of dci_gnn_forward
+        Workload("yelp", 716_480, 6_977_410, 300, (5, 10, 15), 100_000, 4_096, 128, 100, 1_000_000_000),
+        Workload("amazon", 1_598_960, 132_169_734, 200, (5, 10, 15), 200_000, 4_096, 128, 107, 2_000_000_000),
     ]
 }
 

@@ -173,3 +173,40 @@ def test_element_granular_cache_full_size(big):
         assert (st["adj_edge_hits"], st["adj_edge_misses"]) == (hits, host) and hits > 0 and host > 0
     finally:
         e["indices"][:] = original
+
+
+@pytest.fixture(scope="module")
+def yelp():
+    return _setup("yelp")
+
+
+@pytest.mark.parametrize("model", [1, 2])
+def test_table3_models_on_yelp_shape(yelp, model):
+    """The three-layer, hidden-128 sum-aggregate GraphSAGE and averaging GCN (Table III) on a graph of Yelp's shape
+    (Table II): one whole batch, dual cache filled, logits against the fp64 oracle."""
+    e = yelp
+    dci, gu, w, ctx, g = e["dci"], e["gu"], e["w"], e["ctx"], e["g"]
+    assert w.dims == (300, 128, 128, 100)
+    fc = torch.zeros(w.num_nodes, dtype=torch.int32, device="cuda")
+    ac = torch.zeros(w.num_nodes, dtype=torch.int32, device="cuda")
+    seeds_dev = gu.dev(e["seeds"])
+    dci.dci_presample_count(ctx, g, None, seeds_dev, w.batch_size, 0, w.n_presample, w.presample_first_batch, w.fanouts,
+                            w.rng_seed, fc, ac)
+    cache = dci.dci_fill_caches(ctx, g, fc, ac, 200_000_000, 3, 7, 0)
+    assert 0 < cache.feat_rows < w.num_nodes
+    blk = dci.Blocks(ctx, w.num_nodes, w.batch_size, w.fanouts)
+    x = torch.empty(blk.cap_nodes[-1], w.feat_dim, dtype=torch.float32, device="cuda")
+    logits = torch.empty(w.batch_size, w.classes, dtype=torch.float32, device="cuda")
+    ws, wn, bs = ([gu.dev(a) for a in e[k]] for k in ("ws", "wn", "bs"))
+    b = 3
+    sl = slice(b * w.batch_size, (b + 1) * w.batch_size)
+    dci.dci_sample_khop(ctx, g, cache, seeds_dev[sl], b, w.fanouts, w.rng_seed, blk)
+    dci.dci_gather_features(ctx, g, cache, blk.nodes, blk.cap_nodes[-1], x, n_dev=blk.n_input_dev())
+    dci.dci_gnn_forward(ctx, blk, x, model, None if model == 2 else ws, wn, bs, logits)
+    want = oracle.sample_khop(e["indptr"], e["indices"], e["seeds"][sl], b, w.fanouts, w.rng_seed)
+    gu.assert_blocks_equal(gu.blocks_to_host(ctx, blk), want)
+    want_x = oracle.gather(e["feat"], want.nodes)
+    assert x[:len(want.nodes)].cpu().numpy().tobytes() == want_x.tobytes()
+    ref = oracle.gnn_forward(model, want, want_x, e["ws"], e["wn"], e["bs"])
+    err = float(np.abs(logits.cpu().numpy() - ref).max())
+    assert err <= 1e-4 * max(1.0, float(np.abs(ref).max())), err
