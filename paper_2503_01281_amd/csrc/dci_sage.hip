@@ -460,7 +460,8 @@ __global__ __launch_bounds__(kWideThreads, 1) void k_sage_linear_wide(LinearArgs
   do {                                                                                \
     DCI_WAIT_FRAG(FC, LPW * (NS - 2));                                                \
     __builtin_amdgcn_s_barrier();                                                     \
-    DCI_SLAB_PTRS((idx) + NS);                                                        \
+    const char* ga_ = ga_run;                                                         \
+    const char* gw_ = gw_run;                                                         \
     __builtin_amdgcn_sched_barrier(0);                                                \
     DCI_MFMA_G(FC, 0, 0);                                                             \
     DCI_LOAD_A0((U) % 3);                                                             \
@@ -484,6 +485,14 @@ __global__ __launch_bounds__(kWideThreads, 1) void k_sage_linear_wide(LinearArgs
     DCI_DS_READ_B4(FN.b[0], FN.b[1], FN.b[2], FN.b[3], lb0, ((((U) + 1) % 3) * ST + kWideABytes) / 256); \
     __builtin_amdgcn_sched_barrier(0);                                                \
     DCI_MFMA_G(FC, 1, 3);                                                             \
+    /* running operand pointers: one slab on; at the end of the first operand over to the second */ \
+    ga_run += TK * 4;                                                                 \
+    gw_run += (size_t)TK * N * 4;                                                     \
+    if (++ks_run == Sf) {                                                             \
+      ks_run = 0;                                                                     \
+      ga_run = reinterpret_cast<const char*>(pA1);                                    \
+      gw_run = reinterpret_cast<const char*>(pW1);                                    \
+    }                                                                                 \
   } while (0)
 
     if (n > 0) {
@@ -495,6 +504,11 @@ __global__ __launch_bounds__(kWideThreads, 1) void k_sage_linear_wide(LinearArgs
       else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __builtin_amdgcn_s_barrier();
       DCI_READ(fa, 0);
+      // the slab the steady-state loop requests next (slab NS first): operand, slab within it, addresses
+      const bool run_second = NS >= Sf && !a.single;
+      int ks_run = run_second ? NS - Sf : NS;
+      const char* ga_run = reinterpret_cast<const char*>((run_second ? pA1 : pA0) + ks_run * TK);
+      const char* gw_run = reinterpret_cast<const char*>((run_second ? pW1 : pW0) + (size_t)ks_run * TK * N);
       int i = 0;
       for (; i + 5 + NS < n; i += 6) {  // i % 6 == 0: slab i+u sits in stage u % 3, all indices are valid slabs
         DCI_STEP(fa, fb, i, 0);
