@@ -430,11 +430,12 @@ def test_forward_many_rows(env, option):
     assert n_nodes[2] > 4096      # more than one 32-row block for each of the 128 workgroups of a column tile
 
 
-def test_wide_linear_kernel_in_several_passes(env):
-    """More than six 32-row blocks per workgroup: 60,000 rows through one 128-column tile over 256 workgroups.
+@pytest.mark.parametrize("M,K,N", [(60000, 40, 128), (120000, 40, 256)])
+def test_wide_linear_kernel_in_several_passes(env, M, K, N):
+    """More than six 32-row blocks per workgroup: 60,000 rows through one 128-column tile over 256 workgroups (two
+    passes of four blocks) and 120,000 rows through two tiles over 128 workgroups each (five passes of six).
     The block has no edges, so the layer is x W_self + b; the neighbour operand (all zeros) still takes the same path."""
     dci, gu, ctx = env["dci"], env["gu"], env["ctx"]
-    M, K, N = 60000, 40, 128
     blk = dci.Blocks(ctx, 10**6, M, (1,))
     assert blk.cap_nodes[0] >= M
     blk.counts.zero_()
@@ -451,12 +452,15 @@ def test_wide_linear_kernel_in_several_passes(env):
     x_dev = torch.zeros(blk.cap_nodes[1], K, dtype=torch.float32, device="cuda")
     x_dev[:M] = torch.from_numpy(x).cuda()
     logits = torch.full((blk.cap_nodes[0], N), float("nan"), dtype=torch.float32, device="cuda")
-    dci.dci_sage_forward(ctx, blk, x_dev, [gu.dev(a) for a in ws], [gu.dev(a) for a in wn], [gu.dev(a) for a in bs], logits)
-    ctx.sync()
+    ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, 2)     # the input is narrower than the default choice asks for
+    try:
+        dci.dci_sage_forward(ctx, blk, x_dev, [gu.dev(a) for a in ws], [gu.dev(a) for a in wn], [gu.dev(a) for a in bs], logits)
+        ctx.sync()
+    finally:
+        ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, 0)
     _logit_check(logits[:M].cpu().numpy(), want)
 
 
-@pytest.mark.parametrize("split", [1, 2, 0])
 def test_split_contraction_matches_oracle(env, split):
     """Few tiles: by default (0) the 64x64 kernel shares each tile between up to eight workgroups and a second
     kernel adds their partial sums; 1 switches that off, 2 limits it to two."""
