@@ -461,6 +461,7 @@ def test_wide_linear_kernel_in_several_passes(env, M, K, N):
     _logit_check(logits[:M].cpu().numpy(), want)
 
 
+@pytest.mark.parametrize("split", [1, 2, 0])
 def test_split_contraction_matches_oracle(env, split):
     """Few tiles: by default (0) the 64x64 kernel shares each tile between up to eight workgroups and a second
     kernel adds their partial sums; 1 switches that off, 2 limits it to two."""
