@@ -55,8 +55,9 @@ def main() -> int:
                          "last node cached in part; pre-sampling then also counts per element")
     ap.add_argument("--model", default="sage-mean", choices=["sage-mean", "sage-sum", "gcn-avg"],
                     help="GNN of the forward pass (Table III); the headline configuration is sage-mean")
-    ap.add_argument("--linear-kernel", type=int, default=0, choices=[0, 1, 2],
-                    help="dense-layer kernel of the timed region: 0 by shape (default), 1 tile kernel, 2 wide kernel")
+    ap.add_argument("--linear-kernel", type=int, default=0, choices=[0, 1, 2, 3],
+                    help="dense-layer kernel of the timed region: 0 by shape (default), 1 register-staged tile kernel, "
+                         "2 wide kernel, 3 by shape without the wide kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batches", type=int, default=8, help="batches the CPU oracle is timed on")
     ap.add_argument("--streams", type=int, default=1,
@@ -286,7 +287,7 @@ def main() -> int:
             traffic = json.load(open(tpath)).get(f"{dominant}:{w.name}")
         except Exception:
             traffic = None
-    roofline = {"kernel": "k_sage_linear_wide (first layer)" if args.linear_kernel != 1 and w.dims[1] % 128 == 0 and w.dims[0] % 2 == 0 and (w.dims[0] >= 160 or args.linear_kernel == 2)
+    roofline = {"kernel": "k_sage_linear_wide (first layer)" if args.linear_kernel in (0, 2) and w.dims[1] % 128 == 0 and w.dims[0] % 2 == 0 and (w.dims[0] >= 160 or args.linear_kernel == 2)
                 else "k_sage_linear (first layer)", "bound": "mfma", "achieved": round(lin_tflops, 3),
                 "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(lin_tflops / FP32_MFMA_PEAK_TFLOPS, 4),
                 "traffic": traffic, "launches": lin_n, "avg_launch_ms": round(lin_ms / max(lin_n, 1), 4),

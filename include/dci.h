@@ -147,9 +147,11 @@ const char* dci_last_error(const dci_ctx* ctx);
  *       0  by shape (default): the wide kernel (128-column tiles, one workgroup per compute unit)
  *          when the layer is at least 16384 rows tall by capacity, its input width is even and
  *          at least 160, its output width is a multiple of 128 and the operands are suitably
- *          aligned; else the 64x64 tile kernel
- *       1  always the 64x64 tile kernel
- *       2  the wide kernel whenever width and alignment allow it, whatever the row count */
+ *          aligned; else a 64x64 tile kernel, fed by global->LDS loads where the output width is a multiple of 64, the
+ *          input width even and the contraction not split, through registers otherwise
+ *       1  always the 64x64 tile kernel that stages its operands through registers
+ *       2  the wide kernel whenever width and alignment allow it, whatever the row count
+ *       3  like 0 without the wide kernel */
 #define DCI_OPT_LINEAR_KERNEL 1
 /*   DCI_OPT_LINEAR_SPLIT   upper limit on the workgroups that share one output tile of the 64x64 kernel
  *       (the contraction is split between them and a second kernel adds the partial sums in a fixed order):

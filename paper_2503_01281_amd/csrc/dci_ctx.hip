@@ -123,7 +123,7 @@ const char* dci_last_error(const dci_ctx* ctx) { return ctx ? ctx->err : "null c
 int32_t dci_set_option(dci_ctx* ctx, int32_t option, int64_t value) {
   if (!ctx) return DCI_ERR_INVALID_ARG;
   if (option == DCI_OPT_LINEAR_KERNEL) {
-    if (value < 0 || value > 2) return dci::fail(ctx, DCI_ERR_INVALID_ARG, "DCI_OPT_LINEAR_KERNEL takes 0, 1 or 2, not %lld", (long long)value);
+    if (value < 0 || value > 3) return dci::fail(ctx, DCI_ERR_INVALID_ARG, "DCI_OPT_LINEAR_KERNEL takes 0 .. 3, not %lld", (long long)value);
     ctx->linear_kernel = (int)value;
     return DCI_OK;
   }

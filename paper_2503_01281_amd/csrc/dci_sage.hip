@@ -595,6 +595,190 @@ __global__ __launch_bounds__(kWideThreads, 1) void k_sage_linear_wide(LinearArgs
 #undef DCI_STEP
 }
 
+// ---- 64x64 tiles fed by global->LDS loads ---------------------------------------------------
+// The tile kernel's shape (one 32x32 tile per wavefront, four wavefronts, XCD-aware order) with the
+// wide kernel's data path: 16-byte global->LDS loads (two per wave and slab), three stages of
+// 16-deep slabs, inline-assembly fragment reads with immediate offsets, no vector-ALU work in the
+// steady-state loop.  Its slab costs about 0.4 us where the register path needs 0.6-0.8 us, which
+// is what counts for layers of a few thousand rows (every workgroup walks the whole contraction)
+// and for narrow inputs; at tens of thousands of rows and wide inputs it has no edge over the tile
+// kernel and loses to the wide one.  Needs an output width that is a multiple of 64, an even
+// input width, 8-byte aligned rows and 16-byte aligned weights.
+struct FragD {
+  float4v a0, a1;           // t = 0, 1: four consecutive k of this lane's row
+  float2v b0, b1, b2, b3;   // steps (0: 0,1), (0: 2,3), (1: 0,1), (1: 2,3) of this lane's column
+};
+constexpr int kDmaStages = 3, kDmaStageBytes = (TM * TK + TK * TN) * 4;  // 8 KB
+static_assert(TM == 64 && TN == 64 && TK == 16, "the layout below is written for 64x64x16");
+
+#define DCI_D_READ(f, STG)                                                                                            \
+  asm volatile("ds_read_b128 %0, %6 offset:%9\n\tds_read_b128 %1, %7 offset:%9\n\t"                                  \
+               "ds_read2st64_b32 %2, %8 offset0:%10 offset1:%11\n\tds_read2st64_b32 %3, %8 offset0:%12 offset1:%13\n\t" \
+               "ds_read2st64_b32 %4, %8 offset0:%14 offset1:%15\n\tds_read2st64_b32 %5, %8 offset0:%16 offset1:%17"  \
+               : "=&v"(f.a0), "=&v"(f.a1), "=&v"(f.b0), "=&v"(f.b1), "=&v"(f.b2), "=&v"(f.b3)                         \
+               : "v"(la0), "v"(la1), "v"(lb0), "n"((STG)*kDmaStageBytes), "n"((STG)*32 + 16), "n"((STG)*32 + 17),     \
+                 "n"((STG)*32 + 18), "n"((STG)*32 + 19), "n"((STG)*32 + 24), "n"((STG)*32 + 25), "n"((STG)*32 + 26),  \
+                 "n"((STG)*32 + 27)                                                                                   \
+               : "memory")
+#define DCI_D_WAIT(f, VM)                                                                                             \
+  do {                                                                                                                \
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(VM) : "memory");                                              \
+    asm volatile("" : "+v"(f.a0), "+v"(f.a1), "+v"(f.b0), "+v"(f.b1), "+v"(f.b2), "+v"(f.b3)::"memory");              \
+  } while (0)
+
+__global__ __launch_bounds__(kGemmThreads) void k_sage_linear_dma(LinearArgs a) {
+  constexpr int NS = kDmaStages, ST = kDmaStageBytes, A_BYTES = TM * TK * 4, LPW = 2;
+  __shared__ __attribute__((aligned(1024))) char lds[NS * ST];
+  const long long M = a.counts[a.hop];
+  const int id = (int)blockIdx.x;
+  const int xcd = id & 7, jj = id >> 3;
+  const int nt = jj % a.n_tiles_n;
+  const long long row0 = ((long long)(jj / a.n_tiles_n) * 8 + xcd) * TM;
+  const int col0 = nt * TN;
+  if (row0 >= M) return;
+  const int tid = (int)threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int K = a.K, N = a.N;
+  const int Sf = K / TK;
+  const int n = a.single ? Sf : 2 * Sf;
+  const int k_tail = K - Sf * TK;
+  // this wave's share of a slab: rows 16*wave .. +15 of A (lane -> row, chunk of four k; chunk position
+  // xor-ed with row bits), k rows 4*wave .. +3 of B (column halves swapped in every second group of four rows)
+  const int c_a = (lane & 3) ^ ((lane >> 4) & 3);
+  long long r_l = row0 + 16 * wave + (lane >> 2);
+  if (r_l > M - 1) r_l = M - 1;
+  const unsigned voffA = (unsigned)(((r_l - row0) * K + c_a * 4) * 4);
+  const int krB = 4 * wave + (lane >> 4);
+  const unsigned voffB = (unsigned)((krB * N + (((lane & 15) ^ (8 * (wave & 1))) * 4)) * 4);
+  const float* pA0 = (a.single ? a.a_neigh : a.a_self) + row0 * K;
+  const float* pA1 = a.a_neigh + row0 * K;
+  const float* pW0 = (a.single ? a.w_neigh : a.w_self) + col0;
+  const float* pW1 = a.w_neigh + col0;
+  char* const ldsw = lds + 1024 * wave;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int h = lane >> 5, ll = lane & 31;
+  const int am = wm * 32 + ll;
+  const unsigned lds0 = (unsigned)(size_t)(lptr_t)lds;
+  const unsigned la0 = lds0 + am * 64 + ((h ^ ((am >> 2) & 3)) * 16);
+  const unsigned la1 = la0 ^ 32u;
+  const unsigned lb0 = lds0 + 4 * h * TN * 4 + (((wn * 32 + ll) ^ (32 * h)) * 4);  // the B region offset sits in the immediates
+  floatx16 acc0, acc1;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    acc0[r] = 0.f;
+    acc1[r] = 0.f;
+  }
+
+#define DCI_D_ISSUE(s_, STG)                                                                                  \
+  do {                                                                                                        \
+    const bool second_ = (s_) >= Sf && !a.single;                                                             \
+    const int ks_ = second_ ? (s_) - Sf : (s_);                                                               \
+    const char* ga_ = reinterpret_cast<const char*>((second_ ? pA1 : pA0) + ks_ * TK);                        \
+    const char* gw_ = reinterpret_cast<const char*>((second_ ? pW1 : pW0) + (size_t)ks_ * TK * N);            \
+    __builtin_amdgcn_global_load_lds((gptr_t)(ga_ + voffA), (lptr_t)(ldsw + (STG)*ST), 16, 0, 0);             \
+    __builtin_amdgcn_global_load_lds((gptr_t)(gw_ + voffB), (lptr_t)(ldsw + (STG)*ST + A_BYTES), 16, 0, 0);   \
+  } while (0)
+#define DCI_D_MFMA(f)                                                              \
+  do {                                                                             \
+    __builtin_amdgcn_sched_barrier(0);                                             \
+    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a0.x, f.b0.x, acc0, 0, 0, 0);    \
+    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a0.y, f.b0.y, acc1, 0, 0, 0);    \
+    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a0.z, f.b1.x, acc0, 0, 0, 0);    \
+    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a0.w, f.b1.y, acc1, 0, 0, 0);    \
+    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a1.x, f.b2.x, acc0, 0, 0, 0);    \
+    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a1.y, f.b2.y, acc1, 0, 0, 0);    \
+    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a1.z, f.b3.x, acc0, 0, 0, 0);    \
+    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a1.w, f.b3.y, acc1, 0, 0, 0);    \
+    __builtin_amdgcn_sched_barrier(0);                                             \
+  } while (0)
+#define DCI_D_STEP(FC, FN, idx, U)     \
+  do {                                 \
+    DCI_D_WAIT(FC, LPW * (NS - 2));    \
+    __builtin_amdgcn_s_barrier();      \
+    DCI_D_ISSUE((idx) + NS, (U) % 3);  \
+    DCI_D_READ(FN, ((U) + 1) % 3);     \
+    DCI_D_MFMA(FC);                    \
+  } while (0)
+
+  if (n > 0) {
+    FragD fa, fb;
+    if (n > 0) DCI_D_ISSUE(0, 0);
+    if (n > 1) DCI_D_ISSUE(1, 1);
+    if (n > 2) DCI_D_ISSUE(2, 2);
+    if (n >= NS) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPW * (NS - 1)) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    DCI_D_READ(fa, 0);
+    int i = 0;
+    for (; i + 5 + NS < n; i += 6) {  // i % 6 == 0: slab i+u sits in stage u % 3, all indices are valid slabs
+      DCI_D_STEP(fa, fb, i, 0);
+      DCI_D_STEP(fb, fa, i + 1, 1);
+      DCI_D_STEP(fa, fb, i + 2, 2);
+      DCI_D_STEP(fb, fa, i + 3, 3);
+      DCI_D_STEP(fa, fb, i + 4, 4);
+      DCI_D_STEP(fb, fa, i + 5, 5);
+    }
+    for (; i + 1 < n; ++i) {  // drain: stage chosen at run time, every wait is for everything
+      DCI_D_WAIT(fa, 0);
+      __builtin_amdgcn_s_barrier();
+      if (i + NS < n) {
+        const int st_ = i % NS;
+        if (st_ == 0) DCI_D_ISSUE(i + NS, 0);
+        else if (st_ == 1) DCI_D_ISSUE(i + NS, 1);
+        else DCI_D_ISSUE(i + NS, 2);
+      }
+      const int sn_ = (i + 1) % NS;
+      if (sn_ == 0) DCI_D_READ(fb, 0);
+      else if (sn_ == 1) DCI_D_READ(fb, 1);
+      else DCI_D_READ(fb, 2);
+      DCI_D_MFMA(fa);
+      fa = fb;
+    }
+    DCI_D_WAIT(fa, 0);
+    DCI_D_MFMA(fa);
+  }
+  if (k_tail > 0) {
+    // the last k_tail columns of each operand: masked loads through registers into stage 0
+    const int n_ops = a.single ? 1 : 2;
+    for (int o = 0; o < n_ops; ++o) {
+      const float* A = (o == 1 ? pA1 : pA0) + Sf * TK;
+      const float* W = (o == 1 ? pW1 : pW0) + (size_t)Sf * TK * N;
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        v[e] = (Sf * TK + 4 * c_a + e < K)
+                   ? *reinterpret_cast<const float*>(reinterpret_cast<const char*>(A + e) + voffA)
+                   : 0.f;
+      const float4 w = (Sf * TK + krB < K) ? *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(W) + voffB)
+                                           : make_float4(0.f, 0.f, 0.f, 0.f);
+      __syncthreads();  // every wave has its fragments of the slab that used stage 0 last
+      *reinterpret_cast<float4*>(ldsw + lane * 16) = make_float4(v[0], v[1], v[2], v[3]);
+      *reinterpret_cast<float4*>(ldsw + A_BYTES + lane * 16) = w;
+      __syncthreads();
+      FragD f;
+      DCI_D_READ(f, 0);
+      DCI_D_WAIT(f, 0);
+      DCI_D_MFMA(f);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc0[r] += acc1[r];
+  const int col = col0 + wn * 32 + ll;
+  const float b = a.bias[col];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const long long row = row0 + wm * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+    if (row < M) {
+      float v = acc0[r] + b;
+      if (a.relu) v = v > 0.f ? v : 0.f;
+      a.y[row * N + col] = v;
+    }
+  }
+#undef DCI_D_ISSUE
+#undef DCI_D_MFMA
+#undef DCI_D_STEP
+}
+
 struct SageWs {
   float* m;
   float* y[2];
@@ -748,7 +932,10 @@ int32_t dci_gnn_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_i
     const int g_n = n_tiles_w > 0 ? (ctx->num_cus / 8 / n_tiles_w) * 8 : 0;
     const bool wide_ok = Do % kWideCols == 0 && D % 2 == 0 && g_n >= 8 && vb == 4 && aligned(x, 8) &&
                          aligned(ws.m, 8) && aligned(bias[l], 4);
-    const bool use_wide = wide_ok && ctx->linear_kernel != 1 && (ctx->linear_kernel == 2 || (cap >= kWideMinRows && D >= kWideMinWidth));
+    const bool use_wide = wide_ok && (ctx->linear_kernel == 2 || (ctx->linear_kernel == 0 && cap >= kWideMinRows && D >= kWideMinWidth));
+    // 64x64 tiles fed by global->LDS loads: unsplit layers whose widths and alignment allow it
+    const bool dma_ok = Do % TN == 0 && D % 2 == 0 && vb == 4 && va >= 2 && la.split == 1;
+    const bool use_dma = !use_wide && dma_ok && (ctx->linear_kernel == 0 || ctx->linear_kernel == 3);
     {
       Timed timed(ctx, l == 0 ? DCI_K_LINEAR_IN : DCI_K_LINEAR);
       if (use_wide) {
@@ -759,6 +946,8 @@ int32_t dci_gnn_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_i
         else
           hipLaunchKernelGGL(k_sage_linear_wide<false>, dim3((unsigned)(g_n * n_tiles_w)), dim3(kWideThreads), 0,
                              ctx->stream, la, g_n);
+      } else if (use_dma) {
+        hipLaunchKernelGGL(k_sage_linear_dma, dim3((unsigned)n_tiles), dim3(kGemmThreads), 0, ctx->stream, la);
       } else if (va == 4 && vb == 4)
         hipLaunchKernelGGL((k_sage_linear<4, 4>), grid, dim3(kGemmThreads), 0, ctx->stream, la);
       else if (va == 4)
@@ -771,7 +960,7 @@ int32_t dci_gnn_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_i
         hipLaunchKernelGGL((k_sage_linear<1, 4>), grid, dim3(kGemmThreads), 0, ctx->stream, la);
       else
         hipLaunchKernelGGL((k_sage_linear<1, 1>), grid, dim3(kGemmThreads), 0, ctx->stream, la);
-      if (!use_wide && la.split > 1) {
+      if (!use_wide && !use_dma && la.split > 1) {
         int64_t rb = (cap * Do + 255) / 256;
         if (rb > (int64_t)ctx->num_cus * 8) rb = (int64_t)ctx->num_cus * 8;
         hipLaunchKernelGGL(k_split_reduce, dim3((unsigned)rb), dim3(256), 0, ctx->stream, la);

@@ -422,7 +422,22 @@ def test_wide_linear_kernel_matches_oracle(env, model, dims, fanouts, n_seeds):
     _forward_case(env, dims, fanouts, n_seeds, model, option=2)
 
 
-@pytest.mark.parametrize("option", [0, 1])
+@pytest.mark.parametrize("model", [0, 2])
+@pytest.mark.parametrize("dims,fanouts,n_seeds", [((602, 256, 128), (3, 4), 70), ((100, 64, 192, 64), (2, 3, 4), 33),
+                                                  ((8, 64), (7,), 129), ((16, 128), (5,), 1), ((48, 64, 64), (5, 5), 300),
+                                                  ((256, 512, 320), (10, 25), 40)])
+def test_dma_tile_kernel_matches_oracle(env, model, dims, fanouts, n_seeds):
+    """The 64x64 kernel fed by global->LDS loads (kernel choice 3, contraction not split): input widths with and
+    without a k tail, fewer k-slabs than pipeline stages, one to eight column tiles, both operand counts."""
+    dci, ctx = env["dci"], env["ctx"]
+    ctx.set_option(dci.DCI_OPT_LINEAR_SPLIT, 1)
+    try:
+        _forward_case(env, dims, fanouts, n_seeds, model, option=3)
+    finally:
+        ctx.set_option(dci.DCI_OPT_LINEAR_SPLIT, 0)
+
+
+@pytest.mark.parametrize("option", [0, 1, 3])
 def test_forward_many_rows(env, option):
     """A layer tall enough for the default choice to take the wide kernel with several row blocks per workgroup
     (option 0), against the same through the tile kernel (option 1)."""
@@ -478,7 +493,7 @@ def test_split_contraction_matches_oracle(env, split):
 def test_set_option_rejects_bad_values(env):
     dci, ctx = env["dci"], env["ctx"]
     with pytest.raises(dci.DciError):
-        ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, 3)
+        ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, 4)
     with pytest.raises(dci.DciError):
         ctx.set_option(dci.DCI_OPT_LINEAR_SPLIT, 9)
     with pytest.raises(dci.DciError):
