@@ -287,7 +287,7 @@ def main() -> int:
             traffic = json.load(open(tpath)).get(f"{dominant}:{w.name}")
         except Exception:
             traffic = None
-    roofline = {"kernel": "k_sage_linear_wide (first layer)" if args.linear_kernel in (0, 2) and w.dims[1] % 128 == 0 and w.dims[0] % 2 == 0 and (w.dims[0] >= 160 or args.linear_kernel == 2)
+    roofline = {"kernel": "k_sage_linear_wide (first layer)" if args.linear_kernel in (0, 2) and w.dims[1] % 128 == 0 and w.dims[0] % 2 == 0 and (w.dims[0] >= 192 or args.linear_kernel == 2)
                 else "k_sage_linear (first layer)", "bound": "mfma", "achieved": round(lin_tflops, 3),
                 "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(lin_tflops / FP32_MFMA_PEAK_TFLOPS, 4),
                 "traffic": traffic, "launches": lin_n, "avg_launch_ms": round(lin_ms / max(lin_n, 1), 4),

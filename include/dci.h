@@ -146,7 +146,7 @@ const char* dci_last_error(const dci_ctx* ctx);
  *   DCI_OPT_LINEAR_KERNEL  which dense-layer kernel dci_sage_forward / dci_gnn_forward launch:
  *       0  by shape (default): the wide kernel (128-column tiles, one workgroup per compute unit)
  *          when the layer is at least 16384 rows tall by capacity, its input width is even and
- *          at least 160, its output width is a multiple of 128 and the operands are suitably
+ *          at least 192, its output width is a multiple of 128 and the operands are suitably
  *          aligned; else a 64x64 tile kernel, fed by global->LDS loads where the output width is a multiple of 64, the
  *          input width even and the contraction not split, through registers otherwise
  *       1  always the 64x64 tile kernel that stages its operands through registers

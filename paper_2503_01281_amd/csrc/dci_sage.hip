@@ -312,7 +312,7 @@ typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
 constexpr long long kWideMinRows = 16384;  // below this capacity the 64x64 kernel (with its split contraction) fills the chip better
-constexpr int kWideMinWidth = 160;  // narrower inputs spend the kernel in its pipeline fill and drain (measured cross-over)
+constexpr int kWideMinWidth = 192;  // narrower inputs spend the kernel in its pipeline fill and drain (measured cross-over with the 64x64 kernel)
 constexpr int kWideThreads = 512, kWideCols = 128, kWideStages = 3, kWideMaxBlocks = 6;
 constexpr int kWideABytes = kWideMaxBlocks * 32 * 64;           // 192 rows x 16 k x 4 B
 constexpr int kWideBBytes = TK * kWideCols * 4;                 // 16 k x 128 columns x 4 B
