@@ -287,8 +287,14 @@ def main() -> int:
             traffic = json.load(open(tpath)).get(f"{dominant}:{w.name}")
         except Exception:
             traffic = None
-    roofline = {"kernel": "k_sage_linear_wide (first layer)" if args.linear_kernel in (0, 2) and w.dims[1] % 128 == 0 and w.dims[0] % 2 == 0 and (w.dims[0] >= 192 or args.linear_kernel == 2)
-                else "k_sage_linear (first layer)", "bound": "mfma", "achieved": round(lin_tflops, 3),
+    if args.linear_kernel in (0, 2) and w.dims[1] % 128 == 0 and w.dims[0] % 2 == 0 and (w.dims[0] >= 192 or args.linear_kernel == 2):
+        lin_kernel = "k_sage_linear_wide"
+    elif (args.linear_kernel in (0, 3) and w.dims[1] % 64 == 0 and w.dims[0] % 2 == 0
+          and ((blk.cap_nodes[w.n_hops - 1] + 63) // 64 + 7) // 8 * 8 * (w.dims[1] // 64) > 256):   # else the split path
+        lin_kernel = "k_sage_linear_dma"
+    else:
+        lin_kernel = "k_sage_linear"
+    roofline = {"kernel": lin_kernel + " (first layer)", "bound": "mfma", "achieved": round(lin_tflops, 3),
                 "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(lin_tflops / FP32_MFMA_PEAK_TFLOPS, 4),
                 "traffic": traffic, "launches": lin_n, "avg_launch_ms": round(lin_ms / max(lin_n, 1), 4),
                 "flops_per_launch": round(flops_in / max(lin_n, 1), 1)}
