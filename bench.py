@@ -290,7 +290,7 @@ def main() -> int:
     if args.linear_kernel in (0, 2) and w.dims[1] % 128 == 0 and w.dims[0] % 2 == 0 and (w.dims[0] >= 192 or args.linear_kernel == 2):
         lin_kernel = "k_sage_linear_wide"
     elif (args.linear_kernel in (0, 3) and w.dims[1] % 64 == 0 and w.dims[0] % 2 == 0
-          and ((blk.cap_nodes[w.n_hops - 1] + 63) // 64 + 7) // 8 * 8 * (w.dims[1] // 64) > 256):   # else the split path
+          and ((blk.cap_nodes[w.n_hops - 1] + 63) // 64 + 7) // 8 * 8 * (w.dims[1] // 64) > 128):   # else the split path
         lin_kernel = "k_sage_linear_dma"
     else:
         lin_kernel = "k_sage_linear"
