@@ -476,6 +476,51 @@ def test_wide_linear_kernel_in_several_passes(env, M, K, N):
     _logit_check(logits[:M].cpu().numpy(), want)
 
 
+def test_dense_layer_kernels_on_random_shapes(env):
+    """Forty random layer shapes through every kernel choice: row counts around the 32- and 64-row tile edges,
+    input widths from 1 to 330 (k tails, fewer slabs than pipeline stages, odd widths), output widths that are and
+    are not multiples of 64 / 128.  One block without edges for the two-operand layer (x W_self + b) and the GCN
+    layer (x W + b, the row itself being its only aggregate)."""
+    dci, gu, ctx = env["dci"], env["gu"], env["ctx"]
+    rng = np.random.default_rng(77)
+    widths_out = [1, 5, 41, 47, 64, 100, 128, 172, 192, 256, 320, 384]
+    for case in range(40):
+        M = int(rng.choice([1, 31, 32, 33, 63, 64, 65, 200, 1000, 2049, 3000]))
+        K = int(rng.choice([1, 2, 7, 8, 15, 16, 17, 31, 32, 48, 63, 64, 100, 130, 256, 330]))
+        N = int(rng.choice(widths_out))
+        model = int(rng.choice([0, 2]))
+        option = int(rng.choice([0, 1, 2, 3]))
+        split = int(rng.choice([0, 1]))
+        blk = dci.Blocks(ctx, 10**6, M, (1,))
+        blk.counts.zero_()
+        blk.counts[0] = M
+        blk.counts[1] = M
+        blk.blk_indptr[0].zero_()
+        x = rng.standard_normal((M, K), dtype=np.float32)
+        ws, wn, bs = synth.sage_weights((K, N), 100 + case)
+        want_blk = oracle.Blocks(n_nodes=np.array([M, M]), n_edges=np.array([0]), nodes=np.arange(M, dtype=np.int64),
+                                 blk_indptr=[np.zeros(M + 1, dtype=np.int64)], blk_src=[np.zeros(0, dtype=np.int32)],
+                                 src_global=[np.zeros(0, dtype=np.int64)], src_pos=[np.zeros(0, dtype=np.int64)])
+        want = oracle.gnn_forward(model, want_blk, x, ws, wn, bs)
+        x_dev = torch.zeros(blk.cap_nodes[1], K, dtype=torch.float32, device="cuda")
+        x_dev[:M] = torch.from_numpy(x).cuda()
+        logits = torch.full((blk.cap_nodes[0], N), float("nan"), dtype=torch.float32, device="cuda")
+        ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, option)
+        ctx.set_option(dci.DCI_OPT_LINEAR_SPLIT, split)
+        try:
+            dci.dci_gnn_forward(ctx, blk, x_dev, model, [gu.dev(a) for a in ws], [gu.dev(a) for a in wn],
+                                [gu.dev(a) for a in bs], logits)
+            ctx.sync()
+        finally:
+            ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, 0)
+            ctx.set_option(dci.DCI_OPT_LINEAR_SPLIT, 0)
+        got = logits.cpu().numpy()
+        tol = 1e-4 * max(1.0, float(np.abs(want).max()))
+        err = float(np.abs(got[:M].astype(np.float64) - want).max())
+        assert err <= tol, f"case {case}: M={M} K={K} N={N} model={model} kernel={option} split={split}: {err} > {tol}"
+        assert np.isnan(got[M:]).all(), f"case {case}: rows beyond the batch were written"
+
+
 @pytest.mark.parametrize("split", [1, 2, 0])
 def test_split_contraction_matches_oracle(env, split):
     """Few tiles: by default (0) the 64x64 kernel shares each tile between up to eight workgroups and a second
