@@ -249,6 +249,38 @@ def test_element_granular_fill_matches_oracle(env, c_adj):
         assert pn >= 0
 
 
+def test_element_granular_fill_on_small_graphs_with_random_counts(env, small_graphs):
+    """Small graphs (isolated nodes, a self loop, duplicate edges), random element counts with many zeros and ties,
+    budgets from nothing to everything: remap, cache arrays, the partly cached node and the rewritten host lists."""
+    dci, gu, ctx = env["dci"], env["gu"], env["ctx"]
+    rng = np.random.default_rng(31)
+    for indptr, indices in small_graphs:
+        n, e = len(indptr) - 1, len(indices)
+        feat = np.zeros((n, 4), dtype=np.float32)
+        whole = (n + 1 + e) * 8
+        for trial in range(5):
+            ec = (rng.integers(0, 5, e) * rng.integers(0, 2, e)).astype(np.uint32)
+            ac = np.add.reduceat(np.concatenate([ec, [0]]).astype(np.uint64), indptr[:-1])[:n] if e else np.zeros(n, np.uint64)
+            ac = np.where(np.diff(indptr) > 0, ac, 0).astype(np.uint32)
+            for c_adj in [0, 16, 40, int(rng.integers(16, whole)), int(rng.integers(16, whole)), whole - 1, whole]:
+                g = gu.make_graph(indptr, indices.copy(), feat)
+                remap, cp, ci, idx, pn, pd = oracle.fill_adj_element(indptr, indices, ec, c_adj)
+                cache = dci.dci_fill_caches(ctx, g, gu.dev(np.zeros(n, np.int32)), gu.dev(ac.view(np.int32)), c_adj, 1, 0,
+                                            dci.DCI_FILL_STRICT_SPLIT | dci.DCI_FILL_ADJ_ELEMENTS,
+                                            edge_count=gu.dev(ec.view(np.int32)) if e else torch.zeros(1, dtype=torch.int32, device="cuda"))
+                ctx.sync()
+                what = f"n={n} e={e} trial={trial} c_adj={c_adj}"
+                assert (cache.adj_nodes, cache.adj_edges) == (len(cp) - 1, len(ci)), what
+                assert (cache.adj_partial_node, cache.adj_partial_deg) == (pn, pd), what
+                assert np.array_equal(cache.adj_remap.cpu().numpy(), remap), what
+                assert np.array_equal(g.indices.numpy(), idx), what
+                view = lambda addr, k: cache.buf[addr - cache.buf.data_ptr():addr - cache.buf.data_ptr() + 8 * k].view(torch.int64).cpu().numpy()
+                if cache.adj_nodes:
+                    assert np.array_equal(view(cache.c.c_indptr, cache.adj_nodes + 1), cp), what
+                if cache.adj_edges:
+                    assert np.array_equal(view(cache.c.c_indices, cache.adj_edges), ci), what
+
+
 def test_element_granular_cache_is_transparent_and_counts_hits_per_position(env):
     dci, gu, ctx, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "tiny", "w"))
     fc, ac, ec = _element_counts(tiny, w)
