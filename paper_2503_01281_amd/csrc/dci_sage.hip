@@ -1,12 +1,19 @@
-// GraphSAGE-mean forward over the blocks of one mini-batch (Table III family, mean aggregator).
+// Forward pass over the blocks of one mini-batch: GraphSAGE with the mean aggregator, and the two
+// models of Table III (GraphSAGE with the sum aggregator, GCN with the averaging one).
 //
-// Per layer two kernels:
-//   k_sage_mean   - m_i = mean of x[src] over row i of the block (bandwidth bound: one lane group
-//                   per destination row, consecutive lanes on consecutive chunks of the row);
-//   k_sage_linear - y = x W_self + m W_neigh + b (+ ReLU): one dense contraction over the
-//                   concatenated K = 2*D axis on the matrix cores (v_mfma_f32_32x32x2f32, fp32 in,
-//                   fp32 accumulate), operands staged through LDS in k-major order so that
-//                   fragment reads are conflict free.
+// Per layer:
+//   k_sage_mean        - m_i = mean (or sum; for GCN the mean over the row itself and its sources) of
+//                        x[src] over row i of the block; bandwidth bound: one lane group per
+//                        destination row, consecutive lanes on consecutive chunks of the row;
+//   a dense-layer kernel - y = x W_self + m W_neigh + b (+ ReLU) (GCN: y = m W + b): one contraction
+//                        over the concatenated axis on the matrix cores (v_mfma_f32_32x32x2f32, fp32 in,
+//                        fp32 accumulate).  Three of them, chosen by the layer's shape:
+//       k_sage_linear_wide  192x128 passes, one workgroup per compute unit, global->LDS loads
+//                           (tall layers with wide inputs);
+//       k_sage_linear_dma   64x64 tiles, global->LDS loads (output width a multiple of 64);
+//       k_sage_linear       64x64 tiles staged through registers, any width and alignment, with the
+//                           contraction split over several workgroups (+ k_split_reduce) when the
+//                           layer has few tiles.
 // Row counts come from the block's device-side `counts`, so no host round trip is needed; the
 // grids are sized for the capacities and surplus workgroups leave at once.
 #include "dci_internal.h"
@@ -89,12 +96,10 @@ __global__ __launch_bounds__(kMeanBlock) void k_sage_mean(const long long* __res
 // y[M, N] = a_self[M, K] w_self[K, N] + a_neigh[M, K] w_neigh[K, N] + bias, i.e. one contraction
 // over the concatenated axis of length 2K.  M is read from device memory.
 //
-// Tiling: 64x64 outputs per workgroup of four wavefronts, each wavefront one 32x32 MFMA tile
-// (v_mfma_f32_32x32x2f32: lane l feeds A[l%32][l/32] and B[l/32][l%32]).  fp32 matrix math is
-// slow enough (64 cycles per instruction) that small tiles keep the matrix cores fed, and the
-// row counts of a mini-batch are small enough (thousands) that large tiles would leave most of
-// the 256 compute units idle.  Operands go global -> registers -> LDS (k-major, so fragment
-// reads hit consecutive banks) with the next k-slab in flight while the current one is used.
+// k_sage_linear: 64x64 outputs per workgroup of four wavefronts, each wavefront one 32x32 MFMA tile
+// (v_mfma_f32_32x32x2f32: lane l feeds A[l%32][l/32] and B[l/32][l%32]).  Operands go global ->
+// registers -> LDS (k-major, so fragment reads hit consecutive banks) with the next k-slab in
+// flight while the current one is used; every load is masked, so any width and alignment works.
 // Workgroup ids are mapped so that the column tiles of one row tile run on the same XCD and
 // share its L2.
 constexpr int TM = 64, TN = 64, TK = 16, LDS_PAD = 4;
