@@ -1,4 +1,6 @@
-// Capacity split and dual-cache fill (Eq. (1); Section IV-B; Algorithm 1, node-granular).
+// Capacity split and dual-cache fill (Eq. (1); Section IV-B; Algorithm 1: node-granular by default,
+// element-granular as printed - second-level sort inside the nodes, last node cached in part - with
+// DCI_FILL_ADJ_ELEMENTS).
 //
 // Everything that touches N-sized arrays runs on the GPU: reductions (sum / max of the
 // counters), a three-kernel prefix scan, a stable LSD radix sort of (count, id) pairs for the

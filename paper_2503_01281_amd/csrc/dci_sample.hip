@@ -4,7 +4,9 @@
 // One batch is one clear of the batch's hash table, two kernels per hop and one closing kernel:
 //   k_sample_hop  - one lane group per frontier node (a whole wavefront for fan-outs above 32, a
 //                   half / quarter / eighth for smaller ones): read the node's list bounds from the
-//                   adjacency cache or the host CSR, draw the positions (Floyd's subset algorithm
+//                   adjacency cache or the host CSR (a position is served by the cache iff it lies
+//                   below the node's cached length, which is the whole list for every node but the
+//                   one an element-granular fill may have cached in part), draw the positions (Floyd's subset algorithm
 //                   on Philox4x32-10, one lane per slot), read the neighbour ids, store them at the
 //                   padded position row*fanout + slot and register every id in the hash table with
 //                   an atomic minimum over that padded position.  At hop 0 the same kernel turns
