@@ -2,7 +2,8 @@
  * dci.h - C boundary of the MI355X (gfx950) implementation of the dual-cache GNN inference
  * hot path of DCI (arXiv 2503.01281): pre-sampling access counting, the workload-aware
  * dual-cache fill, cache-aware multi-hop neighbour sampling, cache-aware feature gathering
- * and a GraphSAGE-mean forward pass.
+ * and the forward pass (GraphSAGE with the mean aggregator; the sum-aggregate GraphSAGE and the
+ * averaging GCN of the paper's Table III through dci_gnn_forward).
  *
  * General rules
  *  - C linkage, plain pointers and sizes.  Every call returns a status (0 = DCI_OK, negative =
