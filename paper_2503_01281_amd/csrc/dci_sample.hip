@@ -246,6 +246,8 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
         const long long host_start = hit ? a.indptr[v] : start;
         atomicAdd(&a.edge_count[host_start + pos], 1u);
       }
+    } else if (row_ok && gl < f) {
+      a.tmp_slot[(int)(i * f + gl)] = -1;  // no edge here: lets the relabel kernel read the slots without the row count
     }
     if (row_ok && gl == 0) {
       // the hit flag rides in bit 30 so that the relabel kernel can total the hit statistics
@@ -319,8 +321,9 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
   const int f = a.fanout;
 
   // per row: sampled edges, first appearances (the table still holds the lane's own position).
-  // The three dependent loads (row count -> table slot -> table value) are issued stage by stage
-  // for all of the lane's rows, so that the tile pays the memory latency three times, not 24.
+  // Row counts and table slots are independent loads, the table values depend on the slots; each
+  // group is issued for all of the lane's rows at once, so that the tile pays the memory latency
+  // twice, not 24 times.
   int raw[kTileIters], slot[kTileIters];
   unsigned val[kTileIters];
 #pragma unroll
@@ -331,7 +334,7 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
 #pragma unroll
   for (int it = 0; it < kTileIters; ++it) {
     const long long i = row0 + it * kGroups + grp;
-    slot[it] = gl < (raw[it] & kRowCntMask) ? a.tmp_slot[i * f + gl] : -1;
+    slot[it] = (i < n_rows && gl < f) ? a.tmp_slot[i * f + gl] : -1;  // -1 where the row has no edge
   }
 #pragma unroll
   for (int it = 0; it < kTileIters; ++it) val[it] = slot[it] >= 0 ? entry_val(a.table, (unsigned)slot[it]) : 0u;
