@@ -73,27 +73,40 @@ __device__ __forceinline__ unsigned long long uniform_below(unsigned k0, unsigne
 
 // ---- hash table -----------------------------------------------------------------------------
 // Finds or creates the entry of node u (open addressing, linear probing) and lowers its value to
-// v if v is smaller; returns the slot.  For an entry that already holds u, key and value move as
-// one word, so a single 64-bit atomic minimum does it; an empty slot is claimed by compare-and-
-// swap.  Values only decrease and keys never change, so a stale read costs a redundant atomic
-// at most.
+// v if v is smaller; returns the slot and, in *candidate, whether v may have become the entry's
+// value (the slot was empty, or held a larger value when it was looked at).  A call for which that
+// is false can never be the node's first appearance; the reverse need not hold.
+// For an entry that already holds u, key and value move as one word, so a single 64-bit atomic
+// minimum does it; an empty slot is claimed by compare-and-swap.  Values only decrease and keys
+// never change, so a stale read costs a redundant atomic at most.
 __device__ __forceinline__ unsigned table_insert_min(HashEntry* table, unsigned mask, int shift, long long u,
-                                                     unsigned v) {
+                                                     unsigned v, bool* candidate) {
   unsigned slot = (unsigned)(((unsigned long long)u * 0x9E3779B97F4A7C15ull) >> shift) & mask;
   const HashEntry mine = ((HashEntry)u << 32) | v;
+  *candidate = false;
   for (;;) {
     HashEntry w = __atomic_load_n(&table[slot], __ATOMIC_RELAXED);
     if (w == kEmptyEntry) {
       w = atomicCAS(&table[slot], kEmptyEntry, mine);
-      if (w == kEmptyEntry) return slot;
+      if (w == kEmptyEntry) {
+        *candidate = true;
+        return slot;
+      }
     }
     if ((long long)(w >> 32) == u) {
-      if ((unsigned)w > v) atomicMin(&table[slot], mine);
+      if ((unsigned)w > v) {
+        atomicMin(&table[slot], mine);
+        *candidate = true;
+      }
       return slot;
     }
     slot = (slot + 1) & mask;
   }
 }
+
+// tmp_slot encoding: s >= 0 a table slot whose value this edge may still own; -1 no edge at this
+// position; s <= -2 the slot -2 - s of an edge that cannot be its node's first appearance.
+__device__ __forceinline__ unsigned slot_of(int s) { return (unsigned)(s >= 0 ? s : -2 - s); }
 
 template <int G>
 __device__ __forceinline__ unsigned long long group_bits(unsigned long long ballot, int grp_in_wave) {
@@ -146,7 +159,7 @@ __device__ __forceinline__ void write_block_sources(long long n_rows, int fanout
   for (long long q = block * (long long)blockDim.x + threadIdx.x; q < total; q += (long long)n_blocks * blockDim.x) {
     const long long i = q / fanout;
     const int s = (int)(q - i * fanout);
-    if (s < (row_cnt[i] & kRowCntMask)) blk_src[blk_indptr[i] + s] = (int)entry_val(table, (unsigned)tmp_slot[q]);
+    if (s < (row_cnt[i] & kRowCntMask)) blk_src[blk_indptr[i] + s] = (int)entry_val(table, slot_of(tmp_slot[q]));
   }
 }
 
@@ -241,7 +254,8 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
         v = a.seeds[i];
         if (gl == 0) {
           a.nodes[i] = v;
-          (void)table_insert_min(a.table, a.mask, a.shift, v, (unsigned)i);
+          bool ignored;
+          (void)table_insert_min(a.table, a.mask, a.shift, v, (unsigned)i, &ignored);
         }
       } else {
         v = a.nodes[i];
@@ -284,9 +298,10 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
     if (active) {
       const long long u = from_host ? a.indices[a.indptr[v] + pos] : list[start + pos];
       const int p = (int)(i * f + gl);
-      const unsigned slot = table_insert_min(a.table, a.mask, a.shift, u, kTentative | (unsigned)p);
+      bool candidate;
+      const unsigned slot = table_insert_min(a.table, a.mask, a.shift, u, kTentative | (unsigned)p, &candidate);
       a.tmp_u[p] = u;
-      a.tmp_slot[p] = (int)slot;
+      a.tmp_slot[p] = candidate ? (int)slot : -2 - (int)slot;  // the relabel kernel looks at the candidates only
       if (COUNT && a.edge_count) {
         const long long host_start = hit ? a.indptr[v] : start;
         atomicAdd(&a.edge_count[host_start + pos], 1u);
