@@ -176,6 +176,41 @@ def test_presample_counts(env):
     assert st["t_sample_ns"] > 0 and st["t_feature_ns"] > 0
 
 
+def test_presample_counts_through_caches(env):
+    """Counting while the caches are in use: the same counters whether lists come from the host, from a
+    node-granular cache or from an element-granular one with a partly cached node (element counters are indexed by
+    position in the host list, which the element-granular fill has reordered)."""
+    dci, gu, ctx, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "tiny", "w"))
+    seeds = gu.dev(tiny["seeds"])
+    fc0, ac0, ec0 = _element_counts(tiny, w)
+    for elements in (False, True):
+        g = gu.make_graph(tiny["indptr"], tiny["indices"].copy(), tiny["feat"])
+        flags = dci.DCI_FILL_STRICT_SPLIT | (dci.DCI_FILL_ADJ_ELEMENTS if elements else 0)
+        cache = dci.dci_fill_caches(ctx, g, gu.dev(fc0.view(np.int32)), gu.dev(ac0.view(np.int32)), 300_024 + 400_000, 3, 4,
+                                    flags, edge_count=gu.dev(ec0.view(np.int32)))
+        ctx.sync()
+        assert 0 < cache.adj_nodes < w.num_nodes and 0 < cache.feat_rows < w.num_nodes
+        assert (cache.adj_partial_node >= 0) == elements
+        host_lists = g.indices.numpy().copy()
+        fc_w, ac_w, ec_w, (edges, nodes) = oracle.presample_count(tiny["indptr"], host_lists, tiny["seeds"], w.batch_size,
+                                                                  4, w.fanouts, w.rng_seed, 77)
+        fc = torch.zeros(w.num_nodes, dtype=torch.int32, device="cuda")
+        ac = torch.zeros(w.num_nodes, dtype=torch.int32, device="cuda")
+        ec = torch.zeros(w.num_edges, dtype=torch.int32, device="cuda")
+        stats = gu.new_stats()
+        scratch = torch.empty(dci.blocks_bounds(w.num_nodes, w.batch_size, w.fanouts)[0][-1] * w.feat_dim,
+                              dtype=torch.float32, device="cuda")
+        dci.dci_presample_count(ctx, g, cache, seeds, w.batch_size, 0, 4, 77, w.fanouts, w.rng_seed, fc, ac, ec,
+                                feat_scratch=scratch, stats=stats)
+        st = gu.stats_dict(ctx, stats)
+        assert np.array_equal(fc.cpu().numpy().view(np.uint32), fc_w)
+        assert np.array_equal(ac.cpu().numpy().view(np.uint32), ac_w)
+        assert np.array_equal(ec.cpu().numpy().view(np.uint32), ec_w)
+        assert st["edges_sampled"] == edges and st["input_nodes"] == nodes
+        assert st["adj_edge_hits"] > 0 and st["adj_edge_misses"] > 0 and st["feat_hits"] > 0 and st["feat_misses"] > 0
+        assert st["adj_edge_hits"] + st["adj_edge_misses"] == edges
+
+
 def _check_fill(env, budget, ts, tf, policy, spill=True):
     dci, gu, ctx, g, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "graph", "tiny", "w"))
     oc = _oracle_caches(tiny, w, ts, tf, policy, budget, spill)
