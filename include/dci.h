@@ -270,6 +270,25 @@ int32_t dci_sample_khop(dci_ctx* ctx, const dci_graph* graph, const dci_cache* c
                         int64_t n_seeds, uint64_t batch_index, const int32_t* fanouts, int32_t n_hops,
                         uint64_t rng_seed, dci_blocks* out, uint64_t* stats);
 
+/* dci_sample_khop for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and the same result as dci_sample_khop, but the temporaries (hash table, scan status
+ * words, padded per-hop arrays) live in an array of DCI_STATIC_SCRATCH_BYTES bytes that is part of
+ * the library's device code: every GPU the library runs on holds its own copy until the process
+ * ends, and the context's workspace is neither needed nor touched.  The call allocates nothing.
+ * A batch whose bounds need more than the array holds - dci_sample_khop_scratch_bytes(num_nodes,
+ * n_seeds, fanouts, n_hops) says how much a call needs (0 for invalid arguments) - is rejected with
+ * DCI_ERR_CAPACITY and a message naming both sizes.  All contexts on one GPU share that GPU's array
+ * and a call leaves its temporaries behind (every call clears what it needs cleared itself): two
+ * calls that overlap in time on one GPU, on whatever streams or contexts, race. */
+#define DCI_STATIC_SCRATCH_BYTES (32u << 20)
+int32_t dci_sample_khop_static(dci_ctx* ctx, const dci_graph* graph, const dci_cache* cache,
+                               const int64_t* seeds, int64_t n_seeds, uint64_t batch_index,
+                               const int32_t* fanouts, int32_t n_hops, uint64_t rng_seed, dci_blocks* out,
+                               uint64_t* stats);
+size_t dci_sample_khop_scratch_bytes(int64_t num_nodes, int64_t n_seeds, const int32_t* fanouts,
+                                     int32_t n_hops);
+
 /* Cache-aware feature gather (Section IV, framework paragraph; Section IV-B, first paragraph):
  * out[i,:] = feat_cache[feat_remap[id_i],:] on a hit, graph->feat[id_i,:] on a miss.
  * node_ids: device int64.  The number of rows is *n_dev (device int64, e.g. &counts[L] of a

@@ -82,6 +82,10 @@ def load_library():
     lib.dci_presample_count.argtypes = [P, P, P, P, i64, i32, i64, i64, u64, P, i32, u64, P, P, P, P, P]
     lib.dci_fill_caches.argtypes = [P, P, P, P, P, u64, u64, u64, i32, P, P, P, P]
     lib.dci_sample_khop.argtypes = [P, P, P, P, i64, u64, P, i32, u64, P, P]
+    lib.dci_sample_khop_static.argtypes = [P, P, P, P, i64, u64, P, i32, u64, P, P]
+    lib.dci_sample_khop_static.restype = i32
+    lib.dci_sample_khop_scratch_bytes.argtypes = [i64, i64, P, i32]
+    lib.dci_sample_khop_scratch_bytes.restype = sz
     lib.dci_gather_features.argtypes = [P, P, P, P, i64, P, P, P]
     lib.dci_sage_forward.argtypes = [P, P, P, i32, P, P, P, P, P]
     lib.dci_gnn_forward.argtypes = [P, P, P, i32, P, i32, P, P, P, P]
@@ -306,6 +310,18 @@ def dci_sample_khop(ctx: Context, graph: Graph, cache: Optional[Cache], seeds: t
     ctx.check(ctx.lib.dci_sample_khop(ctx.handle, C.byref(graph.c), None if cache is None else C.byref(cache.c),
                                       _ptr(seeds), seeds.numel(), batch_index, _i32_array(fanouts), len(fanouts),
                                       rng_seed, C.byref(out.c), _ptr(stats)))
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def dci_sample_khop_static(ctx: Context, graph: Graph, cache: Optional[Cache], seeds: torch.Tensor, batch_index: int,
+                           fanouts: Sequence[int], rng_seed: int, out: Blocks, stats: Optional[torch.Tensor] = None):
+    """dci_sample_khop with the temporaries in the library's static device array: no workspace, no allocation."""
+    assert seeds.is_cuda and seeds.dtype == torch.int64 and seeds.is_contiguous()
+    ctx.check(ctx.lib.dci_sample_khop_static(ctx.handle, C.byref(graph.c), None if cache is None else C.byref(cache.c),
+                                             _ptr(seeds), seeds.numel(), batch_index, _i32_array(fanouts),
+                                             len(fanouts), rng_seed, C.byref(out.c), _ptr(stats)))
 
 
 def dci_gather_features(ctx: Context, graph: Graph, cache: Optional[Cache], node_ids: torch.Tensor, n_max: int,

@@ -1,9 +1,36 @@
 // Context management and small shared kernels of libdci.
 #include "dci_internal.h"
 
+#include <mutex>
 #include <new>
 
+// Temporaries of the entry points that may not allocate (dci_sample_khop_static): one array per GPU,
+// held by that GPU from the moment the library's code is loaded on it until the process ends.
+// In host code `scratch` only names the symbol; the address of a GPU's copy comes from
+// hipGetSymbolAddress (scratch_for_device below) and is what every launch and fill is given.
+static __device__ __align__(256) unsigned char scratch[DCI_STATIC_SCRATCH_BYTES];
+
 namespace dci {
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Address of `device`'s copy of the static scratch array; `device` must be the current device.
+static hipError_t scratch_for_device(int device, void** out) {
+  *out = nullptr;
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p || (reinterpret_cast<uintptr_t>(p) % kAlign)) return hipErrorInvalidSymbol;
+    g_scratch_ptr[device] = p;
+  }
+  *out = g_scratch_ptr[device];
+  return hipSuccess;
+}
 
 __global__ void k_fill_u32x4(uint4* __restrict__ p, size_t n16, uint32_t pattern) {
   const uint4 v = make_uint4(pattern, pattern, pattern, pattern);
@@ -43,6 +70,11 @@ int32_t dci_create(dci_ctx** out, int32_t device, void* hip_stream, void* worksp
   if (e == hipSuccess) {
     ctx->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     for (int i = 0; i < 3 && e == hipSuccess; ++i) e = hipEventCreate(&ctx->ev[i]);
+  }
+  if (e == hipSuccess) {
+    void* p = nullptr;
+    e = dci::scratch_for_device(device, &p);
+    ctx->static_scratch = static_cast<char*>(p);
   }
   if (e != hipSuccess) {
     for (int i = 0; i < 3; ++i)

@@ -16,6 +16,7 @@ struct dci_ctx {
   hipStream_t stream = nullptr;
   char* ws = nullptr;
   size_t ws_bytes = 0;
+  char* static_scratch = nullptr;  // this GPU's copy of the library's static scratch array (DCI_STATIC_SCRATCH_BYTES)
   int num_cus = 256;
   hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
   char err[512] = {0};

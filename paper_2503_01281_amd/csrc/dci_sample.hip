@@ -796,10 +796,12 @@ size_t dci_sample_workspace_bytes(int64_t num_nodes, int64_t n_seeds, const int3
   return ar.off;
 }
 
-int32_t dci_sample_khop(dci_ctx* ctx, const dci_graph* graph, const dci_cache* cache, const int64_t* seeds,
-                        int64_t n_seeds, uint64_t batch_index, const int32_t* fanouts, int32_t n_hops,
-                        uint64_t rng_seed, dci_blocks* out, uint64_t* stats) {
-  if (!ctx) return DCI_ERR_INVALID_ARG;
+// Shared body of dci_sample_khop and dci_sample_khop_static: the two differ only in where the
+// temporaries live (`ws_base`, `ws_bytes`; `ws_name` names that memory in the error message).
+static int32_t sample_khop_in(dci_ctx* ctx, const dci_graph* graph, const dci_cache* cache, const int64_t* seeds,
+                              int64_t n_seeds, uint64_t batch_index, const int32_t* fanouts, int32_t n_hops,
+                              uint64_t rng_seed, dci_blocks* out, uint64_t* stats, char* ws_base, size_t ws_bytes,
+                              const char* ws_name) {
   int32_t rc = check_common(ctx, graph, seeds, n_seeds, fanouts, n_hops, batch_index);
   if (rc != DCI_OK) return rc;
   if ((rc = check_cache(ctx, cache)) != DCI_OK) return rc;
@@ -818,18 +820,44 @@ int32_t dci_sample_khop(dci_ctx* ctx, const dci_graph* graph, const dci_cache* c
                   (long long)out->cap_rows[h], (long long)out->cap_edges[h], (long long)cap_nodes[h],
                   (long long)cap_edges[h]);
   }
-  Arena ar(ctx->ws, ctx->ws_bytes);
+  Arena ar(ws_base, ws_bytes);
   SampleWs ws;
   carve_sample_ws(ar, cap_nodes, cap_edges, fanouts, n_hops, &ws);
   if (!ar.ok())
-    return fail(ctx, DCI_ERR_CAPACITY, "workspace holds %zu bytes, sampling needs %zu", ctx->ws_bytes, ar.off);
+    return fail(ctx, DCI_ERR_CAPACITY, "%s holds %zu bytes, sampling a batch of these bounds needs %zu", ws_name,
+                ws_bytes, ar.off);
   // launch shapes follow the bounds of this call, not the (possibly larger) capacities
   dci_blocks view = *out;
   for (int32_t h = 0; h < n_hops; ++h) view.cap_rows[h] = cap_nodes[h];
   view.cap_nodes = cap_nodes[n_hops];
-  rc = sample_batch(ctx, graph, cache, seeds, n_seeds, batch_index, fanouts, n_hops, rng_seed, &view, ws, stats,
-                    nullptr, nullptr, nullptr);
-  return rc;
+  return sample_batch(ctx, graph, cache, seeds, n_seeds, batch_index, fanouts, n_hops, rng_seed, &view, ws, stats,
+                      nullptr, nullptr, nullptr);
+}
+
+int32_t dci_sample_khop(dci_ctx* ctx, const dci_graph* graph, const dci_cache* cache, const int64_t* seeds,
+                        int64_t n_seeds, uint64_t batch_index, const int32_t* fanouts, int32_t n_hops,
+                        uint64_t rng_seed, dci_blocks* out, uint64_t* stats) {
+  if (!ctx) return DCI_ERR_INVALID_ARG;
+  return sample_khop_in(ctx, graph, cache, seeds, n_seeds, batch_index, fanouts, n_hops, rng_seed, out, stats,
+                        ctx->ws, ctx->ws_bytes, "workspace");
+}
+
+int32_t dci_sample_khop_static(dci_ctx* ctx, const dci_graph* graph, const dci_cache* cache, const int64_t* seeds,
+                               int64_t n_seeds, uint64_t batch_index, const int32_t* fanouts, int32_t n_hops,
+                               uint64_t rng_seed, dci_blocks* out, uint64_t* stats) {
+  if (!ctx) return DCI_ERR_INVALID_ARG;
+  if (!ctx->static_scratch) return fail(ctx, DCI_ERR_HIP, "the static scratch array has no address on this device");
+  return sample_khop_in(ctx, graph, cache, seeds, n_seeds, batch_index, fanouts, n_hops, rng_seed, out, stats,
+                        ctx->static_scratch, (size_t)DCI_STATIC_SCRATCH_BYTES, "the static scratch array");
+}
+
+size_t dci_sample_khop_scratch_bytes(int64_t num_nodes, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops) {
+  int64_t cap_nodes[DCI_MAX_HOPS + 1], cap_edges[DCI_MAX_HOPS];
+  if (dci_blocks_bounds(num_nodes, n_seeds, fanouts, n_hops, cap_nodes, cap_edges) != DCI_OK) return 0;
+  Arena ar(nullptr, 0);
+  SampleWs ws;
+  carve_sample_ws(ar, cap_nodes, cap_edges, fanouts, n_hops, &ws);
+  return ar.off;
 }
 
 int32_t dci_presample_count(dci_ctx* ctx, const dci_graph* graph, const dci_cache* cache, const int64_t* seeds,

@@ -55,6 +55,18 @@ def test_workspace_queries_grow_with_the_problem(lib):
     assert need >= 67584 * 602 * 4 + 2 * 67584 * 256 * 4
 
 
+def test_static_scratch_size_query(lib):
+    """The no-allocation sampler's size query (host arithmetic only): a Medium-sized batch fits the
+    static array, a Large-sized one does not, invalid fan-outs give 0."""
+    lib.dci_sample_khop_scratch_bytes.restype = C.c_size_t
+    f3 = (C.c_int32 * 3)(5, 10, 15)
+    limit = 32 << 20
+    assert 0 < lib.dci_sample_khop_scratch_bytes(232965, 1024, f3, 3) <= limit
+    assert lib.dci_sample_khop_scratch_bytes(2449029, 4096, f3, 3) > limit
+    assert lib.dci_sample_khop_scratch_bytes(232965, 1024, (C.c_int32 * 1)(65), 1) == 0
+    assert lib.dci_sample_khop_static(None, None, None, None, 0, 0, None, 0, 0, None, None) == -1
+
+
 def test_null_context_and_missing_gpu_are_errors_not_crashes(lib):
     assert lib.dci_sync(None) == -1
     assert lib.dci_set_workspace(None, None, 0) == -1
