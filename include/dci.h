@@ -13,8 +13,10 @@
  *    "mapped" pointers may be HBM or pinned host memory that the GPU can dereference
  *    (hipHostMalloc / a pinned PyTorch tensor): the graph and the feature matrix normally live
  *    there and are read by zero-copy on a cache miss (Section IV, framework paragraph).
- *  - The library allocates nothing.  Temporary device memory comes from the workspace handed to
- *    dci_create(); the dci_*_workspace_bytes() queries say how much each call needs.
+ *  - The library allocates no device memory.  Temporary device memory comes from the workspace
+ *    handed to dci_create(); the dci_*_workspace_bytes() queries say how much each call needs.
+ *    (A context owns a few HIP events and 64 bytes of pinned host memory; dci_timing_enable
+ *    creates events on first use.)
  *  - Calls enqueue work on the context's HIP stream and return without waiting, except
  *    dci_fill_caches(), which waits for completion because the cache sizes it reports are
  *    computed on the GPU.  Device outputs, and host outputs marked "valid after dci_sync", may be
@@ -125,6 +127,13 @@ enum {
   DCI_STAT_INPUT_NODES = 7,    /* sum of |F_L| over sampled batches                        */
   DCI_STAT_T_SAMPLE_NS = 8,    /* dci_presample_count only: GPU time spent sampling        */
   DCI_STAT_T_FEATURE_NS = 9,   /* dci_presample_count only: GPU time spent loading features */
+  DCI_STAT_BYTES_HBM = 10,     /* bytes the caches served: 16 per frontier node with a slot (its pair of
+                                  list bounds), 8 per edge read from the adjacency cache, 4F per row read
+                                  from the feature cache                                              */
+  DCI_STAT_BYTES_HOST = 11,    /* the same quantities for what the graph arrays served (the miss path) */
+  DCI_STAT_HOST_LINES = 12,    /* sampling: distinct 128-byte lines of graph->indptr / graph->indices
+                                  touched per frontier node, summed; the unit in which a host link
+                                  charges small reads                                                  */
   DCI_STATS_WORDS = 16
 };
 
@@ -158,6 +167,19 @@ const char* dci_last_error(const dci_ctx* ctx);
  *       (the contraction is split between them and a second kernel adds the partial sums in a fixed order):
  *       0  by shape (default): layers with few tiles are split up to 8 ways;  1  never split;  n <= 8  at most n */
 #define DCI_OPT_LINEAR_SPLIT 2
+/*   DCI_OPT_RELABEL_SPIN_LIMIT  how often a tile of the frontier scan (dedup + relabel, one chained prefix
+ *       sum per hop) polls for its predecessors before it gives up; default 2^24, far beyond any real wait.
+ *       A tile that gives up voids its batch: the remaining kernels of the batch do nothing, the batch's
+ *       `counts` (and counts_host) are zeroed so that a following gather / forward finds no rows, and the
+ *       next dci_sync (or dci_timing_read, or the waiting dci_presample_count) on the context returns
+ *       DCI_ERR_HIP with the message "relabel scan timed out ...".  Pre-sampling counters updated by a
+ *       voided batch are unspecified. */
+#define DCI_OPT_RELABEL_SPIN_LIMIT 3
+/*   DCI_OPT_TEST_RELABEL_FIRST_TICKET  test hook for that failure path, off (0) by default: the scan numbers
+ *       its tiles from this value, so the tiles below it never run or publish and the first real tile must
+ *       give up.  Only accepted while the spin limit is at most 65536, so that every kernel still ends
+ *       within microseconds. */
+#define DCI_OPT_TEST_RELABEL_FIRST_TICKET 4
 int32_t dci_set_option(dci_ctx* ctx, int32_t option, int64_t value);
 
 /* Kernel timing, for benchmarks and profiles.  Kernel classes whose bit is set in class_mask are
@@ -182,6 +204,22 @@ enum {
 #define DCI_TIMING_MAX_LAUNCHES 8192
 int32_t dci_timing_enable(dci_ctx* ctx, uint32_t class_mask);
 int32_t dci_timing_read(dci_ctx* ctx, double* total_ms, int64_t* launches);
+
+/* Memory-rate probe, for benchmarks: the rates that the access-bound steps are measured against
+ * (Section IV, framework paragraph: a hit reads GPU memory, a miss reads host memory through the
+ * zero-copy mapping).  Reads `mem` (device memory, or pinned host memory that the GPU can
+ * dereference; 256-byte aligned, `bytes` >= 4096) on the context's stream, waits, and returns the
+ * GPU time of the one kernel in *ms.
+ *   granule = 0            streaming read of the whole region, 16 bytes per lane;
+ *   granule = 8 .. 512     n_access reads of aligned `granule`-byte pieces at pseudo-random places
+ *                          (8 and 16: one lane each; above: 16 bytes per lane, granule/16 lanes);
+ *   granule = -64          64-byte pieces read as eight 8-byte words by eight lanes.
+ *   order (granule != 0)   0: the lanes of a piece are adjacent and take its words in order;
+ *                          1: adjacent lanes, words in a scrambled order; 2: the lanes of a piece
+ *                          are spread over the wavefront (never adjacent).
+ * workgroups (1..65536) of 256 lanes are launched; sink: device uint64 [workgroups], scratch. */
+int32_t dci_probe_read(dci_ctx* ctx, const void* mem, uint64_t bytes, int32_t granule, int32_t order,
+                       int64_t n_access, int32_t workgroups, uint64_t seed, uint64_t* sink, float* ms);
 
 /* Upper bounds on the sizes of a mini-batch with n_seeds seeds: cap_nodes[h] bounds |F_h|
  * (h = 0..n_hops), cap_edges[h] the edges of block h.  |F_{h+1}| <= min(|F_h| (1 + f_h),

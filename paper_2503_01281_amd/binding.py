@@ -14,7 +14,8 @@ import torch
 DCI_MAX_HOPS = 8
 STATS_WORDS = 16
 STAT = dict(edges_sampled=0, adj_node_hits=1, adj_node_misses=2, adj_edge_hits=3, adj_edge_misses=4,
-            feat_hits=5, feat_misses=6, input_nodes=7, t_sample_ns=8, t_feature_ns=9)
+            feat_hits=5, feat_misses=6, input_nodes=7, t_sample_ns=8, t_feature_ns=9, bytes_hbm=10, bytes_host=11,
+            host_lines=12)
 
 KERNEL_CLASSES = ["table_clear", "sample", "relabel", "write_src", "gather", "mean_in", "linear_in", "mean", "linear",
                   "count_nodes"]
@@ -89,6 +90,8 @@ def load_library():
     lib.dci_gather_features.argtypes = [P, P, P, P, i64, P, P, P]
     lib.dci_sage_forward.argtypes = [P, P, P, i32, P, P, P, P, P]
     lib.dci_gnn_forward.argtypes = [P, P, P, i32, P, i32, P, P, P, P]
+    lib.dci_probe_read.argtypes = [P, P, u64, i32, i32, i64, i32, u64, P, P]
+    lib.dci_probe_read.restype = i32
     lib.dci_set_option.argtypes = [P, i32, i64]
     lib.dci_timing_enable.argtypes = [P, C.c_uint32]
     lib.dci_timing_read.argtypes = [P, P, P]
@@ -98,6 +101,58 @@ def load_library():
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
+
+
+_hip = None
+
+
+def _hip_runtime():
+    """The HIP runtime this process already uses (PyTorch loads it), for pinned host allocations."""
+    global _hip
+    if _hip is None:
+        torch.cuda.init()
+        h = C.CDLL("libamdhip64.so.7")
+        h.hipHostMalloc.argtypes = [C.POINTER(C.c_void_p), C.c_size_t, C.c_uint]
+        h.hipHostMalloc.restype = C.c_int
+        h.hipHostFree.argtypes = [C.c_void_p]
+        h.hipHostFree.restype = C.c_int
+        h.hipGetLastError.restype = C.c_int
+        _hip = h
+    return _hip
+
+
+class _PinnedOwner:
+    def __init__(self, ptr: int):
+        self.ptr = ptr
+
+    def __del__(self):
+        try:
+            if self.ptr and _hip is not None:
+                _hip.hipHostFree(C.c_void_p(self.ptr))
+        except Exception:
+            pass
+        self.ptr = 0
+
+
+def pinned_empty(numel: int, dtype: torch.dtype) -> torch.Tensor:
+    """Uninitialised pinned (page-locked, device-mapped) host tensor of exactly ``numel`` elements.
+
+    ``torch.empty(..., pin_memory=True)`` rounds an allocation up to the next power of two, which for the
+    tens-of-gigabytes arrays of the host-resident workloads asks for more page-locked memory than a machine
+    grants; this takes the exact size from hipHostMalloc.  The memory is freed when the last tensor that
+    shares it is gone.  Raises MemoryError if the runtime refuses."""
+    nbytes = int(numel) * torch.empty(0, dtype=dtype).element_size()
+    if nbytes == 0:
+        return torch.empty(0, dtype=dtype)
+    h = _hip_runtime()
+    p = C.c_void_p()
+    rc = h.hipHostMalloc(C.byref(p), nbytes, 0)
+    if rc != 0 or not p.value:
+        h.hipGetLastError()
+        raise MemoryError(f"hipHostMalloc of {nbytes} bytes failed with HIP error {rc}")
+    arr = (C.c_char * nbytes).from_address(p.value)
+    arr._owner = _PinnedOwner(p.value)
+    return torch.frombuffer(arr, dtype=dtype)
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -335,10 +390,27 @@ def dci_gather_features(ctx: Context, graph: Graph, cache: Optional[Cache], node
                                           _ptr(node_ids), n_max, n_dev, _ptr(out), _ptr(stats)))
 
 
+def dci_probe_read(ctx: Context, mem: torch.Tensor, granule: int, n_access: int = 0, order: int = 0,
+                   workgroups: int = 4096, seed: int = 1, nbytes: Optional[int] = None) -> float:
+    """GPU milliseconds of one probe kernel over ``mem`` (device or pinned host tensor); see dci_probe_read in dci.h."""
+    assert mem.is_contiguous() and (mem.is_cuda or mem.is_pinned())
+    total = mem.numel() * mem.element_size()
+    base = mem.data_ptr()
+    off = (-base) % 256
+    nbytes = total - off if nbytes is None else min(int(nbytes), total - off)
+    sink = torch.zeros(workgroups, dtype=torch.int64, device=ctx.device)
+    ms = C.c_float(0.0)
+    ctx.check(ctx.lib.dci_probe_read(ctx.handle, base + off, nbytes, granule, order, n_access, workgroups, seed,
+                                     _ptr(sink), C.byref(ms)))
+    return float(ms.value)
+
+
 DCI_MODEL_SAGE_MEAN, DCI_MODEL_SAGE_SUM, DCI_MODEL_GCN_AVG = 0, 1, 2
 DCI_FILL_STRICT_SPLIT, DCI_FILL_ADJ_ELEMENTS = 0x100, 0x200
 DCI_OPT_LINEAR_KERNEL = 1
 DCI_OPT_LINEAR_SPLIT = 2
+DCI_OPT_RELABEL_SPIN_LIMIT = 3
+DCI_OPT_TEST_RELABEL_FIRST_TICKET = 4
 
 
 def dci_sage_forward(ctx: Context, blocks: Blocks, x_in: torch.Tensor, w_self: Sequence[torch.Tensor],

@@ -53,6 +53,16 @@ int32_t fill_bytes(dci_ctx* ctx, void* p, size_t bytes, uint32_t pattern) {
   return DCI_OK;
 }
 
+int32_t check_device_flag(dci_ctx* ctx) {
+  if (ctx->host_flag && *ctx->host_flag != 0u) {
+    *ctx->host_flag = 0u;
+    return fail(ctx, DCI_ERR_HIP,
+                "relabel scan timed out: a tile of the frontier scan waited longer than the spin limit for its "
+                "predecessors; the batch was voided (sizes zeroed) and its outputs must not be used");
+  }
+  return DCI_OK;
+}
+
 }  // namespace dci
 
 extern "C" {
@@ -76,9 +86,18 @@ int32_t dci_create(dci_ctx** out, int32_t device, void* hip_stream, void* worksp
     e = dci::scratch_for_device(device, &p);
     ctx->static_scratch = static_cast<char*>(p);
   }
+  if (e == hipSuccess) {
+    void* p = nullptr;
+    e = hipHostMalloc(&p, 64, hipHostMallocDefault);
+    if (e == hipSuccess) {
+      ctx->host_flag = static_cast<unsigned*>(p);
+      *ctx->host_flag = 0u;
+    }
+  }
   if (e != hipSuccess) {
     for (int i = 0; i < 3; ++i)
       if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
+    if (ctx->host_flag) (void)hipHostFree(ctx->host_flag);
     delete ctx;
     return DCI_ERR_HIP;
   }
@@ -104,6 +123,7 @@ int32_t dci_set_workspace(dci_ctx* ctx, void* workspace, size_t workspace_bytes)
 
 void dci_destroy(dci_ctx* ctx) {
   if (!ctx) return;
+  if (ctx->host_flag) (void)hipHostFree(ctx->host_flag);
   for (int i = 0; i < 3; ++i)
     if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
   if (ctx->t_events) {
@@ -134,6 +154,7 @@ int32_t dci_timing_read(dci_ctx* ctx, double* total_ms, int64_t* launches) {
     launches[k] = 0;
   }
   DCI_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  const int32_t flagged = dci::check_device_flag(ctx);
   for (int i = 0; i < ctx->t_used; ++i) {
     float ms = 0.f;
     DCI_HIP(ctx, hipEventElapsedTime(&ms, ctx->t_events[2 * i], ctx->t_events[2 * i + 1]));
@@ -141,13 +162,13 @@ int32_t dci_timing_read(dci_ctx* ctx, double* total_ms, int64_t* launches) {
     launches[ctx->t_class[i]] += 1;
   }
   ctx->t_used = 0;
-  return DCI_OK;
+  return flagged;
 }
 
 int32_t dci_sync(dci_ctx* ctx) {
   if (!ctx) return DCI_ERR_INVALID_ARG;
   DCI_HIP(ctx, hipStreamSynchronize(ctx->stream));
-  return DCI_OK;
+  return dci::check_device_flag(ctx);
 }
 
 const char* dci_last_error(const dci_ctx* ctx) { return ctx ? ctx->err : "null context"; }
@@ -162,6 +183,22 @@ int32_t dci_set_option(dci_ctx* ctx, int32_t option, int64_t value) {
   if (option == DCI_OPT_LINEAR_SPLIT) {
     if (value < 0 || value > 8) return dci::fail(ctx, DCI_ERR_INVALID_ARG, "DCI_OPT_LINEAR_SPLIT takes 0..8, not %lld", (long long)value);
     ctx->linear_split = (int)value;
+    return DCI_OK;
+  }
+  if (option == DCI_OPT_RELABEL_SPIN_LIMIT) {
+    if (value < 1 || value > (int64_t)0xFFFFFFFFll)
+      return dci::fail(ctx, DCI_ERR_INVALID_ARG, "DCI_OPT_RELABEL_SPIN_LIMIT takes 1 .. 2^32-1, not %lld", (long long)value);
+    if (ctx->test_first_ticket != 0 && value > 65536)
+      return dci::fail(ctx, DCI_ERR_INVALID_ARG, "the spin limit must stay at or below 65536 while the first-ticket test hook is on");
+    ctx->relabel_spin_limit = (unsigned)value;
+    return DCI_OK;
+  }
+  if (option == DCI_OPT_TEST_RELABEL_FIRST_TICKET) {
+    if (value < 0 || value > 65536)
+      return dci::fail(ctx, DCI_ERR_INVALID_ARG, "DCI_OPT_TEST_RELABEL_FIRST_TICKET takes 0 .. 65536, not %lld", (long long)value);
+    if (value != 0 && ctx->relabel_spin_limit > 65536)
+      return dci::fail(ctx, DCI_ERR_INVALID_ARG, "lower DCI_OPT_RELABEL_SPIN_LIMIT to 65536 or less before switching the first-ticket test hook on");
+    ctx->test_first_ticket = (unsigned)value;
     return DCI_OK;
   }
   return dci::fail(ctx, DCI_ERR_INVALID_ARG, "unknown option %d", option);

@@ -102,7 +102,8 @@ __global__ __launch_bounds__(kGatherBlock) void k_gather(const long long* __rest
 }
 
 __global__ __launch_bounds__(kGatherBlock) void k_fold_gather_stats(const unsigned long long* __restrict__ partials,
-                                                                    int n_blocks, unsigned long long* stats) {
+                                                                    int n_blocks, unsigned long long row_bytes,
+                                                                    unsigned long long* stats) {
   unsigned long long h = 0, m = 0;
   for (int b = (int)threadIdx.x; b < n_blocks; b += kGatherBlock) {
     h += partials[2 * b];
@@ -124,6 +125,9 @@ __global__ __launch_bounds__(kGatherBlock) void k_fold_gather_stats(const unsign
     }
     atomicAdd(&stats[DCI_STAT_FEAT_HITS], h);
     atomicAdd(&stats[DCI_STAT_FEAT_MISSES], m);
+    // a gathered row is read once, from the tier that holds it
+    if (h) atomicAdd(&stats[DCI_STAT_BYTES_HBM], h * row_bytes);
+    if (m) atomicAdd(&stats[DCI_STAT_BYTES_HOST], m * row_bytes);
   }
 }
 
@@ -169,7 +173,7 @@ int32_t gather_launch(dci_ctx* ctx, const dci_graph* g, const dci_cache* cache, 
   if (stats) {
     hipLaunchKernelGGL(k_fold_gather_stats, dim3(1), dim3(kGatherBlock), 0, ctx->stream,
                        reinterpret_cast<const unsigned long long*>(partials_buf), (int)blocks,
-                       reinterpret_cast<unsigned long long*>(stats));
+                       (unsigned long long)F * 4ull, reinterpret_cast<unsigned long long*>(stats));
     DCI_LAUNCH_CHECK(ctx);
   }
   return DCI_OK;

@@ -25,6 +25,9 @@ struct dci_ctx {
   hipEvent_t* t_events = nullptr;  // 2 * DCI_TIMING_MAX_LAUNCHES, created on first enable
   int8_t* t_class = nullptr;
   int t_used = 0;
+  unsigned* host_flag = nullptr;  // pinned host word (64 bytes): a kernel raises it when a batch had to be voided
+  unsigned relabel_spin_limit = 1u << 24;  // DCI_OPT_RELABEL_SPIN_LIMIT
+  unsigned test_first_ticket = 0;          // DCI_OPT_TEST_RELABEL_FIRST_TICKET
   int linear_split = 0;   // DCI_OPT_LINEAR_SPLIT: 0 = by shape, n = at most n workgroups per tile
   int linear_kernel = 0;  // DCI_OPT_LINEAR_KERNEL: 0 by shape, 1 tile kernel, 2 wide kernel where the shape allows
 };
@@ -137,6 +140,8 @@ __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long x)
 __global__ void k_fill_u32x4(uint4* __restrict__ p, size_t n16, uint32_t pattern);
 
 int32_t fill_bytes(dci_ctx* ctx, void* p, size_t bytes, uint32_t pattern);
+// After a wait on the context's stream: reports (and clears) a failure that a kernel flagged.
+int32_t check_device_flag(dci_ctx* ctx);
 // partials_buf: gather_partials_bytes(ctx) bytes of device scratch, needed when stats != NULL
 int32_t gather_launch(dci_ctx* ctx, const dci_graph* g, const dci_cache* cache, const int64_t* ids,
                       int64_t n_max, const int64_t* n_dev, float* out, uint64_t* stats, void* partials_buf);

@@ -33,10 +33,18 @@ constexpr unsigned int kTentative = 0x80000000u;
 constexpr HashEntry kEmptyEntry = ~0ull;
 constexpr int kBlock = 256;
 // row_cnt[i]: bits 0..7 sampled edges of row i; bits 8..15 how many of them were read from the host although
-// the node has a cache slot (only the node cached in part has any); bit 30 set if the node has a slot
+// the node has a cache slot (only the node cached in part has any); bits 16..22 the 128-byte lines of host
+// memory the row touched (list bounds and neighbour ids; only counted when statistics are on); bit 30 set if
+// the node has a slot
 constexpr int kRowHitBit = 1 << 30;
 constexpr int kRowCntMask = 0xFF;
 constexpr int kRowHostShift = 8;
+constexpr int kRowLinesShift = 16;
+constexpr int kRowLinesMask = 0x7F;
+constexpr int kHostLineLog2 = 7;  // the host link moves 128-byte lines: smaller reads cost a whole request each
+// Batch status word (in the region that the per-batch clear fills with ones): all ones = fine; anything
+// else = a relabel tile gave up waiting for its predecessors, the batch's outputs are void.
+constexpr unsigned kBatchOk = 0xFFFFFFFFu;
 
 __device__ __forceinline__ unsigned entry_val(const HashEntry* table, unsigned slot) {
   return reinterpret_cast<const unsigned*>(table)[2 * (size_t)slot];  // low half (little endian)
@@ -146,6 +154,8 @@ struct HopArgs {
   const long long* prev_blk_indptr;
   int* prev_blk_src;
   int n_write_blocks;  // leading workgroups that only do the previous hop's edge ids
+  const unsigned* batch_flag;  // != kBatchOk: an earlier kernel of this batch failed, do nothing
+  int count_lines;             // statistics are on: count the host lines every row touches
 };
 
 // blk_src of a finished hop: every edge reads the (by now final) local id of its source.
@@ -167,47 +177,66 @@ __device__ __forceinline__ void write_block_sources(long long n_rows, int fanout
 // Hit statistics of a batch: every relabel tile leaves (rows with a cache slot, edges read from the cache) in
 // its hop's array of partial sums; the closing kernel adds them up and updates the caller's counters with
 // one atomic each.  (Per-tile atomics on the same few words cost 12 us per batch on a 56 k-row frontier.)
+constexpr int kStatPartWords = 3;  // per relabel tile: rows with a slot, edges from the cache, host lines
 struct StatFold {
   unsigned long long* stats;                    // nullptr: no statistics
-  const unsigned long long* part[DCI_MAX_HOPS]; // [2 * tiles] per hop
+  const unsigned long long* part[DCI_MAX_HOPS]; // [kStatPartWords * tiles] per hop
   int tile_rows[DCI_MAX_HOPS];
   int n_hops;
 };
 
-__global__ __launch_bounds__(kBlock) void k_write_src(const long long* __restrict__ counts, int hop, int fanout,
+__global__ __launch_bounds__(kBlock) void k_write_src(const long long* counts, int hop, int fanout,
                                                       const int* row_cnt, const int* tmp_slot,
                                                       const long long* blk_indptr, const HashEntry* table,
-                                                      int* blk_src, long long* counts_host, StatFold sf) {
+                                                      int* blk_src, long long* counts_host, StatFold sf,
+                                                      const unsigned* batch_flag, long long* counts_rw,
+                                                      unsigned* host_flag) {
+  if (*batch_flag != kBatchOk) {
+    // A relabel tile timed out: the batch is void.  Its sizes are zeroed so that whatever consumes the
+    // batch next (gather, forward) finds nothing to do, and the context's host flag is raised for dci_sync.
+    if (blockIdx.x == 0 && threadIdx.x < 2 * DCI_MAX_HOPS + 1) {
+      counts_rw[threadIdx.x] = 0;
+      if (counts_host) counts_host[threadIdx.x] = 0;
+      if (threadIdx.x == 0) *host_flag = 1u;
+    }
+    return;
+  }
   write_block_sources(counts[hop], fanout, row_cnt, tmp_slot, blk_indptr, table, blk_src, (int)blockIdx.x,
                       (int)gridDim.x);
   if (counts_host && blockIdx.x == 0 && threadIdx.x < 2 * DCI_MAX_HOPS + 1)
     counts_host[threadIdx.x] = counts[threadIdx.x];  // pinned host memory, visible once the stream is idle
   if (sf.stats && blockIdx.x == gridDim.x - 1) {
     __shared__ unsigned long long s_r[kBlock / kWave], s_e[kBlock / kWave];
-    unsigned long long hr = 0, he = 0, rows = 0, edges = 0;
+    __shared__ unsigned long long s_l[kBlock / kWave];
+    unsigned long long hr = 0, he = 0, hl = 0, rows = 0, edges = 0;
     for (int h = 0; h < sf.n_hops; ++h) {
       const long long n_rows = counts[h];
       const long long n_tiles = (n_rows + sf.tile_rows[h] - 1) / sf.tile_rows[h];
       for (long long t = threadIdx.x; t < n_tiles; t += kBlock) {
-        hr += sf.part[h][2 * t];
-        he += sf.part[h][2 * t + 1];
+        hr += sf.part[h][kStatPartWords * t];
+        he += sf.part[h][kStatPartWords * t + 1];
+        hl += sf.part[h][kStatPartWords * t + 2];
       }
       rows += (unsigned long long)n_rows;
       edges += (unsigned long long)counts[DCI_MAX_HOPS + 1 + h];
     }
     hr = wave_sum_u64(hr);
     he = wave_sum_u64(he);
+    hl = wave_sum_u64(hl);
     if (lane_id() == 0) {
       s_r[threadIdx.x / kWave] = hr;
       s_e[threadIdx.x / kWave] = he;
+      s_l[threadIdx.x / kWave] = hl;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
       hr = 0;
       he = 0;
+      hl = 0;
       for (int w = 0; w < kBlock / kWave; ++w) {
         hr += s_r[w];
         he += s_e[w];
+        hl += s_l[w];
       }
       if (edges) atomicAdd(&sf.stats[DCI_STAT_EDGES_SAMPLED], edges);
       if (hr) atomicAdd(&sf.stats[DCI_STAT_ADJ_NODE_HITS], hr);
@@ -215,6 +244,11 @@ __global__ __launch_bounds__(kBlock) void k_write_src(const long long* __restric
       if (he) atomicAdd(&sf.stats[DCI_STAT_ADJ_EDGE_HITS], he);
       if (edges - he) atomicAdd(&sf.stats[DCI_STAT_ADJ_EDGE_MISSES], edges - he);
       atomicAdd(&sf.stats[DCI_STAT_INPUT_NODES], (unsigned long long)counts[sf.n_hops]);
+      // a frontier node costs its pair of list bounds (16 bytes), a sampled edge its neighbour id (8 bytes),
+      // charged to the tier that served them
+      if (hr | he) atomicAdd(&sf.stats[DCI_STAT_BYTES_HBM], 16ull * hr + 8ull * he);
+      if ((rows - hr) | (edges - he)) atomicAdd(&sf.stats[DCI_STAT_BYTES_HOST], 16ull * (rows - hr) + 8ull * (edges - he));
+      if (hl) atomicAdd(&sf.stats[DCI_STAT_HOST_LINES], hl);
     }
   }
 }
@@ -228,6 +262,8 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
   const long long n_rows = INIT ? a.n_seeds : a.counts[a.hop];
   if (INIT) {
     if (blockIdx.x == 0 && threadIdx.x == 0) a.counts[0] = a.n_seeds;
+  } else if (*a.batch_flag != kBatchOk) {
+    return;  // an earlier relabel tile gave up: the closing kernel voids the batch
   } else if ((int)blockIdx.x < a.n_write_blocks) {
     // the first few workgroups finish the previous hop while the others sample this one
     write_block_sources(a.counts[a.hop - 1], a.prev_fanout, a.prev_row_cnt, a.prev_tmp_slot, a.prev_blk_indptr,
@@ -295,8 +331,30 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
     // paragraph); beyond it - possible only for the one node cached in part - the host list is read
     const bool from_host = active && hit && pos >= cached_len;
     const int n_host = __popcll(group_bits<G>(__ballot(from_host), grp_in_wave));
+    const long long* src = from_host ? a.indices + (a.indptr[v] + pos) : list + (start + pos);
+    int n_lines = 0;
+    if (a.count_lines) {
+      // Host-memory traffic of the row in the unit the host link moves (128-byte lines): the lines its
+      // pair of list bounds lies in plus the distinct lines of the neighbour ids it reads from the host.
+      const bool host_read = active && (from_host || !hit);
+      if (__ballot(host_read) != 0ull) {
+        const unsigned long long line = (unsigned long long)reinterpret_cast<uintptr_t>(src) >> kHostLineLog2;
+        bool leader = host_read;
+        for (int s = 0; s + 1 < f; ++s) {
+          const unsigned long long ls = __shfl(line, s, G);
+          const bool hs = __shfl((int)host_read, s, G) != 0;
+          if (gl > s && hs && ls == line) leader = false;
+        }
+        n_lines = __popcll(group_bits<G>(__ballot(leader), grp_in_wave));
+      }
+      if (row_ok && hit && n_host > 0) n_lines += 1;  // the partly cached node: where its host list starts
+      if (row_ok && !hit) {
+        const uintptr_t b0 = reinterpret_cast<uintptr_t>(a.indptr + v), b1 = reinterpret_cast<uintptr_t>(a.indptr + v + 1);
+        n_lines += (b0 >> kHostLineLog2) == (b1 >> kHostLineLog2) ? 1 : 2;
+      }
+    }
     if (active) {
-      const long long u = from_host ? a.indices[a.indptr[v] + pos] : list[start + pos];
+      const long long u = *src;
       const int p = (int)(i * f + gl);
       bool candidate;
       const unsigned slot = table_insert_min(a.table, a.mask, a.shift, u, kTentative | (unsigned)p, &candidate);
@@ -311,7 +369,7 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
     }
     if (row_ok && gl == 0) {
       // the hit flag rides in bit 30 so that the relabel kernel can total the hit statistics
-      a.row_cnt[i] = c | (n_host << kRowHostShift) | (hit ? kRowHitBit : 0);
+      a.row_cnt[i] = c | (n_host << kRowHostShift) | (n_lines << kRowLinesShift) | (hit ? kRowHitBit : 0);
       if (COUNT && c > 0) atomicAdd(&a.adj_count[v], (unsigned)c);
     }
   }
@@ -328,7 +386,7 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
 // L2 write-back / invalidate to every publish and every poll.
 constexpr int kTileIters = 8;
 constexpr unsigned long long kStInvalid = 3ull, kStAggregate = 1ull, kStInclusive = 2ull;
-constexpr unsigned kLookbackSpinLimit = 1u << 24;  // polls; far beyond any real wait, ends a wedged launch
+// The look-back polls at most dci_ctx::relabel_spin_limit times (default 2^24: far beyond any real wait, ends a wedged launch).
 
 __device__ __forceinline__ unsigned long long st_pack(unsigned long long flag, unsigned long long firsts,
                                                       unsigned long long edges) {
@@ -347,7 +405,10 @@ struct RelabelArgs {
   long long* blk_indptr;
   unsigned long long* status;  // one word per tile, filled with ones beforehand
   unsigned* ticket;            // filled with ones beforehand: the first ticket is 0xFFFFFFFF + 1 = 0
-  unsigned long long* stat_part;  // [2 * tiles] (rows with a slot, edges from the cache) per tile, or nullptr
+  unsigned long long* stat_part;  // [kStatPartWords * tiles] per tile, or nullptr
+  unsigned* batch_flag;   // set to 0 by a tile that gives up; != kBatchOk on entry: do nothing
+  unsigned spin_limit;    // polls of the look-back before a tile gives up
+  unsigned first_ticket;  // tiles are numbered from here (0 except under the failure-handling test hook)
 };
 
 template <int G>
@@ -358,18 +419,23 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
   static_assert(TR <= kBlock, "one thread per tile row in the block scan");
   __shared__ int s_c[TR], s_f[TR];
   __shared__ int s_wc[kWaves], s_wf[kWaves];
-  __shared__ unsigned long long s_hr[kWaves], s_he[kWaves];
+  __shared__ unsigned long long s_hr[kWaves], s_he[kWaves], s_hl[kWaves];
   __shared__ unsigned s_tile;
   __shared__ long long s_ec;
   __shared__ int s_ef;
   const int tid = (int)threadIdx.x, lane = lane_id(), wave = tid / kWave;
   const int gl = lane & (G - 1), grp_in_wave = lane / G, grp = tid / G;
+  if (*a.batch_flag != kBatchOk) return;  // an earlier hop failed (uniform over the launch: set before it began)
   const long long n_rows = a.counts[a.hop];
-  if (tid == 0) s_tile = atomicAdd(a.ticket, 1u) + 1u;
+  if (tid == 0) s_tile = atomicAdd(a.ticket, 1u) + 1u + a.first_ticket;
   __syncthreads();
   const unsigned tile = s_tile;
   const long long row0 = (long long)tile * TR;
   if (row0 >= n_rows) {
+    // (test hook: when even the first numbered tile lies beyond the frontier nobody would notice the
+    // missing tiles, so that tile voids the batch itself)
+    if (a.first_ticket != 0 && tile == a.first_ticket && tid == 0)
+      __hip_atomic_store(a.batch_flag, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (tile == 0 && tid == 0) {  // empty frontier: the hop adds nothing
       a.blk_indptr[0] = 0;
       a.counts[a.hop + 1] = n_rows;
@@ -398,7 +464,7 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
 #pragma unroll
   for (int it = 0; it < kTileIters; ++it) val[it] = slot[it] >= 0 ? entry_val(a.table, (unsigned)slot[it]) : 0u;
   unsigned first_bits = 0;
-  unsigned long long hit_rows = 0, hit_edges = 0;
+  unsigned long long hit_rows = 0, hit_edges = 0, host_lines = 0;
 #pragma unroll
   for (int it = 0; it < kTileIters; ++it) {
     const int r = it * kGroups + grp;
@@ -414,6 +480,7 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
         hit_rows += 1;
         hit_edges += (unsigned)(c - ((raw[it] >> kRowHostShift) & 0xFF));
       }
+      host_lines += (unsigned)((raw[it] >> kRowLinesShift) & kRowLinesMask);
     }
   }
   __syncthreads();
@@ -427,9 +494,11 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
   }
   hit_rows = wave_sum_u64(hit_rows);
   hit_edges = wave_sum_u64(hit_edges);
+  host_lines = wave_sum_u64(host_lines);
   if (lane == 0) {
     s_hr[wave] = hit_rows;
     s_he[wave] = hit_edges;
+    s_hl[wave] = host_lines;
   }
   __syncthreads();
   int off_c = 0, off_f = 0, tot_c = 0, tot_f = 0;
@@ -465,12 +534,14 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
         const long long idx = j - lane;
         unsigned long long st = idx >= 0 ? __hip_atomic_load(&a.status[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
                                          : st_pack(kStInclusive, 0, 0);
-        while (__ballot((st >> 62) == kStInvalid) != 0ull && polls < kLookbackSpinLimit) {
+        while (__ballot((st >> 62) == kStInvalid) != 0ull && polls < a.spin_limit) {
           __builtin_amdgcn_s_sleep(1);
           ++polls;
           if ((st >> 62) == kStInvalid)
             st = __hip_atomic_load(&a.status[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
+        // the polling loop ends with an unpublished word in the window only when it ran out of polls
+        const bool timed_out = __ballot((st >> 62) == kStInvalid) != 0ull;
         const unsigned long long inc_mask = __ballot((st >> 62) == kStInclusive);
         const int stop = inc_mask ? (int)__ffsll((long long)inc_mask) - 1 : kWave;  // nearest tile with a prefix
         long long pc = 0;
@@ -481,7 +552,14 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
         }
         ec += (long long)wave_sum_u64((unsigned long long)pc);
         ef += (int)wave_sum_u64((unsigned long long)pf);
-        if (inc_mask != 0ull || polls >= kLookbackSpinLimit) break;
+        if (timed_out) {
+          // Gave up: a predecessor never published.  The tile goes on with what it has - every index it
+          // forms stays at or below the true one, hence inside the batch's buffers - and voids the batch,
+          // so that no later kernel reads what this hop leaves behind.
+          if (lane == 0) __hip_atomic_store(a.batch_flag, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          break;
+        }
+        if (inc_mask != 0ull) break;
         j -= kWave;
       }
       ec = __shfl(ec, 0, kWave);
@@ -527,13 +605,15 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
       a.counts[DCI_MAX_HOPS + 1 + a.hop] = ec + tot_c;
     }
     if (a.stat_part) {
-      unsigned long long hr = 0, he = 0;
+      unsigned long long hr = 0, he = 0, hl = 0;
       for (int w = 0; w < kWaves; ++w) {
         hr += s_hr[w];
         he += s_he[w];
+        hl += s_hl[w];
       }
-      a.stat_part[2 * (size_t)tile] = hr;      // added up by the batch's closing kernel
-      a.stat_part[2 * (size_t)tile + 1] = he;
+      a.stat_part[kStatPartWords * (size_t)tile] = hr;      // added up by the batch's closing kernel
+      a.stat_part[kStatPartWords * (size_t)tile + 1] = he;
+      a.stat_part[kStatPartWords * (size_t)tile + 2] = hl;
     }
   }
 }
@@ -555,6 +635,7 @@ struct SampleWs {
   uint64_t table_entries;  // cleared with a single all-ones fill per batch
   unsigned long long* status[DCI_MAX_HOPS];
   unsigned* ticket;        // [DCI_MAX_HOPS]
+  unsigned* batch_flag;    // one word after the tickets, also in the cleared region
   size_t clear_bytes;
   long long* tmp_u;
   int* tmp_slot[2];  // by hop parity: a hop's slots are still read while the next hop samples
@@ -586,7 +667,7 @@ static void carve_sample_ws(Arena& ar, const int64_t* cap_nodes, const int64_t* 
   }
   ws->table_entries = table_entries_for(cap_nodes[n_hops]);
   const size_t table_bytes = ws->table_entries * sizeof(HashEntry);
-  const size_t sync_bytes = align_up(status_words * 8 + DCI_MAX_HOPS * 4, 16);
+  const size_t sync_bytes = align_up(status_words * 8 + (DCI_MAX_HOPS + 1) * 4, 16);
   char* region = ar.take<char>(table_bytes + sync_bytes);
   ws->table = reinterpret_cast<HashEntry*>(region);
   unsigned long long* st = reinterpret_cast<unsigned long long*>(region + table_bytes);
@@ -595,6 +676,7 @@ static void carve_sample_ws(Arena& ar, const int64_t* cap_nodes, const int64_t* 
     st += tiles_for(cap_nodes[h], fanouts[h]);
   }
   ws->ticket = reinterpret_cast<unsigned*>(st);
+  ws->batch_flag = ws->ticket + DCI_MAX_HOPS;
   ws->clear_bytes = table_bytes + sync_bytes;
   ws->tmp_u = ar.take<long long>((size_t)max_edges);
   for (int k = 0; k < 2; ++k) {
@@ -602,7 +684,7 @@ static void carve_sample_ws(Arena& ar, const int64_t* cap_nodes, const int64_t* 
     ws->row_cnt[k] = ar.take<int>((size_t)max_rows);
   }
   for (int32_t h = 0; h < n_hops; ++h)
-    ws->stat_part[h] = ar.take<unsigned long long>(2 * (size_t)tiles_for(cap_nodes[h], fanouts[h]));
+    ws->stat_part[h] = ar.take<unsigned long long>(kStatPartWords * (size_t)tiles_for(cap_nodes[h], fanouts[h]));
 }
 
 static void carve_blocks(Arena& ar, const int64_t* cap_nodes, const int64_t* cap_edges, int32_t n_hops,
@@ -706,6 +788,8 @@ static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* c
     ha.prev_blk_indptr = h > 0 ? reinterpret_cast<const long long*>(out->blk_indptr[h - 1]) : nullptr;
     ha.prev_blk_src = h > 0 ? out->blk_src[h - 1] : nullptr;
     ha.n_write_blocks = h > 0 ? grid_for_rows(ctx, out->cap_rows[h - 1] * fanouts[h - 1], kBlock * 4) : 0;
+    ha.batch_flag = ws.batch_flag;
+    ha.count_lines = stats ? 1 : 0;
     RelabelArgs ra;
     ra.counts = counts;
     ra.hop = h;
@@ -719,6 +803,9 @@ static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* c
     ra.status = ws.status[h];
     ra.ticket = ws.ticket + h;
     ra.stat_part = stats ? ws.stat_part[h] : nullptr;
+    ra.batch_flag = ws.batch_flag;
+    ra.spin_limit = ctx->relabel_spin_limit;
+    ra.first_ticket = ctx->test_first_ticket;
     // launch shapes follow the frontier bound of this call; with zero seeds one workgroup still
     // runs so that the (empty) sizes get written
     const int64_t rows = out->cap_rows[h];
@@ -744,7 +831,8 @@ static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* c
     hipLaunchKernelGGL(k_write_src, dim3(grid_for_rows(ctx, positions, kBlock)), dim3(kBlock), 0, ctx->stream,
                        (const long long*)counts, h, fanouts[h], (const int*)ws.row_cnt[h & 1],
                        (const int*)ws.tmp_slot[h & 1], reinterpret_cast<const long long*>(out->blk_indptr[h]),
-                       (const HashEntry*)ws.table, out->blk_src[h], reinterpret_cast<long long*>(out->counts_host), sf);
+                       (const HashEntry*)ws.table, out->blk_src[h], reinterpret_cast<long long*>(out->counts_host), sf,
+                       (const unsigned*)ws.batch_flag, counts, ctx->host_flag);
   }
   DCI_LAUNCH_CHECK(ctx);
   if (feat_count) {
@@ -901,6 +989,7 @@ int32_t dci_presample_count(dci_ctx* ctx, const dci_graph* graph, const dci_cach
       if (rc != DCI_OK) return rc;
       DCI_HIP(ctx, hipEventRecord(ctx->ev[2], ctx->stream));
       DCI_HIP(ctx, hipEventSynchronize(ctx->ev[2]));
+      if ((rc = check_device_flag(ctx)) != DCI_OK) return rc;
       float a = 0.f, b = 0.f;
       DCI_HIP(ctx, hipEventElapsedTime(&a, ctx->ev[0], ctx->ev[1]));
       DCI_HIP(ctx, hipEventElapsedTime(&b, ctx->ev[1], ctx->ev[2]));

@@ -658,3 +658,102 @@ def test_end_to_end_tiny(env):
         st = gu.stats_dict(ctx, stats)
         assert st["feat_hits"] == int((oc["feat_remap"][want_blk.nodes] >= 0).sum())
         assert st["feat_hits"] + st["feat_misses"] == n_in
+
+
+def _host_lines(base_ptr, byte_offsets):
+    """Distinct 128-byte lines among the addresses base_ptr + byte_offsets."""
+    return len(np.unique((base_ptr + np.asarray(byte_offsets, dtype=np.int64)) >> 7))
+
+
+def _expected_sampler_traffic(want, fanouts, indptr, adj_remap, indptr_base, indices_base):
+    """(bytes_hbm, bytes_host, host_lines) of sampling the batch `want` through a node-granular adjacency
+    cache, from the oracle's blocks and sampled positions: 16 bytes of list bounds per frontier node and
+    8 bytes per neighbour id, charged to the tier that serves the node; lines = per missed node, the lines
+    of its two list bounds plus the distinct lines of the neighbour ids it reads."""
+    b_hbm = b_host = lines = 0
+    for h in range(len(fanouts)):
+        frontier = want.nodes[:want.n_nodes[h]]
+        hit = adj_remap[frontier] >= 0 if adj_remap is not None else np.zeros(len(frontier), dtype=bool)
+        bi = want.blk_indptr[h]
+        rows = np.diff(bi)
+        b_hbm += 16 * int(hit.sum()) + 8 * int(rows[hit].sum())
+        b_host += 16 * int((~hit).sum()) + 8 * int(rows[~hit].sum())
+        for i in np.flatnonzero(~hit):
+            v = int(frontier[i])
+            lines += _host_lines(indptr_base, [8 * v, 8 * (v + 1)])
+            pos = want.src_pos[h][bi[i]:bi[i + 1]]
+            if len(pos):
+                lines += _host_lines(indices_base, 8 * (int(indptr[v]) + pos))
+    return b_hbm, b_host, lines
+
+
+@pytest.mark.parametrize("with_cache", [False, True])
+def test_traffic_statistics_match_counts_derived_from_the_oracle(env, with_cache):
+    """bytes_hbm / bytes_host / host_lines of sampling and gathering, exact."""
+    dci, gu, ctx, g, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "graph", "tiny", "w"))
+    oc = _oracle_caches(tiny, w) if with_cache else None
+    cache = gu.upload_cache(oc["adj_remap"], oc["c_indptr"], oc["c_indices"], oc["feat_remap"], oc["feat_cache"]) if oc else None
+    blk = dci.Blocks(ctx, w.num_nodes, w.batch_size, w.fanouts)
+    x = torch.empty(blk.cap_nodes[-1], w.feat_dim, dtype=torch.float32, device="cuda")
+    for b, fan in ((1, w.fanouts), (6, (12, 3))):
+        seeds = tiny["seeds"][b * w.batch_size:(b + 1) * w.batch_size]
+        blk = dci.Blocks(ctx, w.num_nodes, w.batch_size, fan)
+        stats = gu.new_stats()
+        dci.dci_sample_khop(ctx, g, cache, gu.dev(seeds), b, fan, w.rng_seed, blk, stats)
+        st = gu.stats_dict(ctx, stats)
+        want = oracle.sample_khop(tiny["indptr"], tiny["indices"], seeds, b, fan, w.rng_seed)
+        gu.assert_blocks_equal(gu.blocks_to_host(ctx, blk), want)
+        exp = _expected_sampler_traffic(want, fan, tiny["indptr"], oc["adj_remap"] if oc else None,
+                                        g.indptr.data_ptr(), g.indices.data_ptr())
+        assert (st["bytes_hbm"], st["bytes_host"], st["host_lines"]) == exp
+        assert exp[2] > 0 and (exp[0] > 0) == with_cache
+        # the gather adds one row of 4F bytes per input node to the tier that holds it
+        n_in = int(want.n_nodes[-1])
+        dci.dci_gather_features(ctx, g, cache, blk.nodes, n_in, x, stats=stats)
+        st2 = gu.stats_dict(ctx, stats)
+        hits = int((oc["feat_remap"][want.nodes] >= 0).sum()) if oc else 0
+        assert st2["bytes_hbm"] - st["bytes_hbm"] == 4 * w.feat_dim * hits
+        assert st2["bytes_host"] - st["bytes_host"] == 4 * w.feat_dim * (n_in - hits)
+        assert st2["host_lines"] == st["host_lines"]
+
+
+def test_relabel_timeout_voids_the_batch_and_is_reported(env):
+    """The frontier scan's give-up path, forced from the host: tiles are numbered from 1, so tile 0 never
+    exists and never publishes; with the spin limit at 200 polls every kernel still ends at once.  The next
+    dci_sync reports the failure, the batch's sizes are zero, a following gather / forward touches nothing,
+    and the context works again once the hook is off."""
+    dci, gu, g, tiny, w = (env[k] for k in ("dci", "gu", "graph", "tiny", "w"))
+    ctx = dci.Context(0, workspace_bytes=64 << 20)     # large enough for all three calls: growing it would sync
+    n = 600                                            # three scan tiles at hop 0 (256 rows each)
+    seeds = tiny["seeds"][:n]
+    blk = dci.Blocks(ctx, w.num_nodes, n, w.fanouts)
+    with pytest.raises(dci.DciError) as e:             # the hook is refused while the limit is at its default
+        ctx.set_option(dci.DCI_OPT_TEST_RELABEL_FIRST_TICKET, 1)
+    assert e.value.code == -1
+    ctx.set_option(dci.DCI_OPT_RELABEL_SPIN_LIMIT, 200)
+    ctx.set_option(dci.DCI_OPT_TEST_RELABEL_FIRST_TICKET, 1)
+    with pytest.raises(dci.DciError) as e:
+        ctx.set_option(dci.DCI_OPT_RELABEL_SPIN_LIMIT, 1 << 24)
+    assert e.value.code == -1
+    ws, wn, bs = ([gu.dev(a) for a in tiny[k]] for k in ("w_self", "w_neigh", "bias"))
+    x = torch.full((blk.cap_nodes[-1], w.feat_dim), 7.0, dtype=torch.float32, device="cuda")
+    logits = torch.full((n, w.classes), 9.0, dtype=torch.float32, device="cuda")
+    stats = gu.new_stats()
+    for first in (1, 40):                              # 40: every numbered tile lies beyond the frontier
+        ctx.set_option(dci.DCI_OPT_TEST_RELABEL_FIRST_TICKET, first)
+        blk.counts.fill_(123)
+        dci.dci_sample_khop(ctx, g, None, gu.dev(seeds), 0, w.fanouts, w.rng_seed, blk, stats)
+        dci.dci_gather_features(ctx, g, None, blk.nodes, blk.cap_nodes[-1], x, n_dev=blk.n_input_dev())
+        dci.dci_sage_forward(ctx, blk, x, ws, wn, bs, logits)
+        with pytest.raises(dci.DciError) as e:
+            ctx.sync()
+        assert e.value.code == -3 and "relabel scan timed out" in str(e.value)
+        ctx.sync()                                     # reported once
+        assert blk.counts.cpu().numpy().tolist() == [0] * 17 and blk.counts_host.numpy().tolist() == [0] * 17
+        assert bool((x == 7.0).all()) and bool((logits == 9.0).all())
+        assert stats.cpu().numpy().tolist() == [0] * dci.STATS_WORDS
+    ctx.set_option(dci.DCI_OPT_TEST_RELABEL_FIRST_TICKET, 0)
+    ctx.set_option(dci.DCI_OPT_RELABEL_SPIN_LIMIT, 1 << 24)
+    dci.dci_sample_khop(ctx, g, None, gu.dev(seeds), 0, w.fanouts, w.rng_seed, blk, stats)
+    gu.assert_blocks_equal(gu.blocks_to_host(ctx, blk), oracle.sample_khop(tiny["indptr"], tiny["indices"], seeds, 0,
+                                                                            w.fanouts, w.rng_seed))
