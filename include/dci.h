@@ -362,6 +362,39 @@ int32_t dci_gnn_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_i
                         const int32_t* dims, int32_t model, const float* const* w_self,
                         const float* const* w_neigh, const float* const* bias, float* logits);
 
+/* ---- inference over many batches, several in flight ----------------------------------------- */
+
+/* Inference over the batches [first_batch, first_batch + n_batches) of the seed list (Section V-B: a
+ * batch passes through sampling, feature loading and model computation, and the inference time is
+ * the sum over all test batches; Fig. 1).  Batch b covers seeds[b*batch_size .. min(n_seeds,
+ * (b+1)*batch_size)), uses RNG batch index b and goes, whole, through dci_sample_khop ->
+ * dci_gather_features -> dci_gnn_forward on lane (b - first_batch) mod n_lanes; its logits land in
+ * rows b*batch_size .. of `logits` (device [n_seeds, dims[n_hops]]).  A lane is a context - its own
+ * stream, and a workspace that covers both dci_sample_workspace_bytes and dci_sage_workspace_bytes
+ * for these sizes - with its own batch buffers (blocks sized by dci_blocks_bounds for batch_size
+ * seeds; x: device [blocks->cap_nodes, F]).  Batches on different lanes run concurrently, so the
+ * sampling of one batch overlaps the feature loading and the model computation of others; the
+ * graph, the cache, the weights and the seeds are shared and only read; `stats` (nullable) is
+ * shared and updated atomically.  The result of every batch is exactly what the three calls give
+ * one after the other on one context.  The call only enqueues: results are valid after dci_sync
+ * on every lane's context; each lane's blocks / x then hold the last batch that lane ran.  Work
+ * already enqueued on a lane's stream is waited for by that stream as usual; the caller must have
+ * made the inputs visible to all lanes' streams (e.g. by a device-wide synchronisation after
+ * dci_fill_caches).  No two lanes may share a context or a buffer (DCI_ERR_INVALID_ARG); at most
+ * DCI_MAX_LANES lanes.  model, dims, weights: as for dci_gnn_forward with n_layers = n_hops. */
+#define DCI_MAX_LANES 16
+typedef struct {
+  dci_ctx* ctx;
+  dci_blocks* blocks;
+  float* x;
+} dci_lane;
+int32_t dci_infer_batches(const dci_lane* lanes, int32_t n_lanes, const dci_graph* graph,
+                          const dci_cache* cache, const int64_t* seeds, int64_t n_seeds, int32_t batch_size,
+                          int64_t first_batch, int64_t n_batches, const int32_t* fanouts, int32_t n_hops,
+                          uint64_t rng_seed, int32_t model, const int32_t* dims, const float* const* w_self,
+                          const float* const* w_neigh, const float* const* bias, float* logits,
+                          uint64_t* stats);
+
 #ifdef __cplusplus
 }
 #endif

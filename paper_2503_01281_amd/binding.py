@@ -44,6 +44,10 @@ class _Cache(C.Structure):
                 ("feat_remap", C.c_void_p), ("feat_cache", C.c_void_p)]
 
 
+class _Lane(C.Structure):
+    _fields_ = [("ctx", C.c_void_p), ("blocks", C.c_void_p), ("x", C.c_void_p)]
+
+
 class _Blocks(C.Structure):
     _fields_ = [("n_hops", C.c_int32), ("cap_nodes", C.c_int64), ("cap_rows", C.c_int64 * DCI_MAX_HOPS),
                 ("cap_edges", C.c_int64 * DCI_MAX_HOPS), ("nodes", C.c_void_p),
@@ -90,6 +94,8 @@ def load_library():
     lib.dci_gather_features.argtypes = [P, P, P, P, i64, P, P, P]
     lib.dci_sage_forward.argtypes = [P, P, P, i32, P, P, P, P, P]
     lib.dci_gnn_forward.argtypes = [P, P, P, i32, P, i32, P, P, P, P]
+    lib.dci_infer_batches.argtypes = [P, i32, P, P, P, i64, i32, i64, i64, P, i32, u64, i32, P, P, P, P, P, P]
+    lib.dci_infer_batches.restype = i32
     lib.dci_probe_read.argtypes = [P, P, u64, i32, i32, i64, i32, u64, P, P]
     lib.dci_probe_read.restype = i32
     lib.dci_set_option.argtypes = [P, i32, i64]
@@ -436,3 +442,45 @@ def dci_gnn_forward(ctx: Context, blocks: Blocks, x_in: torch.Tensor, model: int
     else:
         ctx.check(ctx.lib.dci_gnn_forward(ctx.handle, C.byref(blocks.c), _ptr(x_in), L, _i32_array(dims), int(model),
                                           arr(w_self), arr(w_neigh), arr(bias), _ptr(logits)))
+
+
+class Lane:
+    """One lane of dci_infer_batches: a context on its own stream with its own batch buffers."""
+
+    def __init__(self, graph: Graph, batch_size: int, fanouts: Sequence[int], dims: Sequence[int], device: int = 0,
+                 stream: Optional["torch.cuda.Stream"] = None):
+        self.stream = stream if stream is not None else torch.cuda.Stream(device)
+        self.ctx = Context(device, stream=self.stream)
+        self.blocks = Blocks(self.ctx, graph.num_nodes, batch_size, fanouts)
+        self.x = torch.empty(max(self.blocks.cap_nodes[-1], 1), graph.feat_dim, dtype=torch.float32, device=self.ctx.device)
+        L = len(fanouts)
+        lib = self.ctx.lib
+        cap_rows = (C.c_int64 * DCI_MAX_HOPS)(*([self.blocks.cap_nodes[h] for h in range(L)] + [0] * (DCI_MAX_HOPS - L)))
+        need = max(lib.dci_sample_workspace_bytes(graph.num_nodes, batch_size, _i32_array(fanouts), L),
+                   lib.dci_sage_workspace_bytes(cap_rows, L, _i32_array(dims)), 1 << 20)
+        self.ctx.ensure_workspace(need)
+
+
+def dci_infer_batches(lanes: Sequence[Lane], graph: Graph, cache: Optional[Cache], seeds: torch.Tensor, batch_size: int,
+                      first_batch: int, n_batches: int, fanouts: Sequence[int], rng_seed: int, model: int,
+                      w_self: Optional[Sequence[torch.Tensor]], w_neigh: Sequence[torch.Tensor],
+                      bias: Sequence[torch.Tensor], logits: torch.Tensor, stats: Optional[torch.Tensor] = None):
+    """Enqueues the batches round-robin on the lanes and returns; sync every lane's context before reading."""
+    assert seeds.is_cuda and seeds.dtype == torch.int64 and seeds.is_contiguous()
+    L = len(w_neigh)
+    assert L == len(fanouts)
+    dims = [int(w_neigh[0].shape[0])] + [int(w.shape[1]) for w in w_neigh]
+    for t in list(w_self or []) + list(w_neigh) + list(bias) + [logits]:
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+    assert logits.numel() >= seeds.numel() * dims[L]
+    arr = lambda ts: None if ts is None else (C.c_void_p * L)(*[t.data_ptr() for t in ts])
+    c_lanes = (_Lane * len(lanes))()
+    for k, ln in enumerate(lanes):
+        c_lanes[k].ctx = ln.ctx.handle
+        c_lanes[k].blocks = C.addressof(ln.blocks.c)
+        c_lanes[k].x = ln.x.data_ptr()
+    ctx = lanes[0].ctx
+    ctx.check(ctx.lib.dci_infer_batches(c_lanes, len(lanes), C.byref(graph.c), None if cache is None else C.byref(cache.c),
+                                        _ptr(seeds), seeds.numel(), batch_size, first_batch, n_batches,
+                                        _i32_array(fanouts), L, rng_seed, int(model), _i32_array(dims), arr(w_self),
+                                        arr(w_neigh), arr(bias), _ptr(logits), _ptr(stats)))

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdci.so")
-SOURCES = ["dci_ctx.hip", "dci_sample.hip", "dci_gather.hip", "dci_sage.hip", "dci_fill.hip", "dci_probe.hip"]
+SOURCES = ["dci_ctx.hip", "dci_sample.hip", "dci_gather.hip", "dci_sage.hip", "dci_fill.hip", "dci_probe.hip", "dci_pipeline.hip"]
 HEADERS = [os.path.join(CSRC, "dci_internal.h"), os.path.join(ROOT, "include", "dci.h")]
 
 # Packed-fp32 instructions are switched off for all device code on purpose.
