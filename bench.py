@@ -3,21 +3,35 @@
 
 A step is one pass of the per-batch path (cache-aware k-hop sampling -> cache-aware feature
 gather -> GraphSAGE-mean forward) over one mini-batch of the workload; the one-off part of the
-path (pre-sampling counts, Eq. (1) split, dual-cache fill) runs before the timed region and is
-reported separately.  Inputs are seeded synthetic R-MAT graphs / Gaussian features / Glorot
-weights with the shapes of the paper's datasets, resident in pinned host memory (graph,
-features) and HBM (caches, seeds, weights) when the timed region starts.
+path (pre-sampling counts, Eq. (1) split with the stage times measured while pre-sampling,
+dual-cache fill) runs before the timed region and is reported separately.  Inputs are seeded
+synthetic R-MAT graphs / Gaussian features / Glorot weights with the shapes of the paper's
+datasets, resident in pinned host memory (graph, features) and HBM (caches, seeds, weights) when
+the timed region starts.  The default workload is the largest single-GPU configuration ("huge",
+the shape of Ogbn-papers100M with a 64 GB budget).
 
-Prints ONE JSON line.  `value` is sampled edges per second over whole steps; the gather
-bandwidth, hit rates and per-kernel times ride along, plus
-  roofline     - the dominant kernel against MI355X's published peak, timed with HIP events
-                 inside the timed region;
-  cpu_baseline - the CPU oracle timed on this machine's host cores on a bounded sample.
+Regions, in order (all over the same K batches 0..K-1):
+  warm-up        W steps, untimed;
+  kernel pass    K steps, untimed, with every kernel class bracketed by HIP events on the
+                 library's stream -> extras.rooflines (one entry per class: algorithmic bytes /
+                 flops from the batches' own device-side sizes against the bound that applies)
+                 and the choice of the dominant kernel (largest average launch);
+  timed region   EXACTLY K steps on one stream (one lane of dci_infer_batches) with only the
+                 dominant class bracketed -> value, ms_per_step, roofline;
+  pipelined      the same K steps with `--lanes` batches in flight -> extras.pipelined;
+  end to end     pre-sampling + fill + one pass over ALL batches of the workload, pipelined,
+                 measured wall time -> extras.end_to_end;
+  memory rates   streaming and random reads of HBM and of pinned host memory (dci_probe_read) and
+                 a pinned host -> HBM copy -> extras.memory_rates (the measured denominators);
+  cpu_baseline   the CPU oracle on this machine's host cores on a bounded sample (one thread,
+                 then one thread per core over independent batches), and a parity check of the
+                 benchmarked batch 0 against it.
+
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
 import argparse
-import ctypes as C
 import json
 import os
 import sys
@@ -39,9 +53,9 @@ def log(*a):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=54)
+    ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="medium", choices=["tiny", "medium", "large", "huge", "skewed", "yelp", "amazon"])
+    ap.add_argument("--workload", default="huge", choices=["tiny", "medium", "large", "huge", "skewed", "yelp", "amazon"])
     ap.add_argument("--placement", default="auto", choices=["auto", "host", "indices-hbm", "features-hbm"],
                     help="where the graph and the features live: 'host' = all in pinned host memory; 'indices-hbm' = "
                          "features and list bounds pinned, neighbour ids in HBM; 'features-hbm' = graph pinned, features "
@@ -50,6 +64,8 @@ def main() -> int:
     ap.add_argument("--feat-policy", type=int, default=0)
     ap.add_argument("--budget", type=float, default=None, help="cache budget in bytes (default: the workload's)")
     ap.add_argument("--n-presample", type=int, default=None, help="pre-sampled batches (default: the workload's 8)")
+    ap.add_argument("--split-times", default=None, metavar="TS:TF",
+                    help="fixed t_sample:t_feature for Eq. (1) instead of the times measured while pre-sampling")
     ap.add_argument("--single-cache", action="store_true",
                     help="the paper's single-cache comparison: the whole budget goes to features, no adjacency cache")
     ap.add_argument("--adj-elements", action="store_true",
@@ -58,21 +74,21 @@ def main() -> int:
     ap.add_argument("--model", default="sage-mean", choices=["sage-mean", "sage-sum", "gcn-avg"],
                     help="GNN of the forward pass (Table III); the headline configuration is sage-mean")
     ap.add_argument("--linear-kernel", type=int, default=0, choices=[0, 1, 2, 3],
-                    help="dense-layer kernel of the timed region: 0 by shape (default), 1 register-staged tile kernel, "
-                         "2 wide kernel, 3 by shape without the wide kernel")
+                    help="dense-layer kernel of the single-stream regions: 0 by shape (default), 1 register-staged tile "
+                         "kernel, 2 wide kernel, 3 by shape without the wide kernel")
+    ap.add_argument("--pipelined-linear-kernel", type=int, default=1, choices=[0, 1, 2, 3],
+                    help="dense-layer kernel of the pipelined regions (the statically partitioned wide kernel loses "
+                         "when other streams share the compute units)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-batches", type=int, default=8, help="batches the CPU oracle is timed on")
-    ap.add_argument("--streams", type=int, default=1,
-                    help="HIP streams of the timed region; each runs whole steps on its share of the batches. The "
-                         "default 1 keeps every kernel alone on the chip so that the per-kernel roofline is clean")
-    ap.add_argument("--extra-streams", type=int, default=4,
-                    help="after the timed region, time the same K steps once more on this many streams and report "
-                         "it under extras.multi_stream (0 = skip)")
+    ap.add_argument("--cpu-batches", type=int, default=None, help="batches the single-thread CPU oracle is timed on")
+    ap.add_argument("--lanes", type=int, default=4, help="batches in flight in the pipelined regions (0 or 1 = skip them)")
+    ap.add_argument("--roofline-kernel", default="auto",
+                    help="kernel class of the top-level roofline (default: the one with the largest average launch in "
+                         "the kernel pass)")
+    ap.add_argument("--no-end-to-end", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="after the timed region run one device-to-device copy of 1 GiB (a kernel of known "
-                         "traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
-    ap.add_argument("--time-all-kernels", action="store_true",
-                    help="bracket every kernel class with events (perturbs the step time slightly)")
+                    help="at the end run one device-to-device copy of 1 GiB (a kernel of known traffic for scaling "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
@@ -94,8 +110,8 @@ def main() -> int:
     t0 = time.time()
     # Placement.  The graph and the feature matrix belong in pinned host memory (zero-copy misses over the host
     # link).  A GPU machine pins at most 64 GiB, less than the two largest workloads need (70.7 / 81.5 GB), so for
-    # those the feature matrix and the list-bound array stay pinned and the neighbour-id array - which the
-    # adjacency cache covers in full or nearly so at their budgets - is placed in HBM, standing in for the host tier.
+    # those the feature matrix and the list-bound array stay pinned and the neighbour-id array is placed in HBM,
+    # standing in for the host tier.
     place = args.placement
     if place == "auto":
         place = "host" if w.adj_bytes + w.feat_bytes <= PIN_LIMIT_BYTES else "indices-hbm"
@@ -125,16 +141,23 @@ def main() -> int:
     seeds_h = synth.seeds(w.num_nodes, w.num_seeds, w.seed_seed)
     ws_h, wn_h, b_h = synth.sage_weights(w.dims, w.weight_seed)
     log(f"[bench] inputs for '{w.name}' generated in {time.time() - t0:.1f}s "
-        f"(N={w.num_nodes} E={w.num_edges} F={w.feat_dim})")
+        f"(N={w.num_nodes} E={w.num_edges} F={w.feat_dim}, placement {place})")
 
-    ctx = dci.Context(0)
+    model = {"sage-mean": 0, "sage-sum": 1, "gcn-avg": 2}[args.model]
+    k_ops = 1 if model == 2 else 2      # operands of the dense layer's contraction (GCN has one weight matrix)
     g = dci.Graph(indptr, indices, feat)
     seeds = torch.from_numpy(seeds_h).cuda()
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
     ws, wn, bs = [dev(a) for a in ws_h], [dev(a) for a in wn_h], [dev(a) for a in b_h]
-    blk = dci.Blocks(ctx, w.num_nodes, w.batch_size, w.fanouts)
-    x = torch.empty(blk.cap_nodes[-1], w.feat_dim, dtype=torch.float32, device="cuda")
-    logits = torch.empty(w.batch_size, w.classes, dtype=torch.float32, device="cuda")
+    ws_arg = None if model == 2 else ws
+    n_lanes = max(1, args.lanes)
+    # lane 0 runs on PyTorch's current stream (the single-stream regions); the others on streams of their own,
+    # all at the default priority
+    lanes = [dci.Lane(g, w.batch_size, w.fanouts, w.dims, stream=torch.cuda.current_stream() if k == 0 else None)
+             for k in range(n_lanes)]
+    ctx, blk, x = lanes[0].ctx, lanes[0].blocks, lanes[0].x
+    nb = w.num_batches
+    logits = torch.empty(w.num_seeds, w.classes, dtype=torch.float32, device="cuda")
 
     # ---- one-off part: pre-sampling counts (timed per stage for Eq. (1)) and the dual-cache fill
     cache = None
@@ -145,7 +168,7 @@ def main() -> int:
         stats = torch.zeros(dci.STATS_WORDS, dtype=torch.int64, device="cuda")
         ec = torch.zeros(w.num_edges, dtype=torch.int32, device="cuda") if args.adj_elements else None
         fill_flags = args.feat_policy | (dci.DCI_FILL_ADJ_ELEMENTS if args.adj_elements else 0)
-        ctx.sync()
+        torch.cuda.synchronize()
         t0 = time.time()
         dci.dci_presample_count(ctx, g, None, seeds, w.batch_size, 0, w.n_presample, w.presample_first_batch,
                                 w.fanouts, w.rng_seed, fc, ac, ec, feat_scratch=x, stats=stats)
@@ -153,104 +176,229 @@ def main() -> int:
         t1 = time.time()
         st = stats.cpu().numpy()
         ts, tf = int(st[dci.STAT["t_sample_ns"]]), int(st[dci.STAT["t_feature_ns"]])
+        ts_used, tf_used = ts, tf
+        if args.split_times:
+            ts_used, tf_used = (int(v) for v in args.split_times.split(":"))
         if args.single_cache:
             cache = dci.dci_fill_caches(ctx, g, fc, ac, w.budget_bytes, 0, 1, fill_flags | dci.DCI_FILL_STRICT_SPLIT,
                                         edge_count=ec)
         else:
-            cache = dci.dci_fill_caches(ctx, g, fc, ac, w.budget_bytes, ts, tf, fill_flags, edge_count=ec)
+            cache = dci.dci_fill_caches(ctx, g, fc, ac, w.budget_bytes, ts_used, tf_used, fill_flags, edge_count=ec)
         del ec
         t2 = time.time()
         pre = dict(presample_s=round(t1 - t0, 4), fill_s=round(t2 - t1, 4), t_sample_ns=ts, t_feature_ns=tf,
+                   split_times="measured" if not args.split_times else args.split_times,
                    cap_adj_bytes=int(cache.cap_adj_bytes), cap_feat_bytes=int(cache.cap_feat_bytes),
                    adj_nodes=int(cache.adj_nodes), adj_edges=int(cache.adj_edges), feat_rows=int(cache.feat_rows),
                    adj_elements=bool(args.adj_elements), adj_partial_node=int(cache.adj_partial_node))
         log(f"[bench] preprocess: {pre}")
-
-    nb = w.num_batches
-
-    # Batches are independent, so S streams each run whole steps (sample -> gather -> forward, own
-    # context, workspace and buffers) on batches b = s (mod S): the short latency-bound sampling
-    # kernels, the bandwidth-bound gather / mean and the MFMA-bound dense layers of different batches
-    # then share the chip.  All streams have the default priority.
-    n_streams = max(1, args.streams, args.extra_streams)  # buffers for the larger of the two regions
-    main = torch.cuda.current_stream()
-    streams = [main] + [torch.cuda.Stream() for _ in range(n_streams - 1)]
-    ctxs = [ctx] + [dci.Context(0, stream=st_) for st_ in streams[1:]]
-    blks = [blk] + [dci.Blocks(ctx, w.num_nodes, w.batch_size, w.fanouts) for _ in range(n_streams - 1)]
-    xs = [x] + [torch.empty_like(x) for _ in range(n_streams - 1)]
-    outs = [logits] + [torch.empty_like(logits) for _ in range(n_streams - 1)]
-    ws_need = ctx.lib.dci_sample_workspace_bytes(w.num_nodes, w.batch_size, (C.c_int32 * w.n_hops)(*w.fanouts), w.n_hops)
-    sg_need = ctx.lib.dci_sage_workspace_bytes((C.c_int64 * 8)(*(blk.cap_nodes[:w.n_hops] + [0] * (8 - w.n_hops))),
-                                               w.n_hops, (C.c_int32 * (w.n_hops + 1))(*w.dims))
-    for c_ in ctxs:
-        c_.ensure_workspace(max(ws_need, sg_need, 1 << 20))
     torch.cuda.synchronize()
 
-    model = {"sage-mean": 0, "sage-sum": 1, "gcn-avg": 2}[args.model]
-    k_ops = 1 if model == 2 else 2      # operands of the dense layer's contraction (GCN has one weight matrix)
+    def run(first: int, count: int, use_lanes: int, stats_t=None):
+        """Batches first .. first+count-1 on the first `use_lanes` lanes; returns when all of them are done."""
+        dci.dci_infer_batches(lanes[:use_lanes], g, cache, seeds, w.batch_size, first, count, w.fanouts, w.rng_seed,
+                              model, ws_arg, wn, bs, logits, stats_t)
+        for ln in lanes[:use_lanes]:
+            ln.ctx.sync()
 
-    def step(b: int, k: int, stats_t):
-        lo = (b % nb) * w.batch_size
-        c_, bk = ctxs[k], blks[k]
-        dci.dci_sample_khop(c_, g, cache, seeds[lo:lo + w.batch_size], b % nb, w.fanouts, w.rng_seed, bk, stats_t)
-        dci.dci_gather_features(c_, g, cache, bk.nodes, bk.cap_nodes[-1], xs[k], n_dev=bk.n_input_dev(), stats=stats_t)
-        if model == 0:
-            dci.dci_sage_forward(c_, bk, xs[k], ws, wn, bs, outs[k])
-        else:
-            dci.dci_gnn_forward(c_, bk, xs[k], model, ws, wn, bs, outs[k])
+    K = min(args.steps, nb)
+    if K < args.steps:
+        log(f"[bench] the workload has {nb} batches: timing {K} steps instead of {args.steps}")
+    ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, args.linear_kernel)
+    run(0, min(args.warmup, nb), 1)
 
-    def run_steps(first: int, count: int, stats_list, use_streams: int):
-        """Exactly `count` whole steps (batches first .. first+count-1); nothing is in flight before or after."""
-        for st_ in streams[1:use_streams]:
-            st_.wait_stream(main)
-        for b in range(first, first + count):
-            k = (b - first) % use_streams
-            with torch.cuda.stream(streams[k]):
-                step(b, k, None if stats_list is None else stats_list[k])
-        for st_ in streams[1:use_streams]:
-            main.wait_stream(st_)
+    # ---- kernel pass: every class bracketed; per-hop sizes of every batch from the device-side counts
+    ctx.timing_enable(dci.KERNEL_CLASSES)
+    stats_k = torch.zeros(dci.STATS_WORDS, dtype=torch.int64, device="cuda")
+    hop_nodes = np.zeros(w.n_hops + 1, dtype=np.int64)
+    hop_edges = np.zeros(w.n_hops, dtype=np.int64)
+    flops_layer = np.zeros(w.n_hops)
+    for b in range(K):
+        run(b, 1, 1, stats_k)
+        nn, ne = blk.n_nodes(), blk.n_edges()
+        hop_nodes += np.array(nn, dtype=np.int64)
+        hop_edges += np.array(ne, dtype=np.int64)
+        for l in range(w.n_hops):
+            flops_layer[l] += 2.0 * nn[w.n_hops - 1 - l] * (k_ops * w.dims[l]) * w.dims[l + 1]
+    timing_all = ctx.timing_read()
+    ctx.timing_enable([])
+    sk = {k: int(v) for k, v in zip(dci.STAT.keys(), stats_k.cpu().numpy()[:len(dci.STAT)])}
 
-    for c_ in ctxs:
-        c_.set_option(dci.DCI_OPT_LINEAR_KERNEL, args.linear_kernel)
-    run_steps(0, args.warmup, None, max(1, args.streams))
+    # ---- memory rates measured in this run (the denominators of the access-bound kernels)
+    rates = {}
+    probe_dev = cache.buf if cache is not None else torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    dev_bytes = min(probe_dev.numel() - 512, 8 << 30)
+    host_t = feat if feat.is_pinned() else indices
+    host_bytes = min(host_t.numel() * host_t.element_size() - 512, 2 << 30)
+
+    def probe(mem, nbytes, granule, n):
+        dci.dci_probe_read(ctx, mem, granule, n, 0, 4096, 11, nbytes)
+        return min(dci.dci_probe_read(ctx, mem, granule, n, 0, 4096, 12 + r, nbytes) for r in range(2))
+
+    rates["hbm_stream_read_GBps"] = round(dev_bytes / probe(probe_dev, dev_bytes, 0, 0) / 1e6, 1)
+    for gran in (8, 64, 128):
+        rates[f"hbm_random_{gran}B_Gacc_per_s"] = round((1 << 25) / probe(probe_dev, dev_bytes, gran, 1 << 25) / 1e6, 2)
+    rates["host_zero_copy_stream_GBps"] = round(host_bytes / probe(host_t, host_bytes, 0, 0) / 1e6, 1)
+    for gran in (8, 64, 128, 512):
+        rates[f"host_zero_copy_random_{gran}B_Gacc_per_s"] = round((1 << 20) / probe(host_t, host_bytes, gran, 1 << 20) / 1e6, 4)
+    flat = host_t.view(-1)
+    n_link = min(flat.numel(), (1 << 30) // flat.element_size())
+    link_dst = torch.empty(n_link, dtype=flat.dtype, device="cuda")
+    link_ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    link_dst.copy_(flat[:n_link], non_blocking=True)
     torch.cuda.synchronize()
+    link_ev[0].record()
+    link_dst.copy_(flat[:n_link], non_blocking=True)
+    link_ev[1].record()
+    torch.cuda.synchronize()
+    host_link_gbps = n_link * flat.element_size() / (link_ev[0].elapsed_time(link_ev[1]) * 1e-3) / 1e9
+    rates["host_pinned_copy_GBps"] = round(host_link_gbps, 1)
+    del link_dst
+    line_rate = rates["host_zero_copy_random_128B_Gacc_per_s"] * 1e9     # 128-byte host lines per second
+    # random reads of one feature row over the link: a row of 4F bytes is one request of up to 512 bytes, or several
+    row_bytes = 4 * w.feat_dim
+    row_gran = 512 if row_bytes >= 512 else 128
+    row_link_rate = rates[f"host_zero_copy_random_{row_gran}B_Gacc_per_s"] * 1e9 * row_gran   # bytes per second
+    hbm_bw = HBM_PEAK_GBPS * 1e9
 
-    # ---- timed region: exactly K steps; the dominant kernel class is bracketed by events
-    dominant = "linear_in"
-    for c_ in ctxs:
-        c_.timing_enable(dci.KERNEL_CLASSES if args.time_all_kernels else [dominant, "gather"])
-    stats_list = [torch.zeros(dci.STATS_WORDS, dtype=torch.int64, device="cuda") for _ in range(n_streams)]
+    # ---- per-class rooflines from the kernel pass (units per SURVEY-style accounting, stated in DESIGN.md):
+    #   sampling  28 B per frontier node (id, remap, list bounds) + 16 B per edge (id read, id written);
+    #             what a miss reads from pinned host memory is charged in 128-byte lines over the link
+    #   relabel   20 B per edge (table probe + local id) + 8 B per new node        gather  8F+12 B per row
+    #   mean      4D B per edge + 4D B per destination row                         linear  2 n (k D) D' flop
+    F, L = w.feat_dim, w.n_hops
+    rows_total = int(hop_nodes[:L].sum())
+    edges_total = int(hop_edges.sum())
+    n_in_total = int(hop_nodes[L])
+    miss_rows = rows_total - sk["adj_node_hits"]
+    link_lines = (sk["lines_bounds"] if indptr.is_pinned() else 0) + (sk["lines_ids"] if indices.is_pinned() else 0)
+    link_bytes_sampler = (16 * miss_rows if indptr.is_pinned() else 0) + (8 * sk["adj_edge_misses"] if indices.is_pinned() else 0)
+    table_entries = 1024
+    while table_entries < 2 * blk.cap_nodes[L]:
+        table_entries *= 2
+
+    def entry(kernel, cls, t_bound_parts, achieved, peak, unit, **more):
+        """t_bound_parts: {bound name: seconds that bound allows}; the largest one is the class's bound."""
+        t_ms, n = timing_all[cls]
+        bound = max(t_bound_parts, key=t_bound_parts.get)
+        t_bound = t_bound_parts[bound]
+        d = {"kernel": kernel, "bound": bound, "achieved": None, "peak": None, "unit": unit[bound],
+             "frac": round(t_bound / (t_ms * 1e-3), 4) if t_ms > 0 else None,
+             "ms_per_step": round(t_ms / K, 4), "launches_per_step": round(n / K, 2)}
+        if t_ms > 0:
+            d["achieved"] = round(achieved[bound] / (t_ms * 1e-3), 3)
+            d["peak"] = round(peak[bound], 3)
+        d.update(more)
+        return d
+
+    GB, unit_hbm = 1e9, {"hbm": "GB/s", "host_link": "G lines/s", "host_link_bytes": "GB/s", "mfma": "TFLOP/s"}
+    rooflines = {}
+    clear_bytes = 8 * table_entries * K
+    rooflines["table_clear"] = entry("k_fill_u32x4", "table_clear", {"hbm": clear_bytes / hbm_bw}, {"hbm": clear_bytes / GB},
+                                     {"hbm": HBM_PEAK_GBPS}, unit_hbm, bytes_per_step=8 * table_entries)
+    samp_hbm = 28 * rows_total + 16 * edges_total - link_bytes_sampler
+    rooflines["sample"] = entry("k_sample_hop", "sample",
+                                {"hbm": samp_hbm / hbm_bw, "host_link": link_lines / line_rate if line_rate else 0.0},
+                                {"hbm": samp_hbm / GB, "host_link": link_lines / 1e9},
+                                {"hbm": HBM_PEAK_GBPS, "host_link": line_rate / 1e9}, unit_hbm,
+                                hbm_bytes_per_step=round(samp_hbm / K), host_lines_per_step=round(link_lines / K, 1),
+                                host_bytes_per_step=round(link_bytes_sampler / K),
+                                frontier_nodes_per_step=round(rows_total / K, 1))
+    relabel_bytes = 20 * edges_total + 8 * int(hop_nodes[L] - hop_nodes[0])
+    t_rl = timing_all["relabel"][0] + timing_all["write_src"][0]
+    timing_all["relabel+write_src"] = (t_rl, timing_all["relabel"][1] + timing_all["write_src"][1])
+    rooflines["relabel"] = entry("k_relabel_hop + k_write_src", "relabel+write_src", {"hbm": relabel_bytes / hbm_bw},
+                                 {"hbm": relabel_bytes / GB}, {"hbm": HBM_PEAK_GBPS}, unit_hbm,
+                                 bytes_per_step=round(relabel_bytes / K))
+    g_hbm = sk["feat_hits"] * (8 * F + 12) + sk["feat_misses"] * ((4 * F + 12) if feat.is_pinned() else (8 * F + 12))
+    g_link = sk["feat_misses"] * 4 * F if feat.is_pinned() else 0
+    rooflines["gather"] = entry("k_gather", "gather",
+                                {"hbm": g_hbm / hbm_bw, "host_link_bytes": g_link / row_link_rate if row_link_rate else 0.0},
+                                {"hbm": g_hbm / GB, "host_link_bytes": g_link / GB},
+                                {"hbm": HBM_PEAK_GBPS, "host_link_bytes": row_link_rate / GB}, unit_hbm,
+                                hbm_bytes_per_step=round(g_hbm / K), host_bytes_per_step=round(g_link / K),
+                                rows_per_step=round(n_in_total / K, 1))
+    for l in range(L):
+        h = L - 1 - l
+        cls_m, cls_l = ("mean_in", "linear_in") if l == 0 else ("mean", "linear")
+        mb = 4 * w.dims[l] * (int(hop_edges[h]) + int(hop_nodes[h]))
+        if l <= 1:
+            if l == 1 and L > 2:       # the later layers share one class: add them up
+                mb = sum(4 * w.dims[j] * (int(hop_edges[L - 1 - j]) + int(hop_nodes[L - 1 - j])) for j in range(1, L))
+            rooflines[cls_m] = entry("k_sage_mean", cls_m, {"hbm": mb / hbm_bw}, {"hbm": mb / GB}, {"hbm": HBM_PEAK_GBPS},
+                                     unit_hbm, bytes_per_step=round(mb / K))
+            fl = flops_layer[0] if l == 0 else float(flops_layer[1:].sum())
+            rooflines[cls_l] = entry("dense layer (fp32 MFMA)", cls_l, {"mfma": fl / (FP32_MFMA_PEAK_TFLOPS * 1e12)},
+                                     {"mfma": fl / 1e12}, {"mfma": FP32_MFMA_PEAK_TFLOPS}, unit_hbm,
+                                     flops_per_step=round(fl / K))
+    avg_launch = {c: (timing_all[c][0] / timing_all[c][1]) for c in dci.KERNEL_CLASSES if timing_all[c][1]}
+    dominant = args.roofline_kernel if args.roofline_kernel != "auto" else max(avg_launch, key=avg_launch.get)
+    roof_key = {"write_src": "relabel"}.get(dominant, dominant)
+
+    # ---- timed region: exactly K steps, one stream, only the dominant class bracketed
+    ctx.timing_enable([dominant])
+    stats_t = torch.zeros(dci.STATS_WORDS, dtype=torch.int64, device="cuda")
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     ev[0].record()
-    run_steps(0, args.steps, stats_list, max(1, args.streams))
+    run(0, K, 1, stats_t)
     ev[1].record()
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    wall_s = t1 - t0
-    timing = {k: (0.0, 0) for k in dci.KERNEL_CLASSES}
-    for c_ in ctxs:
-        for k, v in c_.timing_read().items():
-            timing[k] = (timing[k][0] + v[0], timing[k][1] + v[1])
-        c_.timing_enable([])
-    stats = sum(stats_list[1:], stats_list[0])
-    st = {k: int(v) for k, v in zip(dci.STAT.keys(), stats.cpu().numpy()[:len(dci.STAT)])}
-    multi = None
-    if args.extra_streams > 1:
-        # with several batches in flight the statically partitioned wide dense-layer kernel (one workgroup per
-        # compute unit) loses to the tile kernel, whose many small workgroups fill whatever the other streams leave
-        for c_ in ctxs:
-            c_.set_option(dci.DCI_OPT_LINEAR_KERNEL, 1)
-        run_steps(0, min(args.steps, 2 * args.extra_streams), None, args.extra_streams)
+    wall_s = time.perf_counter() - t0
+    dom_ms, dom_n = ctx.timing_read()[dominant]
+    ctx.timing_enable([])
+    st = {k: int(v) for k, v in zip(dci.STAT.keys(), stats_t.cpu().numpy()[:len(dci.STAT)])}
+    edges = st["edges_sampled"]
+    rows = st["feat_hits"] + st["feat_misses"]
+    value = edges / wall_s
+
+    # the top-level roofline: the dominant class with the timed region's own event times
+    r0 = dict(rooflines[roof_key])
+    if dominant == roof_key:
+        scale = (timing_all[dominant][0] / dom_ms) if dom_ms > 0 else 0.0
+        r0["achieved"] = round(r0["achieved"] * scale, 3) if r0["achieved"] is not None else None
+        r0["frac"] = round(r0["frac"] * scale, 4) if r0["frac"] is not None else None
+    roofline = {"kernel": r0["kernel"], "bound": r0["bound"], "achieved": r0["achieved"], "peak": r0["peak"],
+                "unit": r0["unit"], "frac": r0["frac"], "traffic": None, "traffic_source": None, "launches": dom_n,
+                "avg_launch_ms": round(dom_ms / max(dom_n, 1), 4), "class": dominant}
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath) and model == 0:
+        try:
+            roofline["traffic"] = json.load(open(tpath)).get(f"{dominant}:{w.name}")
+            if roofline["traffic"] is not None:
+                roofline["traffic_source"] = "profiles/traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, not measured in this run)"
+        except Exception:
+            pass
+
+    # ---- pipelined: the same K steps with several batches in flight
+    pipelined = None
+    if args.lanes > 1:
+        for ln in lanes:
+            ln.ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, args.pipelined_linear_kernel)
+        run(0, min(K, 2 * args.lanes), args.lanes)
         torch.cuda.synchronize()
         tm0 = time.perf_counter()
-        run_steps(0, args.steps, None, args.extra_streams)
+        run(0, K, args.lanes)
         torch.cuda.synchronize()
         tm = time.perf_counter() - tm0
-        multi = {"streams": args.extra_streams, "linear_kernel": "tile", "ms_per_step": round(tm * 1e3 / args.steps, 4)}
-        for c_ in ctxs:
-            c_.set_option(dci.DCI_OPT_LINEAR_KERNEL, args.linear_kernel)
+        pipelined = {"lanes": args.lanes, "linear_kernel": args.pipelined_linear_kernel, "ms_per_step": round(tm * 1e3 / K, 4),
+                     "value": round(edges / tm, 1)}
+
+    # ---- end to end: pre-sampling + fill (measured above) + one pass over all batches, pipelined, wall time
+    e2e = None
+    if not args.no_end_to_end:
+        use = max(1, args.lanes)
+        torch.cuda.synchronize()
+        te0 = time.perf_counter()
+        run(0, nb, use)
+        torch.cuda.synchronize()
+        te = time.perf_counter() - te0
+        e2e = {"batches": nb, "lanes": use, "inference_s": round(te, 4), "presample_s": pre.get("presample_s"),
+               "fill_s": pre.get("fill_s"),
+               "total_s": round(te + (pre.get("presample_s") or 0.0) + (pre.get("fill_s") or 0.0), 4)}
+    for ln in lanes:
+        ln.ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, args.linear_kernel)
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -259,75 +407,14 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    # host-link reference: one pinned-host -> HBM copy of the first GiB (or all) of the edge array
-    link_src = indptr if not indices.is_pinned() else indices
-    n_link = min(link_src.numel(), 1 << 27)
-    link_dst = torch.empty(n_link, dtype=torch.int64, device="cuda")
-    link_ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    link_dst.copy_(link_src[:n_link], non_blocking=True)
-    torch.cuda.synchronize()
-    link_ev[0].record()
-    link_dst.copy_(link_src[:n_link], non_blocking=True)
-    link_ev[1].record()
-    torch.cuda.synchronize()
-    host_link_gbps = n_link * 8 / (link_ev[0].elapsed_time(link_ev[1]) * 1e-3) / 1e9
-    del link_dst
-
-    edges = st["edges_sampled"]
-    rows = st["feat_hits"] + st["feat_misses"]
-    gather_bytes = rows * w.feat_dim * 4
-    gather_ms, gather_n = timing["gather"]
-    value = edges / wall_s
-    if multi is not None:
-        multi["value"] = round(edges / (multi["ms_per_step"] * 1e-3 * args.steps), 1)  # same K batches, same edges
-
-    # ---- roofline of the dominant kernel: the first dense layer (fp32 MFMA, K = 2 * feat_dim).
-    # Flops per launch are 2 * n_nodes[L-1] * (2 * dims[0]) * dims[1]; the row counts of the timed
-    # batches are re-derived by sampling them again outside the timed region (sampling is a pure
-    # function of the batch), the duration is the event time of the same launches.
-    lin_ms, lin_n = timing[dominant]
-    flops_in = flops_all = 0.0
-    for b in range(args.steps):
-        lo = (b % nb) * w.batch_size
-        dci.dci_sample_khop(ctx, g, cache, seeds[lo:lo + w.batch_size], b % nb, w.fanouts, w.rng_seed, blk, None)
-        ctx.sync()
-        nn = blk.n_nodes()
-        for l in range(w.n_hops):
-            fl = 2.0 * nn[w.n_hops - 1 - l] * (k_ops * w.dims[l]) * w.dims[l + 1]
-            flops_all += fl
-            if l == 0:
-                flops_in += fl
-    lin_tflops = flops_in / (lin_ms * 1e-3) / 1e12 if lin_ms > 0 else 0.0
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath) and model == 0:   # the stored counters are of the GraphSAGE-mean launch
-        try:
-            traffic = json.load(open(tpath)).get(f"{dominant}:{w.name}")
-        except Exception:
-            traffic = None
-    if args.linear_kernel in (0, 2) and w.dims[1] % 128 == 0 and w.dims[0] % 2 == 0 and (w.dims[0] >= 192 or args.linear_kernel == 2):
-        lin_kernel = "k_sage_linear_wide"
-    elif (args.linear_kernel in (0, 3) and w.dims[1] % 64 == 0 and w.dims[0] % 2 == 0
-          and ((blk.cap_nodes[w.n_hops - 1] + 63) // 64 + 7) // 8 * 8 * (w.dims[1] // 64) > 128):   # else the split path
-        lin_kernel = "k_sage_linear_dma"
-    else:
-        lin_kernel = "k_sage_linear"
-    roofline = {"kernel": lin_kernel + " (first layer)", "bound": "mfma", "achieved": round(lin_tflops, 3),
-                "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(lin_tflops / FP32_MFMA_PEAK_TFLOPS, 4),
-                "traffic": traffic, "launches": lin_n, "avg_launch_ms": round(lin_ms / max(lin_n, 1), 4),
-                "flops_per_launch": round(flops_in / max(lin_n, 1), 1)}
-    gather_gbps = gather_bytes * 2 / (gather_ms * 1e-3) / 1e9 if gather_ms > 0 else 0.0
-    gather_roof = {"kernel": "k_gather", "bound": "hbm", "achieved": round(gather_gbps, 1), "peak": HBM_PEAK_GBPS,
-                   "unit": "GB/s", "frac": round(gather_gbps / HBM_PEAK_GBPS, 4),
-                   "avg_launch_ms": round(gather_ms / max(gather_n, 1), 4),
-                   "bytes_per_launch": round((gather_bytes * 2 + rows * 12) / max(gather_n, 1), 1)}
-
-    # ---- CPU oracle on this machine's host cores, bounded sample: the first batch of the workload
+    # ---- CPU oracle on this machine's host cores, bounded sample
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
         ip, ix, ft = indptr.numpy(), indices_host.numpy(), feat_host.numpy()
-        n_cpu = max(1, min(args.cpu_batches, nb))
+        # sized for about 10-30 s of CPU work: the forward pass dominates, ~2 s per batch on the large workloads
+        n_cpu = args.cpu_batches if args.cpu_batches is not None else (8 if w.name in ("tiny", "medium") else 4)
+        n_cpu = max(1, min(n_cpu, nb))
         t_s = t_g = t_f = 0.0
         e_cpu = rows_cpu = 0
         for b in range(n_cpu):
@@ -344,15 +431,32 @@ def main() -> int:
             if b == 0:
                 ob, ox, ol = ob_b, ox_b, ol_b
         cpu = {"value": round(e_cpu / (t_s + t_g + t_f), 1), "unit": "edges/s", "cores": 1, "kind": "oracle",
-               "sample": f"batches 0..{n_cpu - 1} of '{w.name}' ({e_cpu} edges, {rows_cpu} input rows): "
+               "sample": f"batches 0..{n_cpu - 1} of '{w.name}' ({e_cpu} edges, {rows_cpu} input rows) on one thread: "
                          f"sample {t_s:.2f}s, gather {t_g:.2f}s, forward {t_f:.2f}s",
                "sample_edges_per_s": round(e_cpu / t_s, 1),
                "gather_GBps": round(rows_cpu * w.feat_dim * 4 / t_g / 1e9, 3)}
+        # second leg: one thread per core over independent batches (the sampler's RNG is counter-based)
+        threads = max(1, min(16, len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)))
+        n_all = min(nb, 2 * threads)
+        r = oracle.run_batches(ip, ix, ft, seeds_h, w.batch_size, 0, n_all, w.fanouts, w.rng_seed, model,
+                               None if model == 2 else ws_h, wn_h, b_h, n_threads=threads)
+        cpu_model = ""
+        try:
+            for line in open("/proc/cpuinfo"):
+                if line.startswith("model name"):
+                    cpu_model = line.split(":", 1)[1].strip()
+                    break
+        except OSError:
+            pass
+        cpu["all_cores"] = {"value": round(r["edges"] / r["wall_s"], 1), "unit": "edges/s", "cores": min(threads, r["batches"]),
+                            "cpu_model": cpu_model,
+                            "sample": f"batches 0..{r['batches'] - 1}, batch k on thread k mod {threads} ({r['edges']} edges): "
+                                      f"wall {r['wall_s']:.2f}s; thread-seconds sample {r['sample_s']:.2f}, gather "
+                                      f"{r['gather_s']:.2f}, forward {r['forward_s']:.2f}",
+                            "sample_edges_per_s": round(r["edges"] / (r["sample_s"] / min(threads, r["batches"])), 1),
+                            "gather_GBps": round(r["input_rows"] * w.feat_dim * 4 / (r["gather_s"] / min(threads, r["batches"])) / 1e9, 3)}
         # the same batch from the GPU, as a last parity check on the benchmarked configuration
-        dci.dci_sample_khop(ctx, g, cache, seeds[:w.batch_size], 0, w.fanouts, w.rng_seed, blk, None)
-        dci.dci_gather_features(ctx, g, cache, blk.nodes, blk.cap_nodes[-1], x, n_dev=blk.n_input_dev())
-        dci.dci_gnn_forward(ctx, blk, x, model, ws, wn, bs, logits)
-        ctx.sync()
+        run(0, 1, 1)
         nn = blk.n_nodes()
         ok_nodes = nn == [int(v) for v in ob.n_nodes] and bool(np.array_equal(blk.nodes[:nn[-1]].cpu().numpy(), ob.nodes))
         ok_src = all(np.array_equal(blk.blk_src[h][:blk.n_edges()[h]].cpu().numpy(), ob.blk_src[h]) for h in range(w.n_hops))
@@ -363,36 +467,32 @@ def main() -> int:
                          "max_logit_err": err, "logit_tol": tol, "ok": bool(ok_nodes and ok_src and ok_x and err <= tol)}
 
     adj_total = st["adj_edge_hits"] + st["adj_edge_misses"]
+    gather_ms = timing_all["gather"][0]
     out = {
-        "metric": "sampled edges/s through sample+gather+forward (gathered feature GB/s, hit rates in extras)",
-        "value": round(value, 1), "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(wall_s * 1e3 / args.steps, 4), "higher_is_better": True, "scaling": "weak",
+        "metric": "sampled edges/s through sample+gather+forward (gathered feature GB/s, fractions of the HBM / host-link "
+                  "rooflines and cache hit rates in extras)",
+        "value": round(value, 1), "unit": "edges/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": round(wall_s * 1e3 / K, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "nodes": w.num_nodes, "edges": w.num_edges, "feat_dim": w.feat_dim,
                    "fanouts_from_seeds": list(w.fanouts), "batch_size": w.batch_size, "sage_dims": list(w.dims), "gnn": args.model,
                    "budget_bytes": 0 if args.no_cache else w.budget_bytes, "feat_policy": args.feat_policy,
                    "n_presample": w.n_presample, "single_cache": bool(args.single_cache),
-                   "adj_elements": bool(args.adj_elements),
-                   "cache": not args.no_cache, "streams": max(1, args.streams),
-                   "placement": place,
-                   "features": "hbm" if feat_in_hbm else "pinned host",
-                   "indices": "hbm" if place == "indices-hbm" else "pinned host", "indptr": "pinned host"},
+                   "adj_elements": bool(args.adj_elements), "cache": not args.no_cache, "streams": 1,
+                   "placement": place, "features": "hbm" if feat_in_hbm else "pinned host",
+                   "indices": "hbm (stand-in for the host tier: a box pins at most 64 GiB)" if place == "indices-hbm" else "pinned host",
+                   "indptr": "pinned host"},
         "extras": {
-            "edges_per_step": round(edges / args.steps, 1), "input_nodes_per_step": round(rows / args.steps, 1),
-            "gather_GBps_delivered": round(gather_bytes / (gather_ms * 1e-3) / 1e9, 1) if gather_ms > 0 else None,
+            "edges_per_step": round(edges / K, 1), "input_nodes_per_step": round(rows / K, 1),
+            "gather_GBps_delivered": round(n_in_total * 4 * F / (gather_ms * 1e-3) / 1e9, 1) if gather_ms > 0 else None,
             "adj_hit_rate_edges": round(st["adj_edge_hits"] / adj_total, 4) if adj_total else None,
             "adj_hit_rate_nodes": round(st["adj_node_hits"] / max(1, st["adj_node_hits"] + st["adj_node_misses"]), 4),
             "feat_hit_rate": round(st["feat_hits"] / rows, 4) if rows else None,
-            "gpu_event_ms_per_step": round(ev[0].elapsed_time(ev[1]) / args.steps, 4),
-            "kernel_ms_per_step": {k: round(v[0] / args.steps, 4) for k, v in timing.items() if v[1]},
-            "preprocess": pre,
-            # pre-sampling + fill + one pass over all of the workload's batches at the measured step time
-            "end_to_end_s": (round(pre["presample_s"] + pre["fill_s"] + wall_s / args.steps * nb, 4) if pre else
-                             round(wall_s / args.steps * nb, 4)),
-            "gather_roofline": gather_roof, "multi_stream": multi,
-            "host_link_pinned_copy_GBps": round(host_link_gbps, 1),
-            "gather_frac_of_host_link": (round(gather_bytes / (gather_ms * 1e-3) / 1e9 / host_link_gbps, 3)
-                                         if (gather_ms > 0 and st["feat_hits"] == 0) else None),
+            "bytes_from_caches_per_step": round(st["bytes_hbm"] / K), "bytes_from_graph_arrays_per_step": round(st["bytes_host"] / K),
+            "gpu_event_ms_per_step": round(ev[0].elapsed_time(ev[1]) / K, 4),
+            "kernel_pass_ms_per_step": {k: round(v[0] / K, 4) for k, v in timing_all.items() if v[1] and "+" not in k},
+            "rooflines": rooflines, "memory_rates": rates,
+            "preprocess": pre, "pipelined": pipelined, "end_to_end": e2e,
         },
         "roofline": roofline, "cpu_baseline": cpu,
     }

@@ -131,9 +131,11 @@ enum {
                                   list bounds), 8 per edge read from the adjacency cache, 4F per row read
                                   from the feature cache                                              */
   DCI_STAT_BYTES_HOST = 11,    /* the same quantities for what the graph arrays served (the miss path) */
-  DCI_STAT_HOST_LINES = 12,    /* sampling: distinct 128-byte lines of graph->indptr / graph->indices
-                                  touched per frontier node, summed; the unit in which a host link
-                                  charges small reads                                                  */
+  DCI_STAT_LINES_BOUNDS = 12,  /* sampling misses: 128-byte lines of graph->indptr that the list bounds of
+                                  the missed frontier nodes lie in (one or two per node), summed        */
+  DCI_STAT_LINES_IDS = 13,     /* sampling misses: distinct 128-byte lines of graph->indices read per
+                                  frontier node, summed.  A host link charges a small read a whole
+                                  request, so lines - not bytes - are what the miss path costs          */
   DCI_STATS_WORDS = 16
 };
 

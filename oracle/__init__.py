@@ -25,7 +25,7 @@ _P = c.c_void_p
 
 def build(force: bool = False) -> str:
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.run(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-o", _LIB, _SRC], check=True)
+        subprocess.run(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-pthread", "-o", _LIB, _SRC], check=True)
     return _LIB
 
 
@@ -69,6 +69,9 @@ def _load():
         lib.oracle_sage_forward.restype = None
         lib.oracle_gnn_forward.argtypes = [c.c_int32, c.c_int32, _P, _P, _P, _P, _P, _P, _P, _P, _P]
         lib.oracle_gnn_forward.restype = None
+        lib.oracle_run_batches.argtypes = [_P, _P, _P, c.c_int32, _P, c.c_int64, c.c_int32, c.c_int64, c.c_int64, _P,
+                                           c.c_int32, c.c_uint64, c.c_int32, _P, _P, _P, _P, c.c_int32, _P]
+        lib.oracle_run_batches.restype = c.c_int32
         _lib = lib
     return _lib
 
@@ -309,3 +312,29 @@ def gnn_forward(model: int, blocks: Blocks, x_in, w_self, w_neigh, bias) -> np.n
     lib.oracle_gnn_forward(model, L, nn.ctypes.data, _ptr_array(bi), _ptr_array(bs), x_in.ctypes.data,
                            dims.ctypes.data, _ptr_array(ws), _ptr_array(wn), _ptr_array(bb), out.ctypes.data)
     return out
+
+
+def run_batches(indptr, indices, feat, seeds, batch_size: int, first_batch: int, n_batches: int,
+                fanouts: Sequence[int], rng_seed: int, model: int, w_self, w_neigh, bias, n_threads: int = 1) -> dict:
+    """Whole batches (sample -> gather -> forward) on ``n_threads`` host threads, batch k of the range on thread
+    k mod n_threads; returns wall seconds, per-stage seconds summed over the threads, and totals."""
+    lib = _load()
+    indptr, indices, seeds = _i64(indptr), _i64(indices), _i64(seeds)
+    feat = np.ascontiguousarray(feat, dtype=np.float32)
+    if w_self is None:
+        w_self = w_neigh
+    L = len(w_neigh)
+    assert L == len(fanouts)
+    dims = _i32([w_neigh[0].shape[0]] + [w.shape[1] for w in w_neigh])
+    ws = [np.ascontiguousarray(w, dtype=np.float32) for w in w_self]
+    wn = [np.ascontiguousarray(w, dtype=np.float32) for w in w_neigh]
+    bb = [np.ascontiguousarray(b, dtype=np.float32) for b in bias]
+    out = np.zeros(8, dtype=np.float64)
+    rc = lib.oracle_run_batches(indptr.ctypes.data, indices.ctypes.data, feat.ctypes.data, int(feat.shape[1]),
+                                seeds.ctypes.data, len(seeds), batch_size, first_batch, n_batches,
+                                _i32(fanouts).ctypes.data, L, rng_seed, model, dims.ctypes.data, _ptr_array(ws),
+                                _ptr_array(wn), _ptr_array(bb), n_threads, out.ctypes.data)
+    if rc != 0:
+        raise ValueError("oracle_run_batches: bad arguments")
+    return dict(wall_s=float(out[0]), sample_s=float(out[1]), gather_s=float(out[2]), forward_s=float(out[3]),
+                edges=int(out[4]), input_rows=int(out[5]), batches=int(out[6]), logit_sum=float(out[7]), threads=n_threads)

@@ -30,9 +30,11 @@
 // numeric hit rates, for which the paper prints no table.
 
 #include <algorithm>
+#include <chrono>
 #include <cstdint>
 #include <cstring>
 #include <numeric>
+#include <thread>
 #include <unordered_map>
 #include <vector>
 
@@ -511,6 +513,69 @@ void oracle_sage_forward(int32_t n_layers, const int64_t* n_nodes, const int64_t
                          const float* const* w_self, const float* const* w_neigh, const float* const* bias,
                          double* logits) {
   oracle_gnn_forward(0, n_layers, n_nodes, blk_indptr, blk_src, x_in, dims, w_self, w_neigh, bias, logits);
+}
+
+// Whole batches on several host threads, for the benchmark's "oracle on all host cores" figure.
+// Batch k of the range [first_batch, first_batch + n_batches) is run - sample, gather, forward, with
+// exactly the functions above - by thread k mod n_threads.  Batches are independent units (Section V-B
+// sums the three stages over the test batches) and the sampler's random numbers are a pure function of
+// (seed, batch, hop, node, slot), so the order and the number of threads change nothing in any result.
+// out[0] wall seconds, out[1..3] seconds spent sampling / gathering / in the forward pass summed over
+// the threads, out[4] sampled edges, out[5] input rows, out[6] batches run, out[7] sum of all logits (so
+// that no stage can be optimised away; also a cheap cross-check between thread counts).
+int32_t oracle_run_batches(const int64_t* indptr, const int64_t* indices, const float* feat, int32_t F,
+                           const int64_t* seeds, int64_t n_seeds, int32_t batch_size, int64_t first_batch,
+                           int64_t n_batches, const int32_t* fanouts, int32_t n_hops, uint64_t rng_seed,
+                           int32_t model, const int32_t* dims, const float* const* w_self,
+                           const float* const* w_neigh, const float* const* bias, int32_t n_threads,
+                           double* out) {
+  if (n_threads < 1 || batch_size < 1 || n_batches < 0 || first_batch < 0 || n_hops < 1) return -1;
+  typedef std::chrono::steady_clock clock;
+  auto seconds = [](clock::time_point a, clock::time_point b) { return std::chrono::duration<double>(b - a).count(); };
+  std::vector<std::vector<double>> acc((size_t)n_threads, std::vector<double>(8, 0.0));
+  auto worker = [&](int32_t t) {
+    std::vector<double>& a = acc[(size_t)t];
+    for (int64_t k = t; k < n_batches; k += n_threads) {
+      const int64_t b = first_batch + k;
+      const int64_t lo = b * batch_size;
+      if (lo >= n_seeds) break;
+      const int64_t n = std::min<int64_t>(batch_size, n_seeds - lo);
+      const auto t0 = clock::now();
+      Batch blk;
+      sample_batch(indptr, indices, seeds + lo, n, (uint64_t)b, fanouts, n_hops, rng_seed, &blk);
+      const auto t1 = clock::now();
+      std::vector<float> x(blk.nodes.size() * (size_t)F);
+      oracle_gather(feat, F, blk.nodes.data(), (int64_t)blk.nodes.size(), x.data());
+      const auto t2 = clock::now();
+      std::vector<const int64_t*> bi((size_t)n_hops);
+      std::vector<const int32_t*> bs((size_t)n_hops);
+      for (int32_t h = 0; h < n_hops; ++h) {
+        bi[(size_t)h] = blk.blk_indptr[(size_t)h].data();
+        bs[(size_t)h] = blk.blk_src[(size_t)h].data();
+        a[4] += (double)blk.blk_src[(size_t)h].size();
+      }
+      std::vector<double> logits((size_t)(n * dims[n_hops]));
+      oracle_gnn_forward(model, n_hops, blk.n_nodes.data(), bi.data(), bs.data(), x.data(), dims, w_self, w_neigh, bias,
+                         logits.data());
+      const auto t3 = clock::now();
+      a[1] += seconds(t0, t1);
+      a[2] += seconds(t1, t2);
+      a[3] += seconds(t2, t3);
+      a[5] += (double)blk.nodes.size();
+      a[6] += 1.0;
+      for (double v : logits) a[7] += v;
+    }
+  };
+  const auto w0 = clock::now();
+  std::vector<std::thread> pool;
+  for (int32_t t = 1; t < n_threads; ++t) pool.emplace_back(worker, t);
+  worker(0);
+  for (auto& th : pool) th.join();
+  for (int i = 0; i < 8; ++i) out[i] = 0.0;
+  out[0] = seconds(w0, clock::now());
+  for (int32_t t = 0; t < n_threads; ++t)
+    for (int i = 1; i < 8; ++i) out[i] += acc[(size_t)t][(size_t)i];
+  return 0;
 }
 
 }  // extern "C"

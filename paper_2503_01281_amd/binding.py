@@ -15,7 +15,7 @@ DCI_MAX_HOPS = 8
 STATS_WORDS = 16
 STAT = dict(edges_sampled=0, adj_node_hits=1, adj_node_misses=2, adj_edge_hits=3, adj_edge_misses=4,
             feat_hits=5, feat_misses=6, input_nodes=7, t_sample_ns=8, t_feature_ns=9, bytes_hbm=10, bytes_host=11,
-            host_lines=12)
+            lines_bounds=12, lines_ids=13)
 
 KERNEL_CLASSES = ["table_clear", "sample", "relabel", "write_src", "gather", "mean_in", "linear_in", "mean", "linear",
                   "count_nodes"]

@@ -33,14 +33,16 @@ constexpr unsigned int kTentative = 0x80000000u;
 constexpr HashEntry kEmptyEntry = ~0ull;
 constexpr int kBlock = 256;
 // row_cnt[i]: bits 0..7 sampled edges of row i; bits 8..15 how many of them were read from the host although
-// the node has a cache slot (only the node cached in part has any); bits 16..22 the 128-byte lines of host
-// memory the row touched (list bounds and neighbour ids; only counted when statistics are on); bit 30 set if
-// the node has a slot
+// the node has a cache slot (only the node cached in part has any); bits 16..22 the distinct 128-byte lines
+// of graph->indices the row read, bits 23..24 those of graph->indptr (both only counted when statistics are
+// on); bit 30 set if the node has a slot
 constexpr int kRowHitBit = 1 << 30;
 constexpr int kRowCntMask = 0xFF;
 constexpr int kRowHostShift = 8;
 constexpr int kRowLinesShift = 16;
 constexpr int kRowLinesMask = 0x7F;
+constexpr int kRowBoundLinesShift = 23;
+constexpr int kRowBoundLinesMask = 0x3;
 constexpr int kHostLineLog2 = 7;  // the host link moves 128-byte lines: smaller reads cost a whole request each
 // Batch status word (in the region that the per-batch clear fills with ones): all ones = fine; anything
 // else = a relabel tile gave up waiting for its predecessors, the batch's outputs are void.
@@ -177,7 +179,7 @@ __device__ __forceinline__ void write_block_sources(long long n_rows, int fanout
 // Hit statistics of a batch: every relabel tile leaves (rows with a cache slot, edges read from the cache) in
 // its hop's array of partial sums; the closing kernel adds them up and updates the caller's counters with
 // one atomic each.  (Per-tile atomics on the same few words cost 12 us per batch on a 56 k-row frontier.)
-constexpr int kStatPartWords = 3;  // per relabel tile: rows with a slot, edges from the cache, host lines
+constexpr int kStatPartWords = 4;  // per relabel tile: rows with a slot, edges from the cache, lines of ids, lines of bounds
 struct StatFold {
   unsigned long long* stats;                    // nullptr: no statistics
   const unsigned long long* part[DCI_MAX_HOPS]; // [kStatPartWords * tiles] per hop
@@ -207,8 +209,8 @@ __global__ __launch_bounds__(kBlock) void k_write_src(const long long* counts, i
     counts_host[threadIdx.x] = counts[threadIdx.x];  // pinned host memory, visible once the stream is idle
   if (sf.stats && blockIdx.x == gridDim.x - 1) {
     __shared__ unsigned long long s_r[kBlock / kWave], s_e[kBlock / kWave];
-    __shared__ unsigned long long s_l[kBlock / kWave];
-    unsigned long long hr = 0, he = 0, hl = 0, rows = 0, edges = 0;
+    __shared__ unsigned long long s_l[kBlock / kWave], s_b[kBlock / kWave];
+    unsigned long long hr = 0, he = 0, hl = 0, hb = 0, rows = 0, edges = 0;
     for (int h = 0; h < sf.n_hops; ++h) {
       const long long n_rows = counts[h];
       const long long n_tiles = (n_rows + sf.tile_rows[h] - 1) / sf.tile_rows[h];
@@ -216,6 +218,7 @@ __global__ __launch_bounds__(kBlock) void k_write_src(const long long* counts, i
         hr += sf.part[h][kStatPartWords * t];
         he += sf.part[h][kStatPartWords * t + 1];
         hl += sf.part[h][kStatPartWords * t + 2];
+        hb += sf.part[h][kStatPartWords * t + 3];
       }
       rows += (unsigned long long)n_rows;
       edges += (unsigned long long)counts[DCI_MAX_HOPS + 1 + h];
@@ -223,20 +226,24 @@ __global__ __launch_bounds__(kBlock) void k_write_src(const long long* counts, i
     hr = wave_sum_u64(hr);
     he = wave_sum_u64(he);
     hl = wave_sum_u64(hl);
+    hb = wave_sum_u64(hb);
     if (lane_id() == 0) {
       s_r[threadIdx.x / kWave] = hr;
       s_e[threadIdx.x / kWave] = he;
       s_l[threadIdx.x / kWave] = hl;
+      s_b[threadIdx.x / kWave] = hb;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
       hr = 0;
       he = 0;
       hl = 0;
+      hb = 0;
       for (int w = 0; w < kBlock / kWave; ++w) {
         hr += s_r[w];
         he += s_e[w];
         hl += s_l[w];
+        hb += s_b[w];
       }
       if (edges) atomicAdd(&sf.stats[DCI_STAT_EDGES_SAMPLED], edges);
       if (hr) atomicAdd(&sf.stats[DCI_STAT_ADJ_NODE_HITS], hr);
@@ -248,7 +255,8 @@ __global__ __launch_bounds__(kBlock) void k_write_src(const long long* counts, i
       // charged to the tier that served them
       if (hr | he) atomicAdd(&sf.stats[DCI_STAT_BYTES_HBM], 16ull * hr + 8ull * he);
       if ((rows - hr) | (edges - he)) atomicAdd(&sf.stats[DCI_STAT_BYTES_HOST], 16ull * (rows - hr) + 8ull * (edges - he));
-      if (hl) atomicAdd(&sf.stats[DCI_STAT_HOST_LINES], hl);
+      if (hl) atomicAdd(&sf.stats[DCI_STAT_LINES_IDS], hl);
+      if (hb) atomicAdd(&sf.stats[DCI_STAT_LINES_BOUNDS], hb);
     }
   }
 }
@@ -332,10 +340,10 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
     const bool from_host = active && hit && pos >= cached_len;
     const int n_host = __popcll(group_bits<G>(__ballot(from_host), grp_in_wave));
     const long long* src = from_host ? a.indices + (a.indptr[v] + pos) : list + (start + pos);
-    int n_lines = 0;
+    int n_lines = 0, n_bound_lines = 0;
     if (a.count_lines) {
-      // Host-memory traffic of the row in the unit the host link moves (128-byte lines): the lines its
-      // pair of list bounds lies in plus the distinct lines of the neighbour ids it reads from the host.
+      // Miss-path traffic of the row in the unit a host link moves (128-byte lines): the distinct lines of
+      // the neighbour ids it reads from graph->indices, and the lines its list bounds in graph->indptr lie in.
       const bool host_read = active && (from_host || !hit);
       if (__ballot(host_read) != 0ull) {
         const unsigned long long line = (unsigned long long)reinterpret_cast<uintptr_t>(src) >> kHostLineLog2;
@@ -347,10 +355,10 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
         }
         n_lines = __popcll(group_bits<G>(__ballot(leader), grp_in_wave));
       }
-      if (row_ok && hit && n_host > 0) n_lines += 1;  // the partly cached node: where its host list starts
+      if (row_ok && hit && n_host > 0) n_bound_lines = 1;  // the partly cached node: where its host list starts
       if (row_ok && !hit) {
         const uintptr_t b0 = reinterpret_cast<uintptr_t>(a.indptr + v), b1 = reinterpret_cast<uintptr_t>(a.indptr + v + 1);
-        n_lines += (b0 >> kHostLineLog2) == (b1 >> kHostLineLog2) ? 1 : 2;
+        n_bound_lines = (b0 >> kHostLineLog2) == (b1 >> kHostLineLog2) ? 1 : 2;
       }
     }
     if (active) {
@@ -369,7 +377,8 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
     }
     if (row_ok && gl == 0) {
       // the hit flag rides in bit 30 so that the relabel kernel can total the hit statistics
-      a.row_cnt[i] = c | (n_host << kRowHostShift) | (n_lines << kRowLinesShift) | (hit ? kRowHitBit : 0);
+      a.row_cnt[i] = c | (n_host << kRowHostShift) | (n_lines << kRowLinesShift) |
+                     (n_bound_lines << kRowBoundLinesShift) | (hit ? kRowHitBit : 0);
       if (COUNT && c > 0) atomicAdd(&a.adj_count[v], (unsigned)c);
     }
   }
@@ -419,7 +428,7 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
   static_assert(TR <= kBlock, "one thread per tile row in the block scan");
   __shared__ int s_c[TR], s_f[TR];
   __shared__ int s_wc[kWaves], s_wf[kWaves];
-  __shared__ unsigned long long s_hr[kWaves], s_he[kWaves], s_hl[kWaves];
+  __shared__ unsigned long long s_hr[kWaves], s_he[kWaves], s_hl[kWaves], s_hb[kWaves];
   __shared__ unsigned s_tile;
   __shared__ long long s_ec;
   __shared__ int s_ef;
@@ -464,7 +473,7 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
 #pragma unroll
   for (int it = 0; it < kTileIters; ++it) val[it] = slot[it] >= 0 ? entry_val(a.table, (unsigned)slot[it]) : 0u;
   unsigned first_bits = 0;
-  unsigned long long hit_rows = 0, hit_edges = 0, host_lines = 0;
+  unsigned long long hit_rows = 0, hit_edges = 0, host_lines = 0, bound_lines = 0;
 #pragma unroll
   for (int it = 0; it < kTileIters; ++it) {
     const int r = it * kGroups + grp;
@@ -481,6 +490,7 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
         hit_edges += (unsigned)(c - ((raw[it] >> kRowHostShift) & 0xFF));
       }
       host_lines += (unsigned)((raw[it] >> kRowLinesShift) & kRowLinesMask);
+      bound_lines += (unsigned)((raw[it] >> kRowBoundLinesShift) & kRowBoundLinesMask);
     }
   }
   __syncthreads();
@@ -495,10 +505,12 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
   hit_rows = wave_sum_u64(hit_rows);
   hit_edges = wave_sum_u64(hit_edges);
   host_lines = wave_sum_u64(host_lines);
+  bound_lines = wave_sum_u64(bound_lines);
   if (lane == 0) {
     s_hr[wave] = hit_rows;
     s_he[wave] = hit_edges;
     s_hl[wave] = host_lines;
+    s_hb[wave] = bound_lines;
   }
   __syncthreads();
   int off_c = 0, off_f = 0, tot_c = 0, tot_f = 0;
@@ -605,15 +617,17 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
       a.counts[DCI_MAX_HOPS + 1 + a.hop] = ec + tot_c;
     }
     if (a.stat_part) {
-      unsigned long long hr = 0, he = 0, hl = 0;
+      unsigned long long hr = 0, he = 0, hl = 0, hb = 0;
       for (int w = 0; w < kWaves; ++w) {
         hr += s_hr[w];
         he += s_he[w];
         hl += s_hl[w];
+        hb += s_hb[w];
       }
       a.stat_part[kStatPartWords * (size_t)tile] = hr;      // added up by the batch's closing kernel
       a.stat_part[kStatPartWords * (size_t)tile + 1] = he;
       a.stat_part[kStatPartWords * (size_t)tile + 2] = hl;
+      a.stat_part[kStatPartWords * (size_t)tile + 3] = hb;
     }
   }
 }

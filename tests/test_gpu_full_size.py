@@ -123,6 +123,50 @@ def test_presample_fill_and_batches(big):
         del cache
 
 
+def test_batches_in_flight_full_size(big):
+    """dci_infer_batches at full size, the launch configuration of bench.py's pipelined region: six consecutive
+    batches on four lanes through partially filled caches (0.4 GB), every batch's logits against the oracle and the
+    blocks / gathered rows of the batch each lane ran last, bit for bit."""
+    e = big
+    dci, gu, w, ctx, g = e["dci"], e["gu"], e["w"], e["ctx"], e["g"]
+    fc = torch.zeros(w.num_nodes, dtype=torch.int32, device="cuda")
+    ac = torch.zeros(w.num_nodes, dtype=torch.int32, device="cuda")
+    seeds_dev = gu.dev(e["seeds"])
+    dci.dci_presample_count(ctx, g, None, seeds_dev, w.batch_size, 0, w.n_presample, w.presample_first_batch,
+                            w.fanouts, w.rng_seed, fc, ac)
+    cache = dci.dci_fill_caches(ctx, g, fc, ac, 400_000_000, 3, 7, 0)
+    assert 0 < cache.adj_nodes < w.num_nodes and 0 < cache.feat_rows < w.num_nodes
+    ws, wn, bs = ([gu.dev(a) for a in e[k]] for k in ("ws", "wn", "bs"))
+    lanes = [dci.Lane(g, w.batch_size, w.fanouts, w.dims) for _ in range(4)]
+    first, count = 2, 6
+    logits = torch.full((w.num_seeds, w.classes), float("nan"), dtype=torch.float32, device="cuda")
+    stats = gu.new_stats()
+    torch.cuda.synchronize()
+    dci.dci_infer_batches(lanes, g, cache, seeds_dev, w.batch_size, first, count, w.fanouts, w.rng_seed, 0, ws, wn, bs,
+                          logits, stats)
+    for ln in lanes:
+        ln.ctx.sync()
+    out = logits.cpu().numpy()
+    edges = 0
+    last_of_lane = {k: first + k + 4 * ((count - 1 - k) // 4) for k in range(4)}      # lane k ran first+k, first+k+4, ...
+    for b in range(first, first + count):
+        sl = slice(b * w.batch_size, (b + 1) * w.batch_size)
+        want = oracle.sample_khop(e["indptr"], e["indices"], e["seeds"][sl], b, w.fanouts, w.rng_seed)
+        want_x = oracle.gather(e["feat"], want.nodes)
+        ref = oracle.sage_forward(want, want_x, e["ws"], e["wn"], e["bs"])
+        err = float(np.abs(out[sl] - ref).max())
+        assert err <= 1e-4 * max(1.0, float(np.abs(ref).max())), (b, err)
+        edges += int(want.n_edges.sum())
+        for k, lb in last_of_lane.items():
+            if lb == b:
+                gu.assert_blocks_equal(gu.blocks_to_host(lanes[k].ctx, lanes[k].blocks), want)
+                assert lanes[k].x[:len(want.nodes)].cpu().numpy().tobytes() == want_x.tobytes()
+    assert np.isnan(out[:first * w.batch_size]).all() and np.isnan(out[(first + count) * w.batch_size:]).all()
+    st = gu.stats_dict(ctx, stats)
+    assert st["edges_sampled"] == edges and st["adj_edge_hits"] > 0 and st["adj_edge_misses"] > 0
+    assert st["feat_hits"] > 0 and st["feat_misses"] > 0
+
+
 def test_element_granular_cache_full_size(big):
     """Algorithm 1 as printed, at full size: second-level sort of every counted node's list (in the pinned host
     structure too), a last node cached in part, blocks bit for bit and hits counted per position.  The host lists

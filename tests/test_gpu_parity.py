@@ -666,11 +666,11 @@ def _host_lines(base_ptr, byte_offsets):
 
 
 def _expected_sampler_traffic(want, fanouts, indptr, adj_remap, indptr_base, indices_base):
-    """(bytes_hbm, bytes_host, host_lines) of sampling the batch `want` through a node-granular adjacency
+    """(bytes_hbm, bytes_host, lines_bounds, lines_ids) of sampling the batch `want` through a node-granular adjacency
     cache, from the oracle's blocks and sampled positions: 16 bytes of list bounds per frontier node and
     8 bytes per neighbour id, charged to the tier that serves the node; lines = per missed node, the lines
     of its two list bounds plus the distinct lines of the neighbour ids it reads."""
-    b_hbm = b_host = lines = 0
+    b_hbm = b_host = lines = blines = 0
     for h in range(len(fanouts)):
         frontier = want.nodes[:want.n_nodes[h]]
         hit = adj_remap[frontier] >= 0 if adj_remap is not None else np.zeros(len(frontier), dtype=bool)
@@ -680,11 +680,11 @@ def _expected_sampler_traffic(want, fanouts, indptr, adj_remap, indptr_base, ind
         b_host += 16 * int((~hit).sum()) + 8 * int(rows[~hit].sum())
         for i in np.flatnonzero(~hit):
             v = int(frontier[i])
-            lines += _host_lines(indptr_base, [8 * v, 8 * (v + 1)])
+            blines += _host_lines(indptr_base, [8 * v, 8 * (v + 1)])
             pos = want.src_pos[h][bi[i]:bi[i + 1]]
             if len(pos):
                 lines += _host_lines(indices_base, 8 * (int(indptr[v]) + pos))
-    return b_hbm, b_host, lines
+    return b_hbm, b_host, blines, lines
 
 
 @pytest.mark.parametrize("with_cache", [False, True])
@@ -705,8 +705,8 @@ def test_traffic_statistics_match_counts_derived_from_the_oracle(env, with_cache
         gu.assert_blocks_equal(gu.blocks_to_host(ctx, blk), want)
         exp = _expected_sampler_traffic(want, fan, tiny["indptr"], oc["adj_remap"] if oc else None,
                                         g.indptr.data_ptr(), g.indices.data_ptr())
-        assert (st["bytes_hbm"], st["bytes_host"], st["host_lines"]) == exp
-        assert exp[2] > 0 and (exp[0] > 0) == with_cache
+        assert (st["bytes_hbm"], st["bytes_host"], st["lines_bounds"], st["lines_ids"]) == exp
+        assert exp[2] > 0 and exp[3] > 0 and (exp[0] > 0) == with_cache
         # the gather adds one row of 4F bytes per input node to the tier that holds it
         n_in = int(want.n_nodes[-1])
         dci.dci_gather_features(ctx, g, cache, blk.nodes, n_in, x, stats=stats)
@@ -714,7 +714,7 @@ def test_traffic_statistics_match_counts_derived_from_the_oracle(env, with_cache
         hits = int((oc["feat_remap"][want.nodes] >= 0).sum()) if oc else 0
         assert st2["bytes_hbm"] - st["bytes_hbm"] == 4 * w.feat_dim * hits
         assert st2["bytes_host"] - st["bytes_host"] == 4 * w.feat_dim * (n_in - hits)
-        assert st2["host_lines"] == st["host_lines"]
+        assert (st2["lines_bounds"], st2["lines_ids"]) == (st["lines_bounds"], st["lines_ids"])
 
 
 def test_relabel_timeout_voids_the_batch_and_is_reported(env):

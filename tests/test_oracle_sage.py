@@ -121,3 +121,26 @@ def test_relu_between_layers_only():
     # layer 0 on block 1: y = 1*(-1) + 3*(-1) = -4 -> ReLU -> 0 ; layer 1 on block 0: 0*1 + 0 - 2 = -2 (kept)
     got = oracle.sage_forward(blk, x, [neg, one], [neg, zero], [b0, np.array([-2.0], dtype=np.float32)])
     assert got.tolist() == [[-2.0]]
+
+
+def test_run_batches_is_the_three_calls_per_batch_whatever_the_thread_count(tiny):
+    """The multi-thread driver used for the benchmark's all-cores figure adds no arithmetic of its own:
+    totals and the sum of all logits equal those of sample_khop -> gather -> gnn_forward called batch by
+    batch, for 1, 3 and 8 threads, including a ragged last batch and a range that runs past the end."""
+    w = tiny["w"]
+    B = 200                                            # 2,048 seeds -> 10 full batches and one of 48
+    edges = rows = 0
+    total = 0.0
+    for b in range(3, 11):
+        s = tiny["seeds"][b * B:(b + 1) * B]
+        blk = oracle.sample_khop(tiny["indptr"], tiny["indices"], s, b, w.fanouts, w.rng_seed)
+        x = oracle.gather(tiny["feat"], blk.nodes)
+        total += float(oracle.gnn_forward(1, blk, x, tiny["w_self"], tiny["w_neigh"], tiny["bias"]).sum())
+        edges += int(blk.n_edges.sum())
+        rows += len(blk.nodes)
+    for threads in (1, 3, 8):
+        r = oracle.run_batches(tiny["indptr"], tiny["indices"], tiny["feat"], tiny["seeds"], B, 3, 50, w.fanouts,
+                               w.rng_seed, 1, tiny["w_self"], tiny["w_neigh"], tiny["bias"], n_threads=threads)
+        assert (r["edges"], r["input_rows"], r["batches"]) == (edges, rows, 8)
+        assert abs(r["logit_sum"] - total) <= 1e-9 * max(1.0, abs(total))
+        assert r["wall_s"] > 0 and r["sample_s"] > 0 and r["forward_s"] > 0
