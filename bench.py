@@ -79,6 +79,9 @@ def main() -> int:
     ap.add_argument("--pipelined-linear-kernel", type=int, default=1, choices=[0, 1, 2, 3],
                     help="dense-layer kernel of the pipelined regions (the statically partitioned wide kernel loses "
                          "when other streams share the compute units)")
+    ap.add_argument("--fused-input", type=int, default=1, choices=[0, 1],
+                    help="1 (default): the input layer reads cached neighbour rows in place (dci_gather_forward: only "
+                         "missed rows and the rows of F_{L-1} are copied); 0: dci_gather_features then dci_gnn_forward")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batches", type=int, default=None, help="batches the single-thread CPU oracle is timed on")
     ap.add_argument("--lanes", type=int, default=4, help="batches in flight in the pipelined regions (0 or 1 = skip them)")
@@ -158,6 +161,8 @@ def main() -> int:
     ctx, blk, x = lanes[0].ctx, lanes[0].blocks, lanes[0].x
     nb = w.num_batches
     logits = torch.empty(w.num_seeds, w.classes, dtype=torch.float32, device="cuda")
+    for ln in lanes:
+        ln.ctx.set_option(dci.DCI_OPT_FUSED_INPUT, args.fused_input)
 
     # ---- one-off part: pre-sampling counts (timed per stage for Eq. (1)) and the dual-cache fill
     cache = None
@@ -314,9 +319,13 @@ def main() -> int:
     rooflines["relabel"] = entry("k_relabel_hop + k_write_src", "relabel+write_src", {"hbm": relabel_bytes / hbm_bw},
                                  {"hbm": relabel_bytes / GB}, {"hbm": HBM_PEAK_GBPS}, unit_hbm,
                                  bytes_per_step=round(relabel_bytes / K))
-    g_hbm = sk["feat_hits"] * (8 * F + 12) + sk["feat_misses"] * ((4 * F + 12) if feat.is_pinned() else (8 * F + 12))
+    # gather: 8F+12 B per row that is copied (4F of them over the link on a miss), 16 B (id, remap, slot note) per row
+    # that is left in the cache for the input layer to read in place
+    copied_hits = sk["rows_copied"] - sk["feat_misses"]
+    g_hbm = (copied_hits * (8 * F + 12) + sk["feat_misses"] * ((4 * F + 12) if feat.is_pinned() else (8 * F + 12))
+             + (sk["feat_hits"] - copied_hits) * 16)
     g_link = sk["feat_misses"] * 4 * F if feat.is_pinned() else 0
-    rooflines["gather"] = entry("k_gather", "gather",
+    rooflines["gather"] = entry("k_gather" + (" (misses and F_{L-1} rows only)" if args.fused_input else ""), "gather",
                                 {"hbm": g_hbm / hbm_bw, "host_link_bytes": g_link / row_link_rate if row_link_rate else 0.0},
                                 {"hbm": g_hbm / GB, "host_link_bytes": g_link / GB},
                                 {"hbm": HBM_PEAK_GBPS, "host_link_bytes": row_link_rate / GB}, unit_hbm,
@@ -325,7 +334,7 @@ def main() -> int:
     for l in range(L):
         h = L - 1 - l
         cls_m, cls_l = ("mean_in", "linear_in") if l == 0 else ("mean", "linear")
-        mb = 4 * w.dims[l] * (int(hop_edges[h]) + int(hop_nodes[h]))
+        mb = 4 * w.dims[l] * (int(hop_edges[h]) + int(hop_nodes[h])) + (4 * int(hop_edges[h]) if l == 0 and args.fused_input else 0)
         if l <= 1:
             if l == 1 and L > 2:       # the later layers share one class: add them up
                 mb = sum(4 * w.dims[j] * (int(hop_edges[L - 1 - j]) + int(hop_nodes[L - 1 - j])) for j in range(1, L))
@@ -335,6 +344,19 @@ def main() -> int:
             rooflines[cls_l] = entry("dense layer (fp32 MFMA)", cls_l, {"mfma": fl / (FP32_MFMA_PEAK_TFLOPS * 1e12)},
                                      {"mfma": fl / 1e12}, {"mfma": FP32_MFMA_PEAK_TFLOPS}, unit_hbm,
                                      flops_per_step=round(fl / K))
+    if args.fused_input:
+        # the pair against what the two separate steps are defined to move: every input row gathered (8F+12 B on a
+        # hit) and every edge's row read once more for the aggregate
+        full = (sk["feat_hits"] * (8 * F + 12) + sk["feat_misses"] * ((4 * F + 12) if feat.is_pinned() else (8 * F + 12))
+                + 4 * F * (int(hop_edges[L - 1]) + int(hop_nodes[L - 1])))
+        timing_all["gather+mean_in"] = (timing_all["gather"][0] + timing_all["mean_in"][0],
+                                        timing_all["gather"][1] + timing_all["mean_in"][1])
+        rooflines["gather+mean_in"] = entry("k_gather + k_sage_mean (input layer, cached rows read in place)", "gather+mean_in",
+                                            {"hbm": full / hbm_bw, "host_link_bytes": g_link / row_link_rate if row_link_rate else 0.0},
+                                            {"hbm": full / GB, "host_link_bytes": g_link / GB},
+                                            {"hbm": HBM_PEAK_GBPS, "host_link_bytes": row_link_rate / GB}, unit_hbm,
+                                            note="bytes of the unfused definition (gather every row, then aggregate) over the "
+                                                 "time of the fused pair")
     avg_launch = {c: (timing_all[c][0] / timing_all[c][1]) for c in dci.KERNEL_CLASSES if timing_all[c][1]}
     dominant = args.roofline_kernel if args.roofline_kernel != "auto" else max(avg_launch, key=avg_launch.get)
     roof_key = {"write_src": "relabel"}.get(dominant, dominant)
@@ -464,6 +486,8 @@ def main() -> int:
         nn = blk.n_nodes()
         ok_nodes = nn == [int(v) for v in ob.n_nodes] and bool(np.array_equal(blk.nodes[:nn[-1]].cpu().numpy(), ob.nodes))
         ok_src = all(np.array_equal(blk.blk_src[h][:blk.n_edges()[h]].cpu().numpy(), ob.blk_src[h]) for h in range(w.n_hops))
+        dci.dci_gather_features(ctx, g, cache, blk.nodes, blk.cap_nodes[-1], x, n_dev=blk.n_input_dev())
+        ctx.sync()
         ok_x = x[:nn[-1]].cpu().numpy().tobytes() == ox.tobytes()
         err = float(np.abs(logits[:w.batch_size].cpu().numpy() - ol).max())
         tol = 1e-4 * max(1.0, float(np.abs(ol).max()))
@@ -483,6 +507,7 @@ def main() -> int:
                    "budget_bytes": 0 if args.no_cache else w.budget_bytes, "feat_policy": args.feat_policy,
                    "n_presample": w.n_presample, "single_cache": bool(args.single_cache),
                    "adj_elements": bool(args.adj_elements), "cache": not args.no_cache, "streams": 1,
+                   "fused_input": bool(args.fused_input),
                    "placement": place, "features": "hbm" if feat_in_hbm else "pinned host",
                    "indices": "hbm (stand-in for the host tier: a box pins at most 64 GiB)" if place == "indices-hbm" else "pinned host",
                    "indptr": "pinned host"},
@@ -495,6 +520,7 @@ def main() -> int:
             "bytes_from_caches_per_step": round(st["bytes_hbm"] / K), "bytes_from_graph_arrays_per_step": round(st["bytes_host"] / K),
             "gpu_event_ms_per_step": round(ev[0].elapsed_time(ev[1]) / K, 4),
             "kernel_pass_ms_per_step": {k: round(v[0] / K, 4) for k, v in timing_all.items() if v[1] and "+" not in k},
+            "rows_copied_by_gather_per_step": round(sk["rows_copied"] / K, 1),
             "rooflines": rooflines, "memory_rates": rates,
             "preprocess": pre, "pipelined": pipelined, "end_to_end": e2e,
         },

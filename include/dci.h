@@ -136,6 +136,8 @@ enum {
   DCI_STAT_LINES_IDS = 13,     /* sampling misses: distinct 128-byte lines of graph->indices read per
                                   frontier node, summed.  A host link charges a small read a whole
                                   request, so lines - not bytes - are what the miss path costs          */
+  DCI_STAT_ROWS_COPIED = 14,   /* rows the gather wrote to its output: all of them for dci_gather_features,
+                                  the misses and the rows of F_{L-1} for dci_gather_forward             */
   DCI_STATS_WORDS = 16
 };
 
@@ -182,6 +184,11 @@ const char* dci_last_error(const dci_ctx* ctx);
  *       give up.  Only accepted while the spin limit is at most 65536, so that every kernel still ends
  *       within microseconds. */
 #define DCI_OPT_TEST_RELABEL_FIRST_TICKET 4
+/*   DCI_OPT_FUSED_INPUT  how dci_infer_batches feeds the model on this context's lane: 0 (default)
+ *       dci_gather_features then dci_gnn_forward, so that the lane's x holds every gathered row;
+ *       1 dci_gather_forward (cached neighbour rows are read in place; x holds only the rows that
+ *       missed and those of F_{L-1}).  The logits are the same up to nothing: the sums run in the same order. */
+#define DCI_OPT_FUSED_INPUT 5
 int32_t dci_set_option(dci_ctx* ctx, int32_t option, int64_t value);
 
 /* Kernel timing, for benchmarks and profiles.  Kernel classes whose bit is set in class_mask are
@@ -364,6 +371,25 @@ int32_t dci_gnn_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_i
                         const int32_t* dims, int32_t model, const float* const* w_self,
                         const float* const* w_neigh, const float* const* bias, float* logits);
 
+/* Feature gather and forward pass in one call, for the case that the gathered rows are wanted only
+ * as the model's input (Section IV, framework paragraph: rows come from GPU memory on a hit, from
+ * host memory on a miss; Section V-B: loading features is the stage the feature cache shortens).
+ * The logits are those of dci_gather_features(blocks->nodes) followed by dci_gnn_forward, but rows
+ * that sit in the feature cache and are needed only as neighbours of the input layer are not copied:
+ * the input layer's aggregation reads them where they are.  Copied into x (device
+ * [blocks->cap_nodes, F], scratch) are the rows that miss - each crosses the host link once, however
+ * many edges use it - and the rows of F_{L-1}, which the input layer's dense product reads as a
+ * matrix; the other rows of x are left as they were.  dims[0] must equal graph->feat_dim.  The
+ * workspace must hold dci_gather_forward_workspace_bytes(blocks->cap_nodes, blocks->cap_rows,
+ * n_layers, dims) bytes.  stats (nullable): DCI_STAT_FEAT_HITS / _MISSES and the byte counters as
+ * dci_gather_features would count them (once per input node). */
+size_t dci_gather_forward_workspace_bytes(int64_t cap_nodes, const int64_t* cap_rows, int32_t n_layers,
+                                          const int32_t* dims);
+int32_t dci_gather_forward(dci_ctx* ctx, const dci_graph* graph, const dci_cache* cache,
+                           const dci_blocks* blocks, float* x, int32_t n_layers, const int32_t* dims,
+                           int32_t model, const float* const* w_self, const float* const* w_neigh,
+                           const float* const* bias, float* logits, uint64_t* stats);
+
 /* ---- inference over many batches, several in flight ----------------------------------------- */
 
 /* Inference over the batches [first_batch, first_batch + n_batches) of the seed list (Section V-B: a
@@ -372,8 +398,8 @@ int32_t dci_gnn_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_i
  * (b+1)*batch_size)), uses RNG batch index b and goes, whole, through dci_sample_khop ->
  * dci_gather_features -> dci_gnn_forward on lane (b - first_batch) mod n_lanes; its logits land in
  * rows b*batch_size .. of `logits` (device [n_seeds, dims[n_hops]]).  A lane is a context - its own
- * stream, and a workspace that covers both dci_sample_workspace_bytes and dci_sage_workspace_bytes
- * for these sizes - with its own batch buffers (blocks sized by dci_blocks_bounds for batch_size
+ * stream, and a workspace that covers dci_sample_workspace_bytes and dci_sage_workspace_bytes (with
+ * DCI_OPT_FUSED_INPUT: dci_gather_forward_workspace_bytes) for these sizes - with its own batch buffers (blocks sized by dci_blocks_bounds for batch_size
  * seeds; x: device [blocks->cap_nodes, F]).  Batches on different lanes run concurrently, so the
  * sampling of one batch overlaps the feature loading and the model computation of others; the
  * graph, the cache, the weights and the seeds are shared and only read; `stats` (nullable) is

@@ -15,7 +15,7 @@ DCI_MAX_HOPS = 8
 STATS_WORDS = 16
 STAT = dict(edges_sampled=0, adj_node_hits=1, adj_node_misses=2, adj_edge_hits=3, adj_edge_misses=4,
             feat_hits=5, feat_misses=6, input_nodes=7, t_sample_ns=8, t_feature_ns=9, bytes_hbm=10, bytes_host=11,
-            lines_bounds=12, lines_ids=13)
+            lines_bounds=12, lines_ids=13, rows_copied=14)
 
 KERNEL_CLASSES = ["table_clear", "sample", "relabel", "write_src", "gather", "mean_in", "linear_in", "mean", "linear",
                   "count_nodes"]
@@ -94,6 +94,10 @@ def load_library():
     lib.dci_gather_features.argtypes = [P, P, P, P, i64, P, P, P]
     lib.dci_sage_forward.argtypes = [P, P, P, i32, P, P, P, P, P]
     lib.dci_gnn_forward.argtypes = [P, P, P, i32, P, i32, P, P, P, P]
+    lib.dci_gather_forward.argtypes = [P, P, P, P, P, i32, P, i32, P, P, P, P, P]
+    lib.dci_gather_forward.restype = i32
+    lib.dci_gather_forward_workspace_bytes.argtypes = [i64, P, i32, P]
+    lib.dci_gather_forward_workspace_bytes.restype = sz
     lib.dci_infer_batches.argtypes = [P, i32, P, P, P, i64, i32, i64, i64, P, i32, u64, i32, P, P, P, P, P, P]
     lib.dci_infer_batches.restype = i32
     lib.dci_probe_read.argtypes = [P, P, u64, i32, i32, i64, i32, u64, P, P]
@@ -417,6 +421,7 @@ DCI_OPT_LINEAR_KERNEL = 1
 DCI_OPT_LINEAR_SPLIT = 2
 DCI_OPT_RELABEL_SPIN_LIMIT = 3
 DCI_OPT_TEST_RELABEL_FIRST_TICKET = 4
+DCI_OPT_FUSED_INPUT = 5
 
 
 def dci_sage_forward(ctx: Context, blocks: Blocks, x_in: torch.Tensor, w_self: Sequence[torch.Tensor],
@@ -444,6 +449,23 @@ def dci_gnn_forward(ctx: Context, blocks: Blocks, x_in: torch.Tensor, model: int
                                           arr(w_self), arr(w_neigh), arr(bias), _ptr(logits)))
 
 
+def dci_gather_forward(ctx: Context, graph: Graph, cache: Optional[Cache], blocks: Blocks, x: torch.Tensor, model: int,
+                       w_self: Optional[Sequence[torch.Tensor]], w_neigh: Sequence[torch.Tensor],
+                       bias: Sequence[torch.Tensor], logits: torch.Tensor, stats: Optional[torch.Tensor] = None):
+    """Gather + forward with cached neighbour rows of the input layer read in place; ``x`` is scratch [cap_nodes, F]."""
+    L = len(w_neigh)
+    dims = [int(w_neigh[0].shape[0])] + [int(w.shape[1]) for w in w_neigh]
+    for t in list(w_self or []) + list(w_neigh) + list(bias) + [x, logits]:
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+    assert x.numel() >= blocks.cap_nodes[L] * graph.feat_dim and logits.numel() >= blocks.cap_nodes[0] * dims[L]
+    cap_rows = (C.c_int64 * DCI_MAX_HOPS)(*([blocks.cap_nodes[h] for h in range(L)] + [0] * (DCI_MAX_HOPS - L)))
+    ctx.ensure_workspace(ctx.lib.dci_gather_forward_workspace_bytes(blocks.cap_nodes[L], cap_rows, L, _i32_array(dims)))
+    arr = lambda ts: None if ts is None else (C.c_void_p * L)(*[t.data_ptr() for t in ts])
+    ctx.check(ctx.lib.dci_gather_forward(ctx.handle, C.byref(graph.c), None if cache is None else C.byref(cache.c),
+                                         C.byref(blocks.c), _ptr(x), L, _i32_array(dims), int(model), arr(w_self),
+                                         arr(w_neigh), arr(bias), _ptr(logits), _ptr(stats)))
+
+
 class Lane:
     """One lane of dci_infer_batches: a context on its own stream with its own batch buffers."""
 
@@ -457,7 +479,7 @@ class Lane:
         lib = self.ctx.lib
         cap_rows = (C.c_int64 * DCI_MAX_HOPS)(*([self.blocks.cap_nodes[h] for h in range(L)] + [0] * (DCI_MAX_HOPS - L)))
         need = max(lib.dci_sample_workspace_bytes(graph.num_nodes, batch_size, _i32_array(fanouts), L),
-                   lib.dci_sage_workspace_bytes(cap_rows, L, _i32_array(dims)), 1 << 20)
+                   lib.dci_gather_forward_workspace_bytes(self.blocks.cap_nodes[L], cap_rows, L, _i32_array(dims)), 1 << 20)
         self.ctx.ensure_workspace(need)
 
 

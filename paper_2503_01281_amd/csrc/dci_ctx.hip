@@ -185,6 +185,11 @@ int32_t dci_set_option(dci_ctx* ctx, int32_t option, int64_t value) {
     ctx->linear_split = (int)value;
     return DCI_OK;
   }
+  if (option == DCI_OPT_FUSED_INPUT) {
+    if (value != 0 && value != 1) return dci::fail(ctx, DCI_ERR_INVALID_ARG, "DCI_OPT_FUSED_INPUT takes 0 or 1, not %lld", (long long)value);
+    ctx->fused_input = (int)value;
+    return DCI_OK;
+  }
   if (option == DCI_OPT_RELABEL_SPIN_LIMIT) {
     if (value < 1 || value > (int64_t)0xFFFFFFFFll)
       return dci::fail(ctx, DCI_ERR_INVALID_ARG, "DCI_OPT_RELABEL_SPIN_LIMIT takes 1 .. 2^32-1, not %lld", (long long)value);

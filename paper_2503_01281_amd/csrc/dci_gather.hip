@@ -27,16 +27,18 @@ struct GVec<2> { typedef float2 reg; typedef float2_u mem; };
 template <>
 struct GVec<1> { typedef float reg; typedef float mem; };
 
+struct GatherCounts {
+  unsigned long long hits = 0, misses = 0, copied = 0;
+};
+
+// Copies rows [0, n) of the id list: a group of 2^lpr_log2 lanes per row, workgroup `block` of `n_blocks`
+// taking every n_blocks-th slice of rows.  rowref (nullable) receives every row's cache slot or -1.
 template <int V>
-__global__ __launch_bounds__(kGatherBlock) void k_gather(const long long* __restrict__ ids, long long n_max,
-                                                         const long long* __restrict__ n_dev,
-                                                         const int* __restrict__ remap,
-                                                         const float* __restrict__ cache,
-                                                         const float* __restrict__ feat, int F, int lpr_log2,
-                                                         float* __restrict__ out,
-                                                         unsigned long long* __restrict__ partials) {
-  long long n = n_dev ? *n_dev : n_max;
-  if (n > n_max) n = n_max;
+__device__ __forceinline__ void copy_rows(const long long* __restrict__ ids, long long n,
+                                          const int* __restrict__ remap, const float* __restrict__ cache,
+                                          const float* __restrict__ feat, int F, int lpr_log2,
+                                          float* __restrict__ out, int* __restrict__ rowref, int block, int n_blocks,
+                                          GatherCounts& cnt) {
   typedef typename GVec<V>::reg reg_t;
   typedef typename GVec<V>::mem mem_t;
   const int chunks = F / V, tail = F % V;
@@ -44,10 +46,9 @@ __global__ __launch_bounds__(kGatherBlock) void k_gather(const long long* __rest
   const int rows_per_block = kGatherBlock >> lpr_log2;
   const int sub = (int)threadIdx.x >> lpr_log2;  // row within the block's slice
   const int cl = (int)threadIdx.x & (lpr - 1);   // first chunk of this lane
-  const long long stride = (long long)gridDim.x * rows_per_block;
-  unsigned long long hits = 0, misses = 0;
+  const long long stride = (long long)n_blocks * rows_per_block;
 
-  long long i = (long long)blockIdx.x * rows_per_block + sub;
+  long long i = (long long)block * rows_per_block + sub;
   long long id = i < n ? ids[i] : 0;
   int r = (i < n && remap) ? remap[id] : -1;
   long long i2 = i + stride;
@@ -61,7 +62,9 @@ __global__ __launch_bounds__(kGatherBlock) void k_gather(const long long* __rest
     const float* src = r >= 0 ? cache + (long long)r * F : feat + id * F;
     float* dst = out + i * F;
     if (cl == 0) {
-      if (r >= 0) ++hits; else ++misses;
+      if (r >= 0) ++cnt.hits; else ++cnt.misses;
+      ++cnt.copied;
+      if (rowref) rowref[i] = r;
     }
     for (int c0 = cl; c0 < chunks; c0 += 4 * lpr) {
       reg_t v[4];
@@ -77,52 +80,153 @@ __global__ __launch_bounds__(kGatherBlock) void k_gather(const long long* __rest
     i = i2; id = id2; r = r2;
     i2 = i3; id2 = id3;
   }
-  if (partials) {
-    // Hit / miss totals leave the kernel as one pair per workgroup and are folded by a second,
-    // tiny kernel: thousands of atomics on one counter serialise in L2 for longer than the copy
-    // takes (measured: +30 us for 4096 workgroups).
-    __shared__ unsigned long long s_h[kGatherBlock / kWave], s_m[kGatherBlock / kWave];
-    hits = wave_sum_u64(hits);
-    misses = wave_sum_u64(misses);
-    if (lane_id() == 0) {
-      s_h[threadIdx.x / kWave] = hits;
-      s_m[threadIdx.x / kWave] = misses;
+}
+
+// Hit / miss / copied totals leave a gather kernel as one triple per workgroup and are folded by a second,
+// tiny kernel: thousands of atomics on one counter serialise in L2 for longer than the copy takes
+// (measured: +30 us for 4096 workgroups).
+__device__ __forceinline__ void store_partials(GatherCounts cnt, unsigned long long* __restrict__ partials) {
+  __shared__ unsigned long long s_h[kGatherBlock / kWave], s_m[kGatherBlock / kWave], s_c[kGatherBlock / kWave];
+  const unsigned long long hits = wave_sum_u64(cnt.hits), misses = wave_sum_u64(cnt.misses), copied = wave_sum_u64(cnt.copied);
+  if (lane_id() == 0) {
+    s_h[threadIdx.x / kWave] = hits;
+    s_m[threadIdx.x / kWave] = misses;
+    s_c[threadIdx.x / kWave] = copied;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned long long h = 0, m = 0, c = 0;
+    for (int w = 0; w < kGatherBlock / kWave; ++w) {
+      h += s_h[w];
+      m += s_m[w];
+      c += s_c[w];
     }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      unsigned long long h = 0, m = 0;
-      for (int w = 0; w < kGatherBlock / kWave; ++w) {
-        h += s_h[w];
-        m += s_m[w];
+    partials[3 * blockIdx.x] = h;
+    partials[3 * blockIdx.x + 1] = m;
+    partials[3 * blockIdx.x + 2] = c;
+  }
+}
+
+template <int V>
+__global__ __launch_bounds__(kGatherBlock) void k_gather(const long long* __restrict__ ids, long long n_max,
+                                                         const long long* __restrict__ n_dev,
+                                                         const int* __restrict__ remap,
+                                                         const float* __restrict__ cache,
+                                                         const float* __restrict__ feat, int F, int lpr_log2,
+                                                         float* __restrict__ out,
+                                                         unsigned long long* __restrict__ partials) {
+  long long n = n_dev ? *n_dev : n_max;
+  if (n > n_max) n = n_max;
+  GatherCounts cnt;
+  copy_rows<V>(ids, n, remap, cache, feat, F, lpr_log2, out, nullptr, (int)blockIdx.x, (int)gridDim.x, cnt);
+  if (partials) store_partials(cnt, partials);
+}
+
+// The selective gather of dci_gather_forward: every row's cache slot (or -1) is noted in rowref[i]; the
+// row itself is copied only if it lies below *n_dense_dev (the rows of F_{L-1}, which the dense layer reads
+// as a matrix) or misses (so that it crosses the host link once, not once per edge that uses it).
+// The first n_dense_blocks workgroups copy the rows of F_{L-1} like the plain gather.  The others go over the
+// rest with one lane per row - 64 dependent id -> remap chains in flight per wavefront instead of one per
+// lane group, because most of these rows are only looked up - and the rows among them that missed are then
+// moved by the whole wavefront, up to four rows' loads in flight at a time.
+template <int V>
+__global__ __launch_bounds__(kGatherBlock) void k_gather_select(const long long* __restrict__ ids, long long n_max,
+                                                                const long long* __restrict__ n_dev,
+                                                                const int* __restrict__ remap,
+                                                                const float* __restrict__ cache,
+                                                                const float* __restrict__ feat, int F, int lpr_log2,
+                                                                float* __restrict__ out,
+                                                                unsigned long long* __restrict__ partials,
+                                                                int* __restrict__ rowref,
+                                                                const long long* __restrict__ n_dense_dev,
+                                                                int n_dense_blocks) {
+  typedef typename GVec<V>::reg reg_t;
+  typedef typename GVec<V>::mem mem_t;
+  long long n = *n_dev;
+  if (n > n_max) n = n_max;
+  long long n_dense = *n_dense_dev;
+  if (n_dense > n) n_dense = n;
+  GatherCounts cnt;
+  if ((int)blockIdx.x < n_dense_blocks) {
+    copy_rows<V>(ids, n_dense, remap, cache, feat, F, lpr_log2, out, rowref, (int)blockIdx.x, n_dense_blocks, cnt);
+  } else {
+    const int chunks = F / V, tail = F % V;
+    const int lane = lane_id();
+    const long long first = n_dense + (long long)((int)blockIdx.x - n_dense_blocks) * kGatherBlock;
+    const long long stride = (long long)((int)gridDim.x - n_dense_blocks) * kGatherBlock;
+    for (long long base = first; base < n; base += stride) {
+      const long long i = base + threadIdx.x;
+      const bool valid = i < n;
+      const long long id = valid ? ids[i] : 0;
+      const int r = (valid && remap) ? remap[id] : -1;
+      if (valid) {
+        rowref[i] = r;
+        if (r >= 0) ++cnt.hits; else ++cnt.misses;
       }
-      partials[2 * blockIdx.x] = h;
-      partials[2 * blockIdx.x + 1] = m;
+      const bool need = valid && r < 0;
+      if (need) ++cnt.copied;
+      const float* my_src = feat + id * F;
+      unsigned long long todo = __ballot(need);
+      const long long wave_row0 = i - lane;  // row of lane 0 of this wavefront
+      while (todo != 0ull) {
+        int j[4];
+        const float* src[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          j[u] = todo ? (int)__ffsll((long long)todo) - 1 : -1;
+          if (todo) todo &= todo - 1ull;
+          const int from = j[u] >= 0 ? j[u] : 0;
+          const unsigned long long p = (unsigned long long)reinterpret_cast<uintptr_t>(my_src);
+          const unsigned lo = (unsigned)__shfl((int)(unsigned)p, from, kWave), hi = (unsigned)__shfl((int)(unsigned)(p >> 32), from, kWave);
+          src[u] = reinterpret_cast<const float*>((uintptr_t)(((unsigned long long)hi << 32) | lo));
+        }
+        for (int c0 = lane; c0 < chunks; c0 += kWave) {
+          reg_t v[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            if (j[u] >= 0) v[u] = reinterpret_cast<const mem_t*>(src[u])[c0];
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            if (j[u] >= 0) reinterpret_cast<mem_t*>(out + (wave_row0 + j[u]) * F)[c0] = v[u];
+        }
+        if (lane < tail) {
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            if (j[u] >= 0) out[(wave_row0 + j[u]) * F + V * chunks + lane] = src[u][V * chunks + lane];
+        }
+      }
     }
   }
+  if (partials) store_partials(cnt, partials);
 }
 
 __global__ __launch_bounds__(kGatherBlock) void k_fold_gather_stats(const unsigned long long* __restrict__ partials,
                                                                     int n_blocks, unsigned long long row_bytes,
                                                                     unsigned long long* stats) {
-  unsigned long long h = 0, m = 0;
+  unsigned long long h = 0, m = 0, c = 0;
   for (int b = (int)threadIdx.x; b < n_blocks; b += kGatherBlock) {
-    h += partials[2 * b];
-    m += partials[2 * b + 1];
+    h += partials[3 * b];
+    m += partials[3 * b + 1];
+    c += partials[3 * b + 2];
   }
-  __shared__ unsigned long long s_h[kGatherBlock / kWave], s_m[kGatherBlock / kWave];
+  __shared__ unsigned long long s_h[kGatherBlock / kWave], s_m[kGatherBlock / kWave], s_c[kGatherBlock / kWave];
   h = wave_sum_u64(h);
   m = wave_sum_u64(m);
+  c = wave_sum_u64(c);
   if (lane_id() == 0) {
     s_h[threadIdx.x / kWave] = h;
     s_m[threadIdx.x / kWave] = m;
+    s_c[threadIdx.x / kWave] = c;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    h = m = 0;
+    h = m = c = 0;
     for (int w = 0; w < kGatherBlock / kWave; ++w) {
       h += s_h[w];
       m += s_m[w];
+      c += s_c[w];
     }
+    if (c) atomicAdd(&stats[DCI_STAT_ROWS_COPIED], c);
     atomicAdd(&stats[DCI_STAT_FEAT_HITS], h);
     atomicAdd(&stats[DCI_STAT_FEAT_MISSES], m);
     // a gathered row is read once, from the tier that holds it
@@ -132,11 +236,12 @@ __global__ __launch_bounds__(kGatherBlock) void k_fold_gather_stats(const unsign
 }
 
 size_t gather_partials_bytes(const dci_ctx* ctx) {
-  return (size_t)ctx->num_cus * kGatherBlocksPerCu * 2 * sizeof(unsigned long long);
+  return (size_t)ctx->num_cus * kGatherBlocksPerCu * 3 * sizeof(unsigned long long);
 }
 
 int32_t gather_launch(dci_ctx* ctx, const dci_graph* g, const dci_cache* cache, const int64_t* ids, int64_t n_max,
-                      const int64_t* n_dev, float* out, uint64_t* stats, void* partials_buf) {
+                      const int64_t* n_dev, float* out, uint64_t* stats, void* partials_buf, int32_t* rowref,
+                      const int64_t* n_dense_dev, int64_t n_dense_max) {
   const int F = g->feat_dim;
   const float* fcache = cache ? cache->feat_cache : nullptr;
   const int* remap = cache ? cache->feat_remap : nullptr;
@@ -150,16 +255,37 @@ int32_t gather_launch(dci_ctx* ctx, const dci_graph* g, const dci_cache* cache, 
   int lpr_log2 = 0;
   while ((1 << lpr_log2) < chunks && lpr_log2 < 6) ++lpr_log2;
   const int rows_per_block = kGatherBlock >> lpr_log2;
-  int64_t blocks = (n_max + rows_per_block - 1) / rows_per_block;
   const int64_t cap = (int64_t)ctx->num_cus * kGatherBlocksPerCu;
-  if (blocks > cap) blocks = cap;
-  if (blocks < 1) blocks = 1;
+  auto blocks_for = [&](int64_t rows, int per_block) {
+    int64_t b = (rows + per_block - 1) / per_block;
+    if (b > cap) b = cap;
+    return b < 1 ? (int64_t)1 : b;
+  };
+  int64_t blocks = blocks_for(n_max, rows_per_block);
   {
     Timed timed(ctx, DCI_K_GATHER);
     const long long* ids_ = reinterpret_cast<const long long*>(ids);
     const long long* nd_ = reinterpret_cast<const long long*>(n_dev);
+    const long long* dn_ = reinterpret_cast<const long long*>(n_dense_dev);
     unsigned long long* st = stats ? reinterpret_cast<unsigned long long*>(partials_buf) : nullptr;
-    if (V == 4)
+    if (rowref) {
+      if (!n_dev || !n_dense_dev) return fail(ctx, DCI_ERR_INVALID_ARG, "selective gather needs device-side row counts");
+      // half of the grid at most for the dense rows, the rest for the look-ups (both parts walk their rows
+      // with a grid stride, so any split is correct)
+      int64_t dense_blocks = blocks_for(n_dense_max, rows_per_block);
+      if (dense_blocks > cap / 2) dense_blocks = cap / 2;
+      const int64_t look_blocks = blocks_for(n_max, kGatherBlock) > cap / 2 ? cap / 2 : blocks_for(n_max, kGatherBlock);
+      blocks = dense_blocks + look_blocks;
+      if (V == 4)
+        hipLaunchKernelGGL((k_gather_select<4>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_,
+                           (long long)n_max, nd_, remap, fcache, g->feat, F, lpr_log2, out, st, rowref, dn_, (int)dense_blocks);
+      else if (V == 2)
+        hipLaunchKernelGGL((k_gather_select<2>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_,
+                           (long long)n_max, nd_, remap, fcache, g->feat, F, lpr_log2, out, st, rowref, dn_, (int)dense_blocks);
+      else
+        hipLaunchKernelGGL((k_gather_select<1>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_,
+                           (long long)n_max, nd_, remap, fcache, g->feat, F, lpr_log2, out, st, rowref, dn_, (int)dense_blocks);
+    } else if (V == 4)
       hipLaunchKernelGGL((k_gather<4>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_, (long long)n_max,
                          nd_, remap, fcache, g->feat, F, lpr_log2, out, st);
     else if (V == 2)
@@ -203,5 +329,5 @@ extern "C" int32_t dci_gather_features(dci_ctx* ctx, const dci_graph* graph, con
       return dci::fail(ctx, DCI_ERR_CAPACITY, "workspace holds %zu bytes, gather statistics need %zu", ctx->ws_bytes,
                        ar.off);
   }
-  return dci::gather_launch(ctx, graph, cache, node_ids, n_max, n_dev, out, stats, partials);
+  return dci::gather_launch(ctx, graph, cache, node_ids, n_max, n_dev, out, stats, partials, nullptr, nullptr, 0);
 }

@@ -28,6 +28,7 @@ struct dci_ctx {
   unsigned* host_flag = nullptr;  // pinned host word (64 bytes): a kernel raises it when a batch had to be voided
   unsigned relabel_spin_limit = 1u << 24;  // DCI_OPT_RELABEL_SPIN_LIMIT
   unsigned test_first_ticket = 0;          // DCI_OPT_TEST_RELABEL_FIRST_TICKET
+  int fused_input = 0;    // DCI_OPT_FUSED_INPUT: dci_infer_batches lets the first layer read cached rows in place
   int linear_split = 0;   // DCI_OPT_LINEAR_SPLIT: 0 = by shape, n = at most n workgroups per tile
   int linear_kernel = 0;  // DCI_OPT_LINEAR_KERNEL: 0 by shape, 1 tile kernel, 2 wide kernel where the shape allows
 };
@@ -143,8 +144,11 @@ int32_t fill_bytes(dci_ctx* ctx, void* p, size_t bytes, uint32_t pattern);
 // After a wait on the context's stream: reports (and clears) a failure that a kernel flagged.
 int32_t check_device_flag(dci_ctx* ctx);
 // partials_buf: gather_partials_bytes(ctx) bytes of device scratch, needed when stats != NULL
+// rowref / n_dense_dev: nullptr for the plain gather; otherwise the selective form (see k_gather_select),
+// n_dense_max bounding *n_dense_dev
 int32_t gather_launch(dci_ctx* ctx, const dci_graph* g, const dci_cache* cache, const int64_t* ids,
-                      int64_t n_max, const int64_t* n_dev, float* out, uint64_t* stats, void* partials_buf);
+                      int64_t n_max, const int64_t* n_dev, float* out, uint64_t* stats, void* partials_buf,
+                      int32_t* rowref, const int64_t* n_dense_dev, int64_t n_dense_max);
 size_t gather_partials_bytes(const dci_ctx* ctx);
 
 }  // namespace dci

@@ -39,11 +39,16 @@ extern "C" int32_t dci_infer_batches(const dci_lane* lanes, int32_t n_lanes, con
     const dci_lane& lane = lanes[k % n_lanes];
     dci_ctx* ctx = lane.ctx;
     int32_t rc = dci_sample_khop(ctx, graph, cache, seeds + lo, n, (uint64_t)b, fanouts, n_hops, rng_seed, lane.blocks, stats);
-    if (rc == DCI_OK)
-      rc = dci_gather_features(ctx, graph, cache, lane.blocks->nodes, lane.blocks->cap_nodes,
-                               lane.blocks->counts + n_hops, lane.x, stats);
-    if (rc == DCI_OK)
-      rc = dci_gnn_forward(ctx, lane.blocks, lane.x, n_hops, dims, model, w_self, w_neigh, bias, logits + lo * width);
+    if (rc == DCI_OK && ctx->fused_input) {
+      rc = dci_gather_forward(ctx, graph, cache, lane.blocks, lane.x, n_hops, dims, model, w_self, w_neigh, bias,
+                              logits + lo * width, stats);
+    } else {
+      if (rc == DCI_OK)
+        rc = dci_gather_features(ctx, graph, cache, lane.blocks->nodes, lane.blocks->cap_nodes,
+                                 lane.blocks->counts + n_hops, lane.x, stats);
+      if (rc == DCI_OK)
+        rc = dci_gnn_forward(ctx, lane.blocks, lane.x, n_hops, dims, model, w_self, w_neigh, bias, logits + lo * width);
+    }
     if (rc != DCI_OK) {
       if (ctx != first) dci::fail(first, rc, "infer_batches: batch %lld on lane %d: %s", (long long)b, (int)(k % n_lanes), ctx->err);
       return rc;

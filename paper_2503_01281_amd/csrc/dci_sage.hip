@@ -48,12 +48,17 @@ struct VecF<1> {
   static __device__ __forceinline__ float div(const float& a, float d) { return a / d; }
 };
 
-template <int V>
+// REF: the input layer when cached rows are read in place - the row of source s is
+// cache[rowref[s]] if rowref[s] >= 0 (its slot in the feature cache) and x[s] otherwise (a row that
+// missed and was staged there); the destination's own row (GCN) is always in x.
+template <int V, bool REF>
 __global__ __launch_bounds__(kMeanBlock) void k_sage_mean(const long long* __restrict__ counts, int hop,
                                                           const long long* __restrict__ blk_indptr,
                                                           const int* __restrict__ blk_src,
                                                           const float* __restrict__ x, int D, int lpr_log2,
-                                                          float* __restrict__ m, int mode) {
+                                                          float* __restrict__ m, int mode,
+                                                          const int* __restrict__ rowref,
+                                                          const float* __restrict__ cache) {
   // mode: DCI_MODEL_SAGE_MEAN  mean of the sampled neighbours (zero vector for an empty row)
   //       DCI_MODEL_SAGE_SUM   their sum
   //       DCI_MODEL_GCN_AVG    mean over the node itself and its sampled neighbours
@@ -65,6 +70,13 @@ __global__ __launch_bounds__(kMeanBlock) void k_sage_mean(const long long* __res
   const int rows_per_block = kMeanBlock >> lpr_log2;
   const int sub = (int)threadIdx.x >> lpr_log2;
   const int cl = (int)threadIdx.x & (lpr - 1);
+  auto row = [&](int s) -> const vec_t* {
+    if (REF) {
+      const int r = rowref[s];
+      return reinterpret_cast<const vec_t*>(r >= 0 ? cache + (long long)r * D : x + (long long)s * D);
+    }
+    return reinterpret_cast<const vec_t*>(x + (long long)s * D);
+  };
   for (long long base = (long long)blockIdx.x * rows_per_block; base < n_rows;
        base += (long long)gridDim.x * rows_per_block) {
     const long long i = base + sub;
@@ -76,17 +88,16 @@ __global__ __launch_bounds__(kMeanBlock) void k_sage_mean(const long long* __res
       vec_t acc = mode == DCI_MODEL_GCN_AVG ? reinterpret_cast<const vec_t*>(x + i * D)[c] : O::zero();
       long long e = e0;
       for (; e + 3 < e1; e += 4) {
-        const int s0 = blk_src[e], s1 = blk_src[e + 1], s2 = blk_src[e + 2], s3 = blk_src[e + 3];
-        const vec_t v0 = reinterpret_cast<const vec_t*>(x + (long long)s0 * D)[c];
-        const vec_t v1 = reinterpret_cast<const vec_t*>(x + (long long)s1 * D)[c];
-        const vec_t v2 = reinterpret_cast<const vec_t*>(x + (long long)s2 * D)[c];
-        const vec_t v3 = reinterpret_cast<const vec_t*>(x + (long long)s3 * D)[c];
+        const vec_t v0 = row(blk_src[e])[c];
+        const vec_t v1 = row(blk_src[e + 1])[c];
+        const vec_t v2 = row(blk_src[e + 2])[c];
+        const vec_t v3 = row(blk_src[e + 3])[c];
         O::add(acc, v0);
         O::add(acc, v1);
         O::add(acc, v2);
         O::add(acc, v3);
       }
-      for (; e < e1; ++e) O::add(acc, reinterpret_cast<const vec_t*>(x + (long long)blk_src[e] * D)[c]);
+      for (; e < e1; ++e) O::add(acc, row(blk_src[e])[c]);
       dst[c] = (mode == DCI_MODEL_SAGE_SUM || cnt == 0.f) ? acc : O::div(acc, cnt);
     }
   }
@@ -848,9 +859,13 @@ int32_t dci_sage_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_
   return dci_gnn_forward(ctx, blocks, x_in, n_layers, dims, DCI_MODEL_SAGE_MEAN, w_self, w_neigh, bias, logits);
 }
 
-int32_t dci_gnn_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_in, int32_t n_layers,
-                        const int32_t* dims, int32_t model, const float* const* w_self,
-                        const float* const* w_neigh, const float* const* bias, float* logits) {
+// Shared body of dci_gnn_forward and dci_gather_forward.  rowref != nullptr: the input layer's aggregation
+// reads the row of source s from feat_cache[rowref[s]] when rowref[s] >= 0 and from x_in[s] otherwise.
+// ws_off: bytes at the start of the workspace that the caller keeps for itself.
+static int32_t forward_in(dci_ctx* ctx, const dci_blocks* blocks, const float* x_in, int32_t n_layers,
+                          const int32_t* dims, int32_t model, const float* const* w_self,
+                          const float* const* w_neigh, const float* const* bias, float* logits,
+                          const int32_t* rowref, const float* feat_cache, size_t ws_off) {
   if (!ctx) return DCI_ERR_INVALID_ARG;
   if (model != DCI_MODEL_SAGE_MEAN && model != DCI_MODEL_SAGE_SUM && model != DCI_MODEL_GCN_AVG)
     return fail(ctx, DCI_ERR_INVALID_ARG, "gnn_forward: unknown model %d", model);
@@ -865,10 +880,11 @@ int32_t dci_gnn_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_i
     if ((!gcn && !w_self[l]) || !w_neigh[l] || !bias[l] || !blocks->blk_indptr[l] || !blocks->blk_src[l])
       return fail(ctx, DCI_ERR_INVALID_ARG, "sage_forward: null weight or block array at layer %d", l);
   Arena ar(ctx->ws, ctx->ws_bytes);
+  if (ws_off) (void)ar.take<char>(ws_off);
   SageWs ws;
   carve_sage_ws(ar, blocks->cap_rows, n_layers, dims, &ws);
   if (!ar.ok())
-    return fail(ctx, DCI_ERR_CAPACITY, "workspace holds %zu bytes, sage_forward needs %zu", ctx->ws_bytes, ar.off);
+    return fail(ctx, DCI_ERR_CAPACITY, "workspace holds %zu bytes, the forward pass needs %zu", ctx->ws_bytes, ar.off);
   const long long* counts = reinterpret_cast<const long long*>(blocks->counts);
   const float* x = x_in;
   auto aligned = [](const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; };
@@ -879,8 +895,9 @@ int32_t dci_gnn_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_i
     float* y = l == n_layers - 1 ? logits : ws.y[l & 1];
     // mean aggregation
     int V = 1;
-    if (D % 4 == 0 && aligned(x, 16)) V = 4;
-    else if (D % 2 == 0 && aligned(x, 8)) V = 2;
+    const bool cache_al16 = !(l == 0 && rowref) || aligned(feat_cache, 16), cache_al8 = !(l == 0 && rowref) || aligned(feat_cache, 8);
+    if (D % 4 == 0 && aligned(x, 16) && cache_al16) V = 4;
+    else if (D % 2 == 0 && aligned(x, 8) && cache_al8) V = 2;
     const int chunks = D / V;
     int lpr_log2 = 0;
     while ((1 << lpr_log2) < chunks && lpr_log2 < 6) ++lpr_log2;
@@ -890,15 +907,21 @@ int32_t dci_gnn_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_i
     const long long* bi = reinterpret_cast<const long long*>(blocks->blk_indptr[h]);
     {
     Timed timed(ctx, l == 0 ? DCI_K_MEAN_IN : DCI_K_MEAN);
-    if (V == 4)
-      hipLaunchKernelGGL((k_sage_mean<4>), dim3((int)mb), dim3(kMeanBlock), 0, ctx->stream, counts, h, bi,
-                         (const int*)blocks->blk_src[h], x, D, lpr_log2, ws.m, model);
-    else if (V == 2)
-      hipLaunchKernelGGL((k_sage_mean<2>), dim3((int)mb), dim3(kMeanBlock), 0, ctx->stream, counts, h, bi,
-                         (const int*)blocks->blk_src[h], x, D, lpr_log2, ws.m, model);
-    else
-      hipLaunchKernelGGL((k_sage_mean<1>), dim3((int)mb), dim3(kMeanBlock), 0, ctx->stream, counts, h, bi,
-                         (const int*)blocks->blk_src[h], x, D, lpr_log2, ws.m, model);
+    const bool ref = l == 0 && rowref != nullptr;
+    const int* bsrc = (const int*)blocks->blk_src[h];
+#define DCI_MEAN_LAUNCH(VV, RR)                                                                                  \
+  hipLaunchKernelGGL((k_sage_mean<VV, RR>), dim3((int)mb), dim3(kMeanBlock), 0, ctx->stream, counts, h, bi, bsrc, x, \
+                     D, lpr_log2, ws.m, model, (const int*)rowref, feat_cache)
+    if (ref) {
+      if (V == 4) DCI_MEAN_LAUNCH(4, true);
+      else if (V == 2) DCI_MEAN_LAUNCH(2, true);
+      else DCI_MEAN_LAUNCH(1, true);
+    } else {
+      if (V == 4) DCI_MEAN_LAUNCH(4, false);
+      else if (V == 2) DCI_MEAN_LAUNCH(2, false);
+      else DCI_MEAN_LAUNCH(1, false);
+    }
+#undef DCI_MEAN_LAUNCH
     }
     DCI_LAUNCH_CHECK(ctx);
     // dense layer
@@ -975,6 +998,58 @@ int32_t dci_gnn_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_i
     x = y;
   }
   return DCI_OK;
+}
+
+int32_t dci_gnn_forward(dci_ctx* ctx, const dci_blocks* blocks, const float* x_in, int32_t n_layers,
+                        const int32_t* dims, int32_t model, const float* const* w_self,
+                        const float* const* w_neigh, const float* const* bias, float* logits) {
+  return forward_in(ctx, blocks, x_in, n_layers, dims, model, w_self, w_neigh, bias, logits, nullptr, nullptr, 0);
+}
+
+static size_t gather_forward_prefix_bytes(const dci_ctx* ctx, int64_t cap_nodes, size_t* partials_off) {
+  Arena ar(nullptr, 0);
+  (void)ar.take<int32_t>((size_t)(cap_nodes > 0 ? cap_nodes : 1));
+  *partials_off = ar.off;
+  (void)ar.take<char>(ctx ? gather_partials_bytes(ctx) : (size_t)kMaxCus * 16 * 3 * sizeof(unsigned long long));
+  return ar.off;
+}
+
+size_t dci_gather_forward_workspace_bytes(int64_t cap_nodes, const int64_t* cap_rows, int32_t n_layers,
+                                          const int32_t* dims) {
+  const size_t fwd = dci_sage_workspace_bytes(cap_rows, n_layers, dims);
+  if (fwd == 0 || cap_nodes < 0) return 0;
+  size_t unused;
+  return gather_forward_prefix_bytes(nullptr, cap_nodes, &unused) + fwd;
+}
+
+int32_t dci_gather_forward(dci_ctx* ctx, const dci_graph* graph, const dci_cache* cache, const dci_blocks* blocks,
+                           float* x, int32_t n_layers, const int32_t* dims, int32_t model,
+                           const float* const* w_self, const float* const* w_neigh, const float* const* bias,
+                           float* logits, uint64_t* stats) {
+  if (!ctx) return DCI_ERR_INVALID_ARG;
+  if (!graph || !graph->feat || graph->feat_dim < 1 || !blocks || !blocks->nodes || !blocks->counts || !x || !dims)
+    return fail(ctx, DCI_ERR_INVALID_ARG, "gather_forward: null argument or missing feature matrix");
+  if (n_layers < 1 || n_layers > DCI_MAX_HOPS || n_layers != blocks->n_hops)
+    return fail(ctx, DCI_ERR_INVALID_ARG, "gather_forward: n_layers must equal blocks.n_hops (1..%d)", DCI_MAX_HOPS);
+  if (dims[0] != graph->feat_dim)
+    return fail(ctx, DCI_ERR_INVALID_ARG, "gather_forward: dims[0] = %d but the graph has %d features", dims[0], graph->feat_dim);
+  if (cache && (!cache->feat_remap || (cache->feat_rows > 0 && !cache->feat_cache)))
+    return fail(ctx, DCI_ERR_INVALID_ARG, "cache: null feature arrays");
+  if ((reinterpret_cast<uintptr_t>(graph->feat) | reinterpret_cast<uintptr_t>(x) |
+       (cache ? reinterpret_cast<uintptr_t>(cache->feat_cache) : 0)) & 3)
+    return fail(ctx, DCI_ERR_INVALID_ARG, "feature arrays must be 4-byte aligned");
+  size_t partials_off;
+  const size_t prefix = gather_forward_prefix_bytes(ctx, blocks->cap_nodes, &partials_off);
+  if (prefix > ctx->ws_bytes || !ctx->ws)
+    return fail(ctx, DCI_ERR_CAPACITY, "workspace holds %zu bytes, gather_forward needs more than %zu", ctx->ws_bytes, prefix);
+  int32_t* rowref = reinterpret_cast<int32_t*>(ctx->ws);
+  // the rows the dense layer of the input layer reads as a matrix: F_{L-1}, a prefix of the input nodes
+  const int64_t* n_dense = blocks->counts + (n_layers - 1);
+  int32_t rc = gather_launch(ctx, graph, cache, blocks->nodes, blocks->cap_nodes, blocks->counts + n_layers, x, stats,
+                             ctx->ws + partials_off, rowref, n_dense, blocks->cap_rows[n_layers - 1]);
+  if (rc != DCI_OK) return rc;
+  return forward_in(ctx, blocks, x, n_layers, dims, model, w_self, w_neigh, bias, logits, rowref,
+                    cache ? cache->feat_cache : nullptr, prefix);
 }
 
 }  // extern "C"

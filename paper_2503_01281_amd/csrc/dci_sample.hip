@@ -999,7 +999,7 @@ int32_t dci_presample_count(dci_ctx* ctx, const dci_graph* graph, const dci_cach
     if (feat_scratch) {
       DCI_HIP(ctx, hipEventRecord(ctx->ev[1], ctx->stream));
       rc = gather_launch(ctx, graph, cache, blk.nodes, cap_nodes[n_hops], blk.counts + n_hops, feat_scratch, stats,
-                         gather_partials);
+                         gather_partials, nullptr, nullptr, 0);
       if (rc != DCI_OK) return rc;
       DCI_HIP(ctx, hipEventRecord(ctx->ev[2], ctx->stream));
       DCI_HIP(ctx, hipEventSynchronize(ctx->ev[2]));

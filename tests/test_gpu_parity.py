@@ -757,3 +757,71 @@ def test_relabel_timeout_voids_the_batch_and_is_reported(env):
     dci.dci_sample_khop(ctx, g, None, gu.dev(seeds), 0, w.fanouts, w.rng_seed, blk, stats)
     gu.assert_blocks_equal(gu.blocks_to_host(ctx, blk), oracle.sample_khop(tiny["indptr"], tiny["indices"], seeds, 0,
                                                                             w.fanouts, w.rng_seed))
+
+
+@pytest.mark.parametrize("F,model", [(64, 0), (64, 2), (63, 0), (602, 0), (602, 1), (100, 2), (1, 0), (130, 0)])
+def test_gather_forward_reads_cached_rows_in_place(env, F, model):
+    """dci_gather_forward against the oracle and against dci_gather_features + dci_gnn_forward: the same logits
+    bit for bit (the sums run in the same order), the same hit / miss statistics, and in x only the rows that
+    miss or belong to F_{L-1}; with a partly filled feature cache, with none, and with everything cached."""
+    dci, gu, ctx, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "tiny", "w"))
+    N = w.num_nodes
+    feat = synth.features(N, F, 40 + F)
+    g = gu.make_graph(tiny["indptr"], tiny["indices"], feat)
+    dims = (F, 48, 10)
+    ws_h, wn_h, b_h = synth.sage_weights(dims, 77)
+    ws, wn, bs = ([gu.dev(a) for a in arr] for arr in (ws_h, wn_h, b_h))
+    rng = np.random.default_rng(F * 10 + model)
+    seeds = tiny["seeds"][300:300 + 200]
+    want = oracle.sample_khop(tiny["indptr"], tiny["indices"], seeds, 5, w.fanouts, w.rng_seed)
+    want_x = oracle.gather(feat, want.nodes)
+    ref = oracle.gnn_forward(model, want, want_x, ws_h, wn_h, b_h)
+    n_in, n_dense = len(want.nodes), int(want.n_nodes[w.n_hops - 1])
+    for share in (0.5, None, 1.0):
+        if share is None:
+            cache, remap = None, np.full(N, -1, dtype=np.int32)
+        else:
+            k = int(N * share)
+            rows = rng.permutation(N)[:k]
+            remap = np.full(N, -1, dtype=np.int32)
+            remap[rows] = np.arange(k, dtype=np.int32)
+            cache = gu.upload_cache(np.full(N, -1), np.zeros(1, np.int64), np.zeros(0, np.int64), remap, feat[rows])
+        blk = dci.Blocks(ctx, N, len(seeds), w.fanouts)
+        dci.dci_sample_khop(ctx, g, cache, gu.dev(seeds), 5, w.fanouts, w.rng_seed, blk)
+        x = torch.full((blk.cap_nodes[-1], F), -123.0, dtype=torch.float32, device="cuda")
+        logits = torch.zeros(len(seeds), dims[-1], dtype=torch.float32, device="cuda")
+        stats = gu.new_stats()
+        dci.dci_gather_forward(ctx, g, cache, blk, x, model, None if model == 2 else ws, wn, bs, logits, stats)
+        st = gu.stats_dict(ctx, stats)
+        got = logits.cpu().numpy()
+        _logit_check(got, ref)
+        hit = remap[want.nodes] >= 0
+        assert (st["feat_hits"], st["feat_misses"]) == (int(hit.sum()), int((~hit).sum()))
+        assert (st["bytes_hbm"], st["bytes_host"]) == (4 * F * int(hit.sum()), 4 * F * int((~hit).sum()))
+        xs = x.cpu().numpy()
+        copied = ~hit | (np.arange(n_in) < n_dense)
+        assert st["rows_copied"] == int(copied.sum())
+        assert xs[:n_in][copied].tobytes() == want_x[copied].tobytes()
+        assert (xs[:n_in][~copied] == -123.0).all() and (xs[n_in:] == -123.0).all()
+        if share == 0.5:
+            assert 0 < copied.sum() < n_in
+        # the two-call route gives the same bits
+        x2 = torch.empty_like(x)
+        logits2 = torch.zeros_like(logits)
+        dci.dci_gather_features(ctx, g, cache, blk.nodes, blk.cap_nodes[-1], x2, n_dev=blk.n_input_dev())
+        dci.dci_gnn_forward(ctx, blk, x2, model, None if model == 2 else ws, wn, bs, logits2)
+        ctx.sync()
+        assert logits2.cpu().numpy().tobytes() == got.tobytes()
+
+
+def test_gather_forward_rejects_bad_arguments(env):
+    dci, gu, ctx, g, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "graph", "tiny", "w"))
+    blk = dci.Blocks(ctx, w.num_nodes, 16, w.fanouts)
+    dci.dci_sample_khop(ctx, g, None, gu.dev(tiny["seeds"][:16]), 0, w.fanouts, w.rng_seed, blk)
+    x = torch.empty(blk.cap_nodes[-1], w.feat_dim, dtype=torch.float32, device="cuda")
+    logits = torch.empty(16, 10, dtype=torch.float32, device="cuda")
+    ws_h, wn_h, b_h = synth.sage_weights((w.feat_dim + 1, 8, 10), 3)       # wrong input width
+    ws, wn, bs = ([gu.dev(a) for a in arr] for arr in (ws_h, wn_h, b_h))
+    with pytest.raises(dci.DciError) as e:
+        dci.dci_gather_forward(ctx, g, None, blk, x, 0, ws, wn, bs, logits)
+    assert e.value.code == -1 and "features" in str(e.value)

@@ -99,6 +99,34 @@ def test_sixteen_batches_on_four_lanes(setup, model):
         _check_logits(out[b * B:(b + 1) * B], ref[b])
 
 
+def test_fused_input_lanes_give_the_same_logits(setup):
+    """DCI_OPT_FUSED_INPUT on every lane: cached neighbour rows are read in place; logits of all sixteen batches
+    against the oracle, blocks bit for bit, statistics as with the two-call route."""
+    dci, gu, w, g, cache, lanes, want, tiny = (setup[k] for k in ("dci", "gu", "w", "g", "cache", "lanes", "want", "tiny"))
+    ws, wn, bs = setup["weights"]
+    nb = len(want)
+    logits = torch.full((w.num_seeds, w.classes), float("nan"), dtype=torch.float32, device="cuda")
+    stats = gu.new_stats()
+    torch.cuda.synchronize()
+    for ln in lanes:
+        ln.ctx.set_option(dci.DCI_OPT_FUSED_INPUT, 1)
+    try:
+        dci.dci_infer_batches(lanes, g, cache, setup["seeds"], B, 0, nb, w.fanouts, w.rng_seed, 0, ws, wn, bs, logits, stats)
+        for ln in lanes:
+            ln.ctx.sync()
+    finally:
+        for ln in lanes:
+            ln.ctx.set_option(dci.DCI_OPT_FUSED_INPUT, 0)
+    out = logits.cpu().numpy()
+    for b, (blk, x) in enumerate(want):
+        _check_logits(out[b * B:(b + 1) * B], oracle.sage_forward(blk, x, tiny["w_self"], tiny["w_neigh"], tiny["bias"]))
+    for k, ln in enumerate(lanes):
+        gu.assert_blocks_equal(gu.blocks_to_host(ln.ctx, ln.blocks), want[nb - N_LANES + k][0])
+    st = {k: int(v) for k, v in zip(dci.STAT.keys(), stats.cpu().numpy())}
+    hits = sum(int((setup["feat_remap"][blk.nodes] >= 0).sum()) for blk, _ in want)
+    assert (st["feat_hits"], st["feat_hits"] + st["feat_misses"]) == (hits, sum(len(blk.nodes) for blk, _ in want))
+
+
 def test_ragged_last_batch_and_ranges(setup):
     """A seed list that ends inside a batch, a range that runs past the last batch, an empty range, one lane."""
     dci, gu, w, g, cache, lanes, tiny = (setup[k] for k in ("dci", "gu", "w", "g", "cache", "lanes", "tiny"))
