@@ -189,6 +189,9 @@ const char* dci_last_error(const dci_ctx* ctx);
  *       1 dci_gather_forward (cached neighbour rows are read in place; x holds only the rows that
  *       missed and those of F_{L-1}).  The logits are the same up to nothing: the sums run in the same order. */
 #define DCI_OPT_FUSED_INPUT 5
+/*   DCI_OPT_RELABEL_TILE_ITERS  rows per lane group in a tile of the frontier scan: 0 (default) chosen from
+ *       the frontier's size, or 2, 4, 8.  Tuning only: the result does not depend on it. */
+#define DCI_OPT_RELABEL_TILE_ITERS 6
 int32_t dci_set_option(dci_ctx* ctx, int32_t option, int64_t value);
 
 /* Kernel timing, for benchmarks and profiles.  Kernel classes whose bit is set in class_mask are

@@ -185,6 +185,12 @@ int32_t dci_set_option(dci_ctx* ctx, int32_t option, int64_t value) {
     ctx->linear_split = (int)value;
     return DCI_OK;
   }
+  if (option == DCI_OPT_RELABEL_TILE_ITERS) {
+    if (value != 0 && value != 2 && value != 4 && value != 8)
+      return dci::fail(ctx, DCI_ERR_INVALID_ARG, "DCI_OPT_RELABEL_TILE_ITERS takes 0, 2, 4 or 8, not %lld", (long long)value);
+    ctx->relabel_tile_iters = (int)value;
+    return DCI_OK;
+  }
   if (option == DCI_OPT_FUSED_INPUT) {
     if (value != 0 && value != 1) return dci::fail(ctx, DCI_ERR_INVALID_ARG, "DCI_OPT_FUSED_INPUT takes 0 or 1, not %lld", (long long)value);
     ctx->fused_input = (int)value;

@@ -393,7 +393,11 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
 // the all-ones fill pattern reads as "not yet published".  A status word carries its whole
 // message, so the atomic accesses are relaxed: release / acquire at device scope would add an
 // L2 write-back / invalidate to every publish and every poll.
-constexpr int kTileIters = 8;
+// Rows per tile = (lane groups per workgroup) x (rows per group, kTileItersMax at most).  Many rows per
+// group keep several independent loads in flight per lane; few rows per group give more tiles, i.e. more
+// workgroups to hide the tile's chain of dependent phases behind.  Which wins depends on how many tiles a
+// frontier makes, so the count is picked per hop from the frontier's capacity (tile_iters_for).
+constexpr int kTileItersMax = 8;
 constexpr unsigned long long kStInvalid = 3ull, kStAggregate = 1ull, kStInclusive = 2ull;
 // The look-back polls at most dci_ctx::relabel_spin_limit times (default 2^24: far beyond any real wait, ends a wedged launch).
 
@@ -420,7 +424,7 @@ struct RelabelArgs {
   unsigned first_ticket;  // tiles are numbered from here (0 except under the failure-handling test hook)
 };
 
-template <int G>
+template <int G, int kTileIters>
 __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
   constexpr int kGroups = kBlock / G;
   constexpr int TR = kGroups * kTileIters;  // rows per tile, at most kBlock
@@ -436,6 +440,16 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
   const int gl = lane & (G - 1), grp_in_wave = lane / G, grp = tid / G;
   if (*a.batch_flag != kBatchOk) return;  // an earlier hop failed (uniform over the launch: set before it began)
   const long long n_rows = a.counts[a.hop];
+  // The grid is sized for the frontier's bound; only as many workgroups as the frontier has tiles take a
+  // ticket (the tickets are atomics on one word and serialise, about 25 ns each: left to the whole grid
+  // they were most of this kernel's time).  Which workgroups those are does not matter for progress: a
+  // tile waits only for smaller tickets, and those are held by workgroups that are already running.
+  {
+    const long long n_tiles = (n_rows + TR - 1) / TR;
+    long long takers = n_tiles - (long long)a.first_ticket;
+    if (takers < 1) takers = 1;  // an empty frontier (or a test hook beyond it) still needs one workgroup
+    if ((long long)blockIdx.x >= takers) return;
+  }
   if (tid == 0) s_tile = atomicAdd(a.ticket, 1u) + 1u + a.first_ticket;
   __syncthreads();
   const unsigned tile = s_tile;
@@ -540,39 +554,60 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
       if (lane == 0)
         __hip_atomic_store(&a.status[tile], st_pack(kStAggregate, (unsigned)tot_f, (unsigned)tot_c), __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
+      // Look back over the earlier tiles, kLookWindows x 64 status words per round trip (lane l of window k
+      // reads tile j - 64 k - l), nearest first.  A window is resolved once every word nearer than its
+      // nearest inclusive one (or, if it has none, every word) is published; the sum stops at the first
+      // inclusive word.
+      constexpr int kLookWindows = 4;
       long long j = (long long)tile - 1;
       unsigned polls = 0;
-      for (;;) {
-        const long long idx = j - lane;
-        unsigned long long st = idx >= 0 ? __hip_atomic_load(&a.status[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                         : st_pack(kStInclusive, 0, 0);
-        while (__ballot((st >> 62) == kStInvalid) != 0ull && polls < a.spin_limit) {
-          __builtin_amdgcn_s_sleep(1);
-          ++polls;
-          if ((st >> 62) == kStInvalid)
-            st = __hip_atomic_load(&a.status[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      bool found = false, timed_out = false;
+      while (!found && !timed_out) {
+        unsigned long long st[kLookWindows];
+#pragma unroll
+        for (int k = 0; k < kLookWindows; ++k) {
+          const long long idx = j - (long long)k * kWave - lane;
+          st[k] = idx >= 0 ? __hip_atomic_load(&a.status[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                           : st_pack(kStInclusive, 0, 0);
         }
-        // the polling loop ends with an unpublished word in the window only when it ran out of polls
-        const bool timed_out = __ballot((st >> 62) == kStInvalid) != 0ull;
-        const unsigned long long inc_mask = __ballot((st >> 62) == kStInclusive);
-        const int stop = inc_mask ? (int)__ffsll((long long)inc_mask) - 1 : kWave;  // nearest tile with a prefix
-        long long pc = 0;
-        int pf = 0;
-        if (lane <= stop && (st >> 62) != kStInvalid) {
-          pc = (long long)(st & 0x7FFFFFFFull);
-          pf = (int)((st >> 31) & 0x7FFFFFFFull);
+#pragma unroll
+        for (int k = 0; k < kLookWindows; ++k) {
+          if (!found && !timed_out) {
+            const long long idx = j - (long long)k * kWave - lane;
+            int first_inc;
+            for (;;) {
+              const unsigned long long inv = __ballot((st[k] >> 62) == kStInvalid);
+              const unsigned long long inc = __ballot((st[k] >> 62) == kStInclusive);
+              first_inc = inc ? (int)__ffsll((long long)inc) - 1 : kWave;  // nearest tile with a prefix
+              const unsigned long long nearer = first_inc >= kWave ? ~0ull : ((1ull << first_inc) - 1ull);
+              if ((inv & nearer) == 0ull) break;
+              if (polls >= a.spin_limit) {
+                timed_out = true;
+                break;
+              }
+              __builtin_amdgcn_s_sleep(1);
+              ++polls;
+              if ((st[k] >> 62) == kStInvalid)
+                st[k] = __hip_atomic_load(&a.status[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            long long pc = 0;
+            int pf = 0;
+            if (lane <= first_inc && (st[k] >> 62) != kStInvalid) {
+              pc = (long long)(st[k] & 0x7FFFFFFFull);
+              pf = (int)((st[k] >> 31) & 0x7FFFFFFFull);
+            }
+            ec += (long long)wave_sum_u64((unsigned long long)pc);
+            ef += (int)wave_sum_u64((unsigned long long)pf);
+            if (!timed_out && first_inc < kWave) found = true;
+          }
         }
-        ec += (long long)wave_sum_u64((unsigned long long)pc);
-        ef += (int)wave_sum_u64((unsigned long long)pf);
-        if (timed_out) {
-          // Gave up: a predecessor never published.  The tile goes on with what it has - every index it
-          // forms stays at or below the true one, hence inside the batch's buffers - and voids the batch,
-          // so that no later kernel reads what this hop leaves behind.
-          if (lane == 0) __hip_atomic_store(a.batch_flag, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          break;
-        }
-        if (inc_mask != 0ull) break;
-        j -= kWave;
+        j -= (long long)kLookWindows * kWave;
+      }
+      if (timed_out && lane == 0) {
+        // Gave up: a predecessor never published.  The tile goes on with what it has - every index it
+        // forms stays at or below the true one, hence inside the batch's buffers - and voids the batch,
+        // so that no later kernel reads what this hop leaves behind.
+        __hip_atomic_store(a.batch_flag, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
       ec = __shfl(ec, 0, kWave);
       ef = __shfl(ef, 0, kWave);
@@ -664,10 +699,19 @@ static uint64_t table_entries_for(int64_t cap_nodes_last) {
 
 static int group_for(int fanout) { return fanout <= 8 ? 8 : fanout <= 16 ? 16 : fanout <= 32 ? 32 : 64; }
 
-static int64_t tiles_for(int64_t rows, int fanout) {
-  const int64_t tr = (int64_t)(kBlock / group_for(fanout)) * kTileIters;
+static int64_t tiles_for(int64_t rows, int fanout, int iters) {
+  const int64_t tr = (int64_t)(kBlock / group_for(fanout)) * iters;
   const int64_t t = (rows + tr - 1) / tr;
   return t < 1 ? 1 : t;
+}
+constexpr int kTileItersMin = 2;  // the workspace is sized for the smallest tiles
+
+// Rows per lane group of a relabel tile for a frontier of up to cap_rows rows (DCI_OPT_RELABEL_TILE_ITERS overrides).
+static int tile_iters_for(const dci_ctx* ctx, int64_t cap_rows, int fanout) {
+  if (ctx->relabel_tile_iters) return ctx->relabel_tile_iters;
+  (void)cap_rows;
+  (void)fanout;
+  return kTileItersMax;
 }
 
 static void carve_sample_ws(Arena& ar, const int64_t* cap_nodes, const int64_t* cap_edges, const int32_t* fanouts,
@@ -677,7 +721,7 @@ static void carve_sample_ws(Arena& ar, const int64_t* cap_nodes, const int64_t* 
   for (int32_t h = 0; h < n_hops; ++h) {
     if (cap_edges[h] > max_edges) max_edges = cap_edges[h];
     if (cap_nodes[h] > max_rows) max_rows = cap_nodes[h];
-    status_words += (size_t)tiles_for(cap_nodes[h], fanouts[h]);
+    status_words += (size_t)tiles_for(cap_nodes[h], fanouts[h], kTileItersMin);
   }
   ws->table_entries = table_entries_for(cap_nodes[n_hops]);
   const size_t table_bytes = ws->table_entries * sizeof(HashEntry);
@@ -687,7 +731,7 @@ static void carve_sample_ws(Arena& ar, const int64_t* cap_nodes, const int64_t* 
   unsigned long long* st = reinterpret_cast<unsigned long long*>(region + table_bytes);
   for (int32_t h = 0; h < n_hops; ++h) {
     ws->status[h] = st;
-    st += tiles_for(cap_nodes[h], fanouts[h]);
+    st += tiles_for(cap_nodes[h], fanouts[h], kTileItersMin);
   }
   ws->ticket = reinterpret_cast<unsigned*>(st);
   ws->batch_flag = ws->ticket + DCI_MAX_HOPS;
@@ -698,7 +742,7 @@ static void carve_sample_ws(Arena& ar, const int64_t* cap_nodes, const int64_t* 
     ws->row_cnt[k] = ar.take<int>((size_t)max_rows);
   }
   for (int32_t h = 0; h < n_hops; ++h)
-    ws->stat_part[h] = ar.take<unsigned long long>(kStatPartWords * (size_t)tiles_for(cap_nodes[h], fanouts[h]));
+    ws->stat_part[h] = ar.take<unsigned long long>(kStatPartWords * (size_t)tiles_for(cap_nodes[h], fanouts[h], kTileItersMin));
 }
 
 static void carve_blocks(Arena& ar, const int64_t* cap_nodes, const int64_t* cap_edges, int32_t n_hops,
@@ -744,8 +788,14 @@ static int32_t launch_hop(dci_ctx* ctx, const HopArgs& ha, const RelabelArgs& ra
   DCI_LAUNCH_CHECK(ctx);
   {
     Timed t(ctx, DCI_K_RELABEL);
-    hipLaunchKernelGGL((k_relabel_hop<G>), dim3((unsigned)tiles_for(cap_rows, ha.fanout)), dim3(kBlock), 0, ctx->stream,
-                       ra);
+    const int iters = tile_iters_for(ctx, cap_rows, ha.fanout);
+    const dim3 grid_r((unsigned)tiles_for(cap_rows, ha.fanout, iters));
+    if (iters == 2)
+      hipLaunchKernelGGL((k_relabel_hop<G, 2>), grid_r, dim3(kBlock), 0, ctx->stream, ra);
+    else if (iters == 4)
+      hipLaunchKernelGGL((k_relabel_hop<G, 4>), grid_r, dim3(kBlock), 0, ctx->stream, ra);
+    else
+      hipLaunchKernelGGL((k_relabel_hop<G, 8>), grid_r, dim3(kBlock), 0, ctx->stream, ra);
   }
   DCI_LAUNCH_CHECK(ctx);
   return DCI_OK;
@@ -839,7 +889,7 @@ static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* c
     sf.n_hops = n_hops;
     for (int32_t k = 0; k < DCI_MAX_HOPS; ++k) {
       sf.part[k] = k < n_hops ? ws.stat_part[k] : nullptr;
-      sf.tile_rows[k] = k < n_hops ? (kBlock / group_for(fanouts[k])) * kTileIters : 1;
+      sf.tile_rows[k] = k < n_hops ? (kBlock / group_for(fanouts[k])) * tile_iters_for(ctx, out->cap_rows[k], fanouts[k]) : 1;
     }
     Timed t(ctx, DCI_K_WRITE_SRC);
     hipLaunchKernelGGL(k_write_src, dim3(grid_for_rows(ctx, positions, kBlock)), dim3(kBlock), 0, ctx->stream,
