@@ -85,6 +85,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batches", type=int, default=None, help="batches the single-thread CPU oracle is timed on")
     ap.add_argument("--lanes", type=int, default=4, help="batches in flight in the pipelined regions (0 or 1 = skip them)")
+    ap.add_argument("--lanes-sweep", default=None, metavar="N,N,...",
+                    help="also time the pipelined region with these lane counts and dense-layer kernels 0 and 1 "
+                         "(extras.pipelined_sweep)")
     ap.add_argument("--roofline-kernel", default="auto",
                     help="kernel class of the top-level roofline (default: the one with the largest average launch in "
                          "the kernel pass)")
@@ -153,7 +156,8 @@ def main() -> int:
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
     ws, wn, bs = [dev(a) for a in ws_h], [dev(a) for a in wn_h], [dev(a) for a in b_h]
     ws_arg = None if model == 2 else ws
-    n_lanes = max(1, args.lanes)
+    sweep = [int(v) for v in args.lanes_sweep.split(",")] if args.lanes_sweep else []
+    n_lanes = max([1, args.lanes] + sweep)
     # lane 0 runs on PyTorch's current stream (the single-stream regions); the others on streams of their own,
     # all at the default priority
     lanes = [dci.Lane(g, w.batch_size, w.fanouts, w.dims, stream=torch.cuda.current_stream() if k == 0 else None)
@@ -280,9 +284,7 @@ def main() -> int:
     miss_rows = rows_total - sk["adj_node_hits"]
     link_lines = (sk["lines_bounds"] if indptr.is_pinned() else 0) + (sk["lines_ids"] if indices.is_pinned() else 0)
     link_bytes_sampler = (16 * miss_rows if indptr.is_pinned() else 0) + (8 * sk["adj_edge_misses"] if indices.is_pinned() else 0)
-    table_entries = 1024
-    while table_entries < 2 * blk.cap_nodes[L]:
-        table_entries *= 2
+    table_entries = max(1024, 2 * blk.cap_nodes[L])     # the sampler's per-batch hash table: 8 bytes per entry
 
     def entry(kernel, cls, t_bound_parts, achieved, peak, unit, **more):
         """t_bound_parts: {bound name: seconds that bound allows}; the largest one is the class's bound."""
@@ -411,10 +413,28 @@ def main() -> int:
         pipelined = {"lanes": args.lanes, "linear_kernel": args.pipelined_linear_kernel, "ms_per_step": round(tm * 1e3 / K, 4),
                      "value": round(edges / tm, 1)}
 
+    pipelined_sweep = None
+    if sweep:
+        pipelined_sweep = []
+        for nl in sweep:
+            for lk in (0, 1):
+                for ln in lanes:
+                    ln.ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, lk)
+                run(0, min(K, 2 * nl), nl)
+                torch.cuda.synchronize()
+                tm0 = time.perf_counter()
+                run(0, K, nl)
+                torch.cuda.synchronize()
+                tm = time.perf_counter() - tm0
+                pipelined_sweep.append({"lanes": nl, "linear_kernel": lk, "ms_per_step": round(tm * 1e3 / K, 4)})
+        log(f"[bench] pipelined sweep: {pipelined_sweep}")
+
     # ---- end to end: pre-sampling + fill (measured above) + one pass over all batches, pipelined, wall time
     e2e = None
     if not args.no_end_to_end:
         use = max(1, args.lanes)
+        for ln in lanes:
+            ln.ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, args.pipelined_linear_kernel if use > 1 else args.linear_kernel)
         torch.cuda.synchronize()
         te0 = time.perf_counter()
         run(0, nb, use)
@@ -522,7 +542,7 @@ def main() -> int:
             "kernel_pass_ms_per_step": {k: round(v[0] / K, 4) for k, v in timing_all.items() if v[1] and "+" not in k},
             "rows_copied_by_gather_per_step": round(sk["rows_copied"] / K, 1),
             "rooflines": rooflines, "memory_rates": rates,
-            "preprocess": pre, "pipelined": pipelined, "end_to_end": e2e,
+            "preprocess": pre, "pipelined": pipelined, "pipelined_sweep": pipelined_sweep, "end_to_end": e2e,
         },
         "roofline": roofline, "cpu_baseline": cpu,
     }

@@ -89,9 +89,10 @@ __device__ __forceinline__ unsigned long long uniform_below(unsigned k0, unsigne
 // For an entry that already holds u, key and value move as one word, so a single 64-bit atomic
 // minimum does it; an empty slot is claimed by compare-and-swap.  Values only decrease and keys
 // never change, so a stale read costs a redundant atomic at most.
-__device__ __forceinline__ unsigned table_insert_min(HashEntry* table, unsigned mask, int shift, long long u,
+__device__ __forceinline__ unsigned table_insert_min(HashEntry* table, unsigned entries, long long u,
                                                      unsigned v, bool* candidate) {
-  unsigned slot = (unsigned)(((unsigned long long)u * 0x9E3779B97F4A7C15ull) >> shift) & mask;
+  // multiplicative hash, its high 32 bits scaled to [0, entries): the table need not be a power of two
+  unsigned slot = __umulhi((unsigned)(((unsigned long long)u * 0x9E3779B97F4A7C15ull) >> 32), entries);
   const HashEntry mine = ((HashEntry)u << 32) | v;
   *candidate = false;
   for (;;) {
@@ -110,7 +111,7 @@ __device__ __forceinline__ unsigned table_insert_min(HashEntry* table, unsigned 
       }
       return slot;
     }
-    slot = (slot + 1) & mask;
+    slot = slot + 1 == entries ? 0u : slot + 1;
   }
 }
 
@@ -145,8 +146,7 @@ struct HopArgs {
   int* tmp_slot;
   int* row_cnt;
   HashEntry* table;
-  unsigned mask;
-  int shift;
+  unsigned entries;  // of the table
   unsigned* adj_count;
   unsigned* edge_count;
   // previous hop, whose edges get their local ids at the start of this kernel (hop >= 1)
@@ -299,7 +299,7 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
         if (gl == 0) {
           a.nodes[i] = v;
           bool ignored;
-          (void)table_insert_min(a.table, a.mask, a.shift, v, (unsigned)i, &ignored);
+          (void)table_insert_min(a.table, a.entries, v, (unsigned)i, &ignored);
         }
       } else {
         v = a.nodes[i];
@@ -365,7 +365,7 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
       const long long u = *src;
       const int p = (int)(i * f + gl);
       bool candidate;
-      const unsigned slot = table_insert_min(a.table, a.mask, a.shift, u, kTentative | (unsigned)p, &candidate);
+      const unsigned slot = table_insert_min(a.table, a.entries, u, kTentative | (unsigned)p, &candidate);
       a.tmp_u[p] = u;
       a.tmp_slot[p] = candidate ? (int)slot : -2 - (int)slot;  // the relabel kernel looks at the candidates only
       if (COUNT && a.edge_count) {
@@ -692,8 +692,10 @@ struct SampleWs {
   unsigned long long* stat_part[DCI_MAX_HOPS];  // per hop: two words per relabel tile
 };
 
+// Twice the bound on the batch's distinct nodes (load factor at most one half), even so that the
+// region is a whole number of 16-byte words for the clear.
 static uint64_t table_entries_for(int64_t cap_nodes_last) {
-  uint64_t want = next_pow2((uint64_t)(cap_nodes_last > 0 ? cap_nodes_last : 1) * 2);
+  uint64_t want = (uint64_t)(cap_nodes_last > 0 ? cap_nodes_last : 1) * 2;
   return want < 1024 ? 1024 : want;
 }
 
@@ -813,10 +815,6 @@ static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* c
     rc = fill_bytes(ctx, ws.table, ws.clear_bytes, 0xFFFFFFFFu);
   }
   if (rc != DCI_OK) return rc;
-  const unsigned mask = (unsigned)(ws.table_entries - 1);
-  int log2n = 0;
-  while ((1ull << log2n) < ws.table_entries) ++log2n;
-  const int shift = 64 - log2n;
   long long* counts = reinterpret_cast<long long*>(out->counts);
   long long* nodes = reinterpret_cast<long long*>(out->nodes);
   const bool count = adj_count != nullptr;
@@ -842,8 +840,7 @@ static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* c
     ha.tmp_slot = ws.tmp_slot[h & 1];
     ha.row_cnt = ws.row_cnt[h & 1];
     ha.table = ws.table;
-    ha.mask = mask;
-    ha.shift = shift;
+    ha.entries = (unsigned)ws.table_entries;
     ha.adj_count = adj_count;
     ha.edge_count = edge_count;
     ha.prev_fanout = h > 0 ? fanouts[h - 1] : 1;
