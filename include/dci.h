@@ -155,6 +155,13 @@ int32_t dci_sync(dci_ctx* ctx);
 /* Message of the last failed call on this context (never NULL; "" if none). */
 const char* dci_last_error(const dci_ctx* ctx);
 
+/* The sizes that the last dci_sample_khop / dci_sample_khop_static call on this context needed,
+ * for a caller that got DCI_ERR_CAPACITY and wants to grow its buffers: cap_nodes[DCI_MAX_HOPS + 1]
+ * (entries of blocks.nodes = cap_nodes[n_hops]; rows of block h = cap_nodes[h]), cap_edges[DCI_MAX_HOPS]
+ * and the bytes of temporaries (workspace or static scratch).  Any pointer may be NULL.  The same
+ * numbers come from dci_blocks_bounds and the *_workspace_bytes queries before a call. */
+int32_t dci_last_required(const dci_ctx* ctx, int64_t* cap_nodes, int64_t* cap_edges, size_t* workspace_bytes);
+
 /* Tuning options of a context.  None changes what is computed (the dense-layer kernels differ only
  * in the order of the floating-point sums).  DCI_ERR_INVALID_ARG for an unknown option or value.
  *   DCI_OPT_LINEAR_KERNEL  which dense-layer kernel dci_sage_forward / dci_gnn_forward launch:
@@ -288,8 +295,12 @@ int32_t dci_presample_count(dci_ctx* ctx, const dci_graph* graph, const dci_cach
  *     concatenated in that order, each in its original element order.  adj_remap[v] = slot or -1.
  *     With DCI_FILL_ADJ_ELEMENTS (Algorithm 1 and Fig. 6 as printed) the second branch also
  *     reorders the elements inside every node by their own edge_count descending (ties: original
- *     order), in graph->indices itself - which must therefore be writable mapped memory - so
- *     that position p of a list means the same neighbour in the cache and on the host; and the
+ *     order), in graph->indices itself, so that position p of a list means the same neighbour in
+ *     the cache and on the host.  Because this rewrites an array the graph struct only lends as
+ *     const, the caller must say so: indices_rw must then be the same address as graph->indices,
+ *     writable mapped memory (DCI_ERR_INVALID_ARG otherwise; ignored, and may be NULL, without the
+ *     flag).  Everything else that holds this graph - other contexts, caches filled earlier,
+ *     per-element counters - refers to the old order afterwards.  And the
  *     first node that does not fit as a whole is cached in part when at least 16 bytes are left:
  *     its pointer entry and its floor((left - 8) / 8) leading elements (adj_partial_node /
  *     adj_partial_deg).  A sampled position p of a node with a slot is served by the cache iff
@@ -304,7 +315,7 @@ int32_t dci_presample_count(dci_ctx* ctx, const dci_graph* graph, const dci_cach
 int32_t dci_fill_caches(dci_ctx* ctx, const dci_graph* graph, const uint32_t* feat_count,
                         const uint32_t* adj_count, const uint32_t* edge_count, uint64_t budget_bytes,
                         uint64_t t_sample_ns, uint64_t t_feature_ns, int32_t feat_policy, void* cache_buf,
-                        int32_t* adj_remap, int32_t* feat_remap, dci_cache* out);
+                        int32_t* adj_remap, int32_t* feat_remap, int64_t* indices_rw, dci_cache* out);
 
 /* Cache-aware multi-hop uniform neighbour sampling (Section II-C; Section IV, framework
  * paragraph; hit rule of Section IV-B, third paragraph).

@@ -23,10 +23,21 @@ c = ctypes
 _P = c.c_void_p
 
 
+SANITIZE_FLAGS = ["-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-g", "-O1"]
+
+
 def build(force: bool = False) -> str:
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.run(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-pthread", "-o", _LIB, _SRC], check=True)
     return _LIB
+
+
+def build_sanitized() -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (host code only); load it by
+    pointing DCI_ORACLE_LIB at the result in a process that has the sanitizer runtime preloaded."""
+    out = os.path.join(_HERE, "libdci_oracle_asan.so")
+    subprocess.run(["g++", "-std=c++17", "-fPIC", "-shared", "-pthread"] + SANITIZE_FLAGS + ["-o", out, _SRC], check=True)
+    return out
 
 
 def _load():

@@ -76,6 +76,8 @@ def load_library():
     lib.dci_last_error.argtypes = [P]
     lib.dci_last_error.restype = C.c_char_p
     lib.dci_blocks_bounds.argtypes = [i64, i64, P, i32, P, P]
+    lib.dci_last_required.argtypes = [P, P, P, P]
+    lib.dci_last_required.restype = i32
     lib.dci_sample_workspace_bytes.argtypes = [i64, i64, P, i32]
     lib.dci_sample_workspace_bytes.restype = sz
     lib.dci_fill_workspace_bytes.argtypes = [i64]
@@ -85,7 +87,7 @@ def load_library():
     lib.dci_sage_workspace_bytes.argtypes = [P, i32, P]
     lib.dci_sage_workspace_bytes.restype = sz
     lib.dci_presample_count.argtypes = [P, P, P, P, i64, i32, i64, i64, u64, P, i32, u64, P, P, P, P, P]
-    lib.dci_fill_caches.argtypes = [P, P, P, P, P, u64, u64, u64, i32, P, P, P, P]
+    lib.dci_fill_caches.argtypes = [P, P, P, P, P, u64, u64, u64, i32, P, P, P, P, P]
     lib.dci_sample_khop.argtypes = [P, P, P, P, i64, u64, P, i32, u64, P, P]
     lib.dci_sample_khop_static.argtypes = [P, P, P, P, i64, u64, P, i32, u64, P, P]
     lib.dci_sample_khop_static.restype = i32
@@ -220,6 +222,14 @@ class Context:
     def sync(self):
         self.check(self.lib.dci_sync(self._h))
 
+    def last_required(self):
+        """(cap_nodes[9], cap_edges[8], temporaries in bytes) that the last sampling call on this context needed."""
+        cn = (C.c_int64 * (DCI_MAX_HOPS + 1))()
+        ce = (C.c_int64 * DCI_MAX_HOPS)()
+        ws = C.c_size_t(0)
+        self.check(self.lib.dci_last_required(self._h, cn, ce, C.byref(ws)))
+        return [int(v) for v in cn], [int(v) for v in ce], int(ws.value)
+
     def set_option(self, option: int, value: int):
         self.check(self.lib.dci_set_option(self._h, int(option), int(value)))
 
@@ -347,7 +357,9 @@ def dci_presample_count(ctx: Context, graph: Graph, cache: Optional[Cache], seed
 
 def dci_fill_caches(ctx: Context, graph: Graph, feat_count: torch.Tensor, adj_count: torch.Tensor,
                     budget_bytes: int, t_sample_ns: int, t_feature_ns: int, feat_policy: int = 0,
-                    edge_count: Optional[torch.Tensor] = None) -> Cache:
+                    edge_count: Optional[torch.Tensor] = None, indices_rw: Optional[torch.Tensor] = None) -> Cache:
+    """``indices_rw``: with DCI_FILL_ADJ_ELEMENTS the graph's own ``indices`` tensor, handed over as writable
+    (the fill reorders the lists in place); defaults to ``graph.indices`` when that flag is set."""
     dev = ctx.device
     if feat_policy & DCI_FILL_ADJ_ELEMENTS:
         ctx.ensure_workspace(ctx.lib.dci_fill_elements_workspace_bytes(graph.num_nodes, graph.num_edges))
@@ -362,6 +374,8 @@ def dci_fill_caches(ctx: Context, graph: Graph, feat_count: torch.Tensor, adj_co
     ctx.check(ctx.lib.dci_fill_caches(ctx.handle, C.byref(graph.c), _ptr(feat_count), _ptr(adj_count),
                                       _ptr(edge_count), int(budget_bytes), int(t_sample_ns), int(t_feature_ns),
                                       feat_policy, buf.data_ptr() + off, _ptr(adj_remap), _ptr(feat_remap),
+                                      _ptr(indices_rw if indices_rw is not None else
+                                           (graph.indices if feat_policy & DCI_FILL_ADJ_ELEMENTS else None)),
                                       C.byref(c)))
     cache = Cache(c, (buf, adj_remap, feat_remap))
     cache.adj_remap, cache.feat_remap, cache.buf, cache.buf_offset = adj_remap, feat_remap, buf, off

@@ -173,6 +173,14 @@ int32_t dci_sync(dci_ctx* ctx) {
 
 const char* dci_last_error(const dci_ctx* ctx) { return ctx ? ctx->err : "null context"; }
 
+int32_t dci_last_required(const dci_ctx* ctx, int64_t* cap_nodes, int64_t* cap_edges, size_t* workspace_bytes) {
+  if (!ctx) return DCI_ERR_INVALID_ARG;
+  if (cap_nodes) std::memcpy(cap_nodes, ctx->req_nodes, sizeof(ctx->req_nodes));
+  if (cap_edges) std::memcpy(cap_edges, ctx->req_edges, sizeof(ctx->req_edges));
+  if (workspace_bytes) *workspace_bytes = ctx->req_workspace;
+  return DCI_OK;
+}
+
 int32_t dci_set_option(dci_ctx* ctx, int32_t option, int64_t value) {
   if (!ctx) return DCI_ERR_INVALID_ARG;
   if (option == DCI_OPT_LINEAR_KERNEL) {

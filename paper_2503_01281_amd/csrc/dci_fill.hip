@@ -595,7 +595,7 @@ size_t dci_fill_elements_workspace_bytes(int64_t num_nodes, int64_t n_elements) 
 int32_t dci_fill_caches(dci_ctx* ctx, const dci_graph* g, const uint32_t* feat_count, const uint32_t* adj_count,
                         const uint32_t* edge_count, uint64_t budget_bytes, uint64_t t_sample_ns,
                         uint64_t t_feature_ns, int32_t feat_policy, void* cache_buf, int32_t* adj_remap,
-                        int32_t* feat_remap, dci_cache* out) {
+                        int32_t* feat_remap, int64_t* indices_rw, dci_cache* out) {
   if (!ctx) return DCI_ERR_INVALID_ARG;
   if (!g || !g->indptr || !g->indices || !g->feat || g->num_nodes < 1 || g->num_edges < 0 || g->feat_dim < 1)
     return fail(ctx, DCI_ERR_INVALID_ARG, "graph: null arrays or bad sizes");
@@ -605,6 +605,10 @@ int32_t dci_fill_caches(dci_ctx* ctx, const dci_graph* g, const uint32_t* feat_c
   const bool strict_split = (feat_policy & DCI_FILL_STRICT_SPLIT) != 0;
   const bool elements = (feat_policy & DCI_FILL_ADJ_ELEMENTS) != 0;
   feat_policy &= ~(DCI_FILL_STRICT_SPLIT | DCI_FILL_ADJ_ELEMENTS);
+  if (elements && (indices_rw == nullptr || indices_rw != g->indices))
+    return fail(ctx, DCI_ERR_INVALID_ARG,
+                "fill_caches: the element-granular fill reorders the graph's lists in place; pass graph->indices as "
+                "indices_rw to allow it");
   if (elements && !edge_count)
     return fail(ctx, DCI_ERR_INVALID_ARG, "fill_caches: DCI_FILL_ADJ_ELEMENTS needs edge_count");
   if (feat_policy != DCI_FEAT_POLICY_PAPER_MEAN && feat_policy != DCI_FEAT_POLICY_TOPK)
@@ -797,7 +801,7 @@ int32_t dci_fill_caches(dci_ctx* ctx, const dci_graph* g, const uint32_t* feat_c
         if (seg_bits > 0 && (rc = resort_by_key(ctx, by_count, ew.seg, e_nz, seg_bits, ew.sort, &sorted)) != DCI_OK) return rc;
         const long long n_cached = n_nz < K ? n_nz : K;
         hipLaunchKernelGGL(k_scatter_elems, dim3(grid_1d(ctx, n_nz, wpb)), dim3(kFillBlock), 0, ctx->stream, order, n_nz,
-                           n_cached, indptr, const_cast<long long*>(indices), (const long long*)ew.off,
+                           n_cached, indptr, reinterpret_cast<long long*>(indices_rw), (const long long*)ew.off,
                            (const long long*)ew.vals, sorted, (const long long*)c_indptr, c_indices);
         DCI_LAUNCH_CHECK(ctx);
         first_plain = n_cached;

@@ -28,6 +28,10 @@ struct dci_ctx {
   unsigned* host_flag = nullptr;  // pinned host word (64 bytes): a kernel raises it when a batch had to be voided
   unsigned relabel_spin_limit = 1u << 24;  // DCI_OPT_RELABEL_SPIN_LIMIT
   unsigned test_first_ticket = 0;          // DCI_OPT_TEST_RELABEL_FIRST_TICKET
+  // what the last call that returned DCI_ERR_CAPACITY needed (dci_last_required)
+  int64_t req_nodes[DCI_MAX_HOPS + 1] = {0};
+  int64_t req_edges[DCI_MAX_HOPS] = {0};
+  size_t req_workspace = 0;
   int relabel_tile_iters = 0;  // DCI_OPT_RELABEL_TILE_ITERS: 0 = by frontier size, else 2, 4 or 8 rows per lane group
   int fused_input = 0;    // DCI_OPT_FUSED_INPUT: dci_infer_batches lets the first layer read cached rows in place
   int linear_split = 0;   // DCI_OPT_LINEAR_SPLIT: 0 = by shape, n = at most n workgroups per tile

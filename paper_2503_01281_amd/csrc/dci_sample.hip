@@ -959,6 +959,16 @@ static int32_t sample_khop_in(dci_ctx* ctx, const dci_graph* graph, const dci_ca
   int64_t cap_nodes[DCI_MAX_HOPS + 1], cap_edges[DCI_MAX_HOPS];
   rc = dci_blocks_bounds(graph->num_nodes, n_seeds, fanouts, n_hops, cap_nodes, cap_edges);
   if (rc != DCI_OK) return fail(ctx, rc, "batch bounds reach 2^31");
+  {  // remembered for dci_last_required, should one of the capacity checks below fail
+    Arena probe(nullptr, 0);
+    SampleWs unused;
+    carve_sample_ws(probe, cap_nodes, cap_edges, fanouts, n_hops, &unused);
+    std::memset(ctx->req_nodes, 0, sizeof(ctx->req_nodes));
+    std::memset(ctx->req_edges, 0, sizeof(ctx->req_edges));
+    for (int32_t h = 0; h <= n_hops; ++h) ctx->req_nodes[h] = cap_nodes[h];
+    for (int32_t h = 0; h < n_hops; ++h) ctx->req_edges[h] = cap_edges[h];
+    ctx->req_workspace = probe.off;
+  }
   if (out->cap_nodes < cap_nodes[n_hops])
     return fail(ctx, DCI_ERR_CAPACITY, "blocks.nodes holds %lld entries, %lld needed", (long long)out->cap_nodes,
                 (long long)cap_nodes[n_hops]);

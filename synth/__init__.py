@@ -18,7 +18,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "dci_synth.cpp")
-_LIB = os.path.join(_HERE, "libdci_synth.so")
+_LIB = os.environ.get("DCI_SYNTH_LIB") or os.path.join(_HERE, "libdci_synth.so")  # override: the sanitizer build
 _lib = None
 
 
@@ -28,6 +28,15 @@ def build(force: bool = False) -> str:
         cmd = ["g++", "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread", "-o", _LIB, _SRC]
         subprocess.run(cmd, check=True)
     return _LIB
+
+
+def build_sanitized() -> str:
+    """The generator library with AddressSanitizer and UndefinedBehaviorSanitizer (DCI_SYNTH_LIB selects it)."""
+    out = os.path.join(_HERE, "libdci_synth_asan.so")
+    cmd = ["g++", "-std=c++17", "-fPIC", "-shared", "-pthread", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-g", "-O1", "-o", out, _SRC]
+    subprocess.run(cmd, check=True)
+    return out
 
 
 def _load():

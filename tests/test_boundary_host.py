@@ -73,7 +73,7 @@ def test_null_context_and_missing_gpu_are_errors_not_crashes(lib):
     assert lib.dci_last_error(None) == b"null context"
     assert lib.dci_sample_khop(None, None, None, None, 0, 0, None, 0, 0, None, None) == -1
     assert lib.dci_gather_features(None, None, None, None, 0, None, None, None) == -1
-    assert lib.dci_fill_caches(None, None, None, None, None, 0, 0, 0, 0, None, None, None, None) == -1
+    assert lib.dci_fill_caches(None, None, None, None, None, 0, 0, 0, 0, None, None, None, None, None) == -1
     assert lib.dci_create(None, 0, None, None, 0) == -1
     import torch
     if not torch.cuda.is_available():

@@ -224,6 +224,35 @@ def yelp():
     return _setup("yelp")
 
 
+def test_table3_model_on_amazon_shape():
+    """The sum-aggregate GraphSAGE of Table III on a graph of Amazon's shape (Table II: 1.6 M nodes, 132 M edges,
+    200 features, 107 classes): one whole batch through partly filled caches against the oracle."""
+    e = _setup("amazon")
+    dci, gu, w, ctx, g = e["dci"], e["gu"], e["w"], e["ctx"], e["g"]
+    assert w.dims == (200, 128, 128, 107)
+    fc = torch.zeros(w.num_nodes, dtype=torch.int32, device="cuda")
+    ac = torch.zeros(w.num_nodes, dtype=torch.int32, device="cuda")
+    seeds_dev = gu.dev(e["seeds"])
+    dci.dci_presample_count(ctx, g, None, seeds_dev, w.batch_size, 0, w.n_presample, w.presample_first_batch, w.fanouts,
+                            w.rng_seed, fc, ac)
+    cache = dci.dci_fill_caches(ctx, g, fc, ac, 600_000_000, 3, 7, 0)
+    assert 0 < cache.feat_rows < w.num_nodes and 0 < cache.adj_nodes < w.num_nodes
+    blk = dci.Blocks(ctx, w.num_nodes, w.batch_size, w.fanouts)
+    x = torch.empty(blk.cap_nodes[-1], w.feat_dim, dtype=torch.float32, device="cuda")
+    logits = torch.empty(w.batch_size, w.classes, dtype=torch.float32, device="cuda")
+    ws, wn, bs = ([gu.dev(a) for a in e[k]] for k in ("ws", "wn", "bs"))
+    b = 2
+    sl = slice(b * w.batch_size, (b + 1) * w.batch_size)
+    dci.dci_sample_khop(ctx, g, cache, seeds_dev[sl], b, w.fanouts, w.rng_seed, blk)
+    dci.dci_gather_forward(ctx, g, cache, blk, x, 1, ws, wn, bs, logits)
+    got = gu.blocks_to_host(ctx, blk)
+    want = oracle.sample_khop(e["indptr"], e["indices"], e["seeds"][sl], b, w.fanouts, w.rng_seed)
+    gu.assert_blocks_equal(got, want)
+    ref = oracle.gnn_forward(1, want, oracle.gather(e["feat"], want.nodes), e["ws"], e["wn"], e["bs"])
+    err = float(np.abs(logits.cpu().numpy() - ref).max())
+    assert err <= 1e-4 * max(1.0, float(np.abs(ref).max())), err
+
+
 @pytest.mark.parametrize("model", [1, 2])
 def test_table3_models_on_yelp_shape(yelp, model):
     """The three-layer, hidden-128 sum-aggregate GraphSAGE and averaging GCN (Table III) on a graph of Yelp's shape

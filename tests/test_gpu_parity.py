@@ -117,6 +117,10 @@ def test_sample_rejects_bad_arguments(env):
     with pytest.raises(dci.DciError) as e:
         dci.dci_sample_khop(ctx, g, None, seeds, 0, (5, 10), 4, small)
     assert e.value.code == -2 and "needed" in str(e.value)
+    # the sizes the refused call needed are there to be read
+    cn, ce, ws_need = ctx.last_required()
+    want_n, want_e = dci.blocks_bounds(w.num_nodes, 16, (5, 10))
+    assert cn[:3] == want_n and ce[:2] == want_e and cn[3:] == [0] * 6 and ce[2:] == [0] * 6 and ws_need > 0
 
 
 @pytest.mark.parametrize("F", [64, 100, 602, 63, 1, 256])
@@ -352,6 +356,35 @@ def test_element_granular_fill_needs_edge_counts(env):
     z = torch.zeros(w.num_nodes, dtype=torch.int32, device="cuda")
     with pytest.raises(dci.DciError):
         dci.dci_fill_caches(ctx, g, z, z, 1000, 1, 1, dci.DCI_FILL_ADJ_ELEMENTS)
+    # ... and the caller's word that the graph's lists may be rewritten: indices_rw must be graph.indices itself
+    ec = torch.zeros(w.num_edges, dtype=torch.int32, device="cuda")
+    other = torch.zeros(w.num_edges, dtype=torch.int64, device="cuda")
+    with pytest.raises(dci.DciError) as e:
+        dci.dci_fill_caches(ctx, g, z, z, 1000, 1, 1, dci.DCI_FILL_ADJ_ELEMENTS, edge_count=ec, indices_rw=other)
+    assert e.value.code == -1 and "indices_rw" in str(e.value)
+
+
+def test_same_call_twice_gives_the_same_bytes(env):
+    """Determinism: sampling, gathering and the forward pass of one batch, run twice on one context and once on
+    a second context with another stream, leave byte-identical outputs (the float sums run in a fixed order)."""
+    dci, gu, g, tiny, w = (env[k] for k in ("dci", "gu", "graph", "tiny", "w"))
+    oc = _oracle_caches(tiny, w)
+    cache = gu.upload_cache(oc["adj_remap"], oc["c_indptr"], oc["c_indices"], oc["feat_remap"], oc["feat_cache"])
+    ws, wn, bs = ([gu.dev(a) for a in tiny[k]] for k in ("w_self", "w_neigh", "bias"))
+    seeds = gu.dev(tiny["seeds"][256:512])
+    outs = []
+    for ctx in (env["ctx"], env["ctx"], dci.Context(0, stream=torch.cuda.Stream())):
+        blk = dci.Blocks(ctx, w.num_nodes, w.batch_size, w.fanouts)
+        x = torch.zeros(blk.cap_nodes[-1], w.feat_dim, dtype=torch.float32, device="cuda")
+        logits = torch.zeros(w.batch_size, w.classes, dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()
+        dci.dci_sample_khop(ctx, g, cache, seeds, 1, w.fanouts, w.rng_seed, blk)
+        dci.dci_gather_features(ctx, g, cache, blk.nodes, blk.cap_nodes[-1], x, n_dev=blk.n_input_dev())
+        dci.dci_sage_forward(ctx, blk, x, ws, wn, bs, logits)
+        got = gu.blocks_to_host(ctx, blk)
+        outs.append(b"".join([got["nodes"].tobytes()] + [a.tobytes() for a in got["blk_indptr"] + got["blk_src"]]
+                             + [x.cpu().numpy().tobytes(), logits.cpu().numpy().tobytes()]))
+    assert outs[0] == outs[1] == outs[2]
 
 
 @pytest.mark.parametrize("budget,ts,tf", [(5_636_104, 9, 1), (5_000_000, 1, 9), (3_000_000, 0, 1), (3_000_000, 1, 0)])
