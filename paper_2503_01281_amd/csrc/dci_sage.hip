@@ -51,7 +51,11 @@ struct VecF<1> {
 // REF: the input layer when cached rows are read in place - the row of source s is
 // cache[rowref[s]] if rowref[s] >= 0 (its slot in the feature cache) and x[s] otherwise (a row that
 // missed and was staged there); the destination's own row (GCN) is always in x.
-template <int V, bool REF>
+// CPL: chunks (of V floats) per lane.  CPL >= 1: the lane keeps its CPL partial sums in registers and walks
+// the row's edges once, so that an edge's source index (and cache slot) is looked up once and its row is
+// read in one sweep of the lane group; CPL = 0: rows wider than 8 chunks per lane, walked chunk by chunk.
+// Either way every output element adds its sources in edge order.
+template <int V, bool REF, int CPL>
 __global__ __launch_bounds__(kMeanBlock) void k_sage_mean(const long long* __restrict__ counts, int hop,
                                                           const long long* __restrict__ blk_indptr,
                                                           const int* __restrict__ blk_src,
@@ -84,6 +88,43 @@ __global__ __launch_bounds__(kMeanBlock) void k_sage_mean(const long long* __res
     const long long e0 = blk_indptr[i], e1 = blk_indptr[i + 1];
     const float cnt = (float)(e1 - e0) + (mode == DCI_MODEL_GCN_AVG ? 1.f : 0.f);
     vec_t* dst = reinterpret_cast<vec_t*>(m + i * D);
+    if (CPL > 0) {
+      constexpr int N = CPL > 0 ? CPL : 1;
+      constexpr int EU = N <= 2 ? 4 : 2;  // edges in flight: 8 to 16 loads per lane
+      vec_t acc[N];
+#pragma unroll
+      for (int k = 0; k < N; ++k) {
+        const int c = cl + k * lpr;
+        acc[k] = (mode == DCI_MODEL_GCN_AVG && c < chunks) ? reinterpret_cast<const vec_t*>(x + i * D)[c] : O::zero();
+      }
+      long long e = e0;
+      for (; e + EU <= e1; e += EU) {
+        const vec_t* p[EU];
+#pragma unroll
+        for (int u = 0; u < EU; ++u) p[u] = row(blk_src[e + u]);
+        vec_t v[EU][N];
+#pragma unroll
+        for (int u = 0; u < EU; ++u)
+#pragma unroll
+          for (int k = 0; k < N; ++k)
+            if (cl + k * lpr < chunks) v[u][k] = p[u][cl + k * lpr];
+#pragma unroll
+        for (int u = 0; u < EU; ++u)
+#pragma unroll
+          for (int k = 0; k < N; ++k)
+            if (cl + k * lpr < chunks) O::add(acc[k], v[u][k]);
+      }
+      for (; e < e1; ++e) {
+        const vec_t* p = row(blk_src[e]);
+#pragma unroll
+        for (int k = 0; k < N; ++k)
+          if (cl + k * lpr < chunks) O::add(acc[k], p[cl + k * lpr]);
+      }
+#pragma unroll
+      for (int k = 0; k < N; ++k)
+        if (cl + k * lpr < chunks) dst[cl + k * lpr] = (mode == DCI_MODEL_SAGE_SUM || cnt == 0.f) ? acc[k] : O::div(acc[k], cnt);
+      continue;
+    }
     for (int c = cl; c < chunks; c += lpr) {
       vec_t acc = mode == DCI_MODEL_GCN_AVG ? reinterpret_cast<const vec_t*>(x + i * D)[c] : O::zero();
       long long e = e0;
@@ -909,18 +950,28 @@ static int32_t forward_in(dci_ctx* ctx, const dci_blocks* blocks, const float* x
     Timed timed(ctx, l == 0 ? DCI_K_MEAN_IN : DCI_K_MEAN);
     const bool ref = l == 0 && rowref != nullptr;
     const int* bsrc = (const int*)blocks->blk_src[h];
-#define DCI_MEAN_LAUNCH(VV, RR)                                                                                  \
-  hipLaunchKernelGGL((k_sage_mean<VV, RR>), dim3((int)mb), dim3(kMeanBlock), 0, ctx->stream, counts, h, bi, bsrc, x, \
-                     D, lpr_log2, ws.m, model, (const int*)rowref, feat_cache)
+#define DCI_MEAN_LAUNCH(VV, RR, CC)                                                                                  \
+  hipLaunchKernelGGL((k_sage_mean<VV, RR, CC>), dim3((int)mb), dim3(kMeanBlock), 0, ctx->stream, counts, h, bi, bsrc, \
+                     x, D, lpr_log2, ws.m, model, (const int*)rowref, feat_cache)
+#define DCI_MEAN_BY_CPL(VV, RR)                         \
+  do {                                                  \
+    if (cpl <= 1) DCI_MEAN_LAUNCH(VV, RR, 1);           \
+    else if (cpl <= 2) DCI_MEAN_LAUNCH(VV, RR, 2);      \
+    else if (cpl <= 4) DCI_MEAN_LAUNCH(VV, RR, 4);      \
+    else if (cpl <= 8) DCI_MEAN_LAUNCH(VV, RR, 8);      \
+    else DCI_MEAN_LAUNCH(VV, RR, 0);                    \
+  } while (0)
+    const int cpl = (chunks + (1 << lpr_log2) - 1) >> lpr_log2;  // chunks per lane
     if (ref) {
-      if (V == 4) DCI_MEAN_LAUNCH(4, true);
-      else if (V == 2) DCI_MEAN_LAUNCH(2, true);
-      else DCI_MEAN_LAUNCH(1, true);
+      if (V == 4) DCI_MEAN_BY_CPL(4, true);
+      else if (V == 2) DCI_MEAN_BY_CPL(2, true);
+      else DCI_MEAN_BY_CPL(1, true);
     } else {
-      if (V == 4) DCI_MEAN_LAUNCH(4, false);
-      else if (V == 2) DCI_MEAN_LAUNCH(2, false);
-      else DCI_MEAN_LAUNCH(1, false);
+      if (V == 4) DCI_MEAN_BY_CPL(4, false);
+      else if (V == 2) DCI_MEAN_BY_CPL(2, false);
+      else DCI_MEAN_BY_CPL(1, false);
     }
+#undef DCI_MEAN_BY_CPL
 #undef DCI_MEAN_LAUNCH
     }
     DCI_LAUNCH_CHECK(ctx);
