@@ -125,7 +125,8 @@ __global__ __launch_bounds__(kGatherBlock) void k_gather(const long long* __rest
 // The selective gather of dci_gather_forward: every row's cache slot (or -1) is noted in rowref[i]; the
 // row itself is copied only if it lies below *n_dense_dev (the rows of F_{L-1}, which the dense layer reads
 // as a matrix) or misses (so that it crosses the host link once, not once per edge that uses it).
-// The first n_dense_blocks workgroups copy the rows of F_{L-1} like the plain gather.  The others go over the
+// Even workgroups copy the rows of F_{L-1} like the plain gather (interleaved with the others so that the
+// two kinds of work run side by side instead of one after the other).  Odd workgroups go over the
 // rest with one lane per row - 64 dependent id -> remap chains in flight per wavefront instead of one per
 // lane group, because most of these rows are only looked up - and the rows among them that missed are then
 // moved by the whole wavefront, up to four rows' loads in flight at a time.
@@ -138,8 +139,7 @@ __global__ __launch_bounds__(kGatherBlock) void k_gather_select(const long long*
                                                                 float* __restrict__ out,
                                                                 unsigned long long* __restrict__ partials,
                                                                 int* __restrict__ rowref,
-                                                                const long long* __restrict__ n_dense_dev,
-                                                                int n_dense_blocks) {
+                                                                const long long* __restrict__ n_dense_dev) {
   typedef typename GVec<V>::reg reg_t;
   typedef typename GVec<V>::mem mem_t;
   long long n = *n_dev;
@@ -147,13 +147,14 @@ __global__ __launch_bounds__(kGatherBlock) void k_gather_select(const long long*
   long long n_dense = *n_dense_dev;
   if (n_dense > n) n_dense = n;
   GatherCounts cnt;
-  if ((int)blockIdx.x < n_dense_blocks) {
-    copy_rows<V>(ids, n_dense, remap, cache, feat, F, lpr_log2, out, rowref, (int)blockIdx.x, n_dense_blocks, cnt);
+  const int half = (int)gridDim.x >> 1, which = (int)blockIdx.x >> 1;  // the grid is even
+  if (((int)blockIdx.x & 1) == 0) {
+    copy_rows<V>(ids, n_dense, remap, cache, feat, F, lpr_log2, out, rowref, which, half, cnt);
   } else {
     const int chunks = F / V, tail = F % V;
     const int lane = lane_id();
-    const long long first = n_dense + (long long)((int)blockIdx.x - n_dense_blocks) * kGatherBlock;
-    const long long stride = (long long)((int)gridDim.x - n_dense_blocks) * kGatherBlock;
+    const long long first = n_dense + (long long)which * kGatherBlock;
+    const long long stride = (long long)half * kGatherBlock;
     for (long long base = first; base < n; base += stride) {
       const long long i = base + threadIdx.x;
       const bool valid = i < n;
@@ -270,21 +271,21 @@ int32_t gather_launch(dci_ctx* ctx, const dci_graph* g, const dci_cache* cache, 
     unsigned long long* st = stats ? reinterpret_cast<unsigned long long*>(partials_buf) : nullptr;
     if (rowref) {
       if (!n_dev || !n_dense_dev) return fail(ctx, DCI_ERR_INVALID_ARG, "selective gather needs device-side row counts");
-      // half of the grid at most for the dense rows, the rest for the look-ups (both parts walk their rows
-      // with a grid stride, so any split is correct)
-      int64_t dense_blocks = blocks_for(n_dense_max, rows_per_block);
-      if (dense_blocks > cap / 2) dense_blocks = cap / 2;
-      const int64_t look_blocks = blocks_for(n_max, kGatherBlock) > cap / 2 ? cap / 2 : blocks_for(n_max, kGatherBlock);
-      blocks = dense_blocks + look_blocks;
+      // half of the grid for the dense rows, half for the look-ups (both halves walk their rows with a grid
+      // stride, so any size is correct)
+      int64_t half = blocks_for(n_dense_max, rows_per_block);
+      if (blocks_for(n_max, kGatherBlock) > half) half = blocks_for(n_max, kGatherBlock);
+      if (half > cap / 2) half = cap / 2;
+      blocks = 2 * half;
       if (V == 4)
         hipLaunchKernelGGL((k_gather_select<4>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_,
-                           (long long)n_max, nd_, remap, fcache, g->feat, F, lpr_log2, out, st, rowref, dn_, (int)dense_blocks);
+                           (long long)n_max, nd_, remap, fcache, g->feat, F, lpr_log2, out, st, rowref, dn_);
       else if (V == 2)
         hipLaunchKernelGGL((k_gather_select<2>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_,
-                           (long long)n_max, nd_, remap, fcache, g->feat, F, lpr_log2, out, st, rowref, dn_, (int)dense_blocks);
+                           (long long)n_max, nd_, remap, fcache, g->feat, F, lpr_log2, out, st, rowref, dn_);
       else
         hipLaunchKernelGGL((k_gather_select<1>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_,
-                           (long long)n_max, nd_, remap, fcache, g->feat, F, lpr_log2, out, st, rowref, dn_, (int)dense_blocks);
+                           (long long)n_max, nd_, remap, fcache, g->feat, F, lpr_log2, out, st, rowref, dn_);
     } else if (V == 4)
       hipLaunchKernelGGL((k_gather<4>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_, (long long)n_max,
                          nd_, remap, fcache, g->feat, F, lpr_log2, out, st);

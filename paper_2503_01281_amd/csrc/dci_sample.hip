@@ -116,7 +116,9 @@ __device__ __forceinline__ unsigned table_insert_min(HashEntry* table, unsigned 
 }
 
 // tmp_slot encoding: s >= 0 a table slot whose value this edge may still own; -1 no edge at this
-// position; s <= -2 the slot -2 - s of an edge that cannot be its node's first appearance.
+// position; kSlotDone an edge whose local id the relabel kernel has already written (it was its node's first
+// appearance); any other s <= -2 the slot -2 - s of an edge that cannot be its node's first appearance.
+constexpr int kSlotDone = (int)0x80000000;
 __device__ __forceinline__ unsigned slot_of(int s) { return (unsigned)(s >= 0 ? s : -2 - s); }
 
 template <int G>
@@ -171,7 +173,10 @@ __device__ __forceinline__ void write_block_sources(long long n_rows, int fanout
   for (long long q = block * (long long)blockDim.x + threadIdx.x; q < total; q += (long long)n_blocks * blockDim.x) {
     const long long i = q / fanout;
     const int s = (int)(q - i * fanout);
-    if (s < (row_cnt[i] & kRowCntMask)) blk_src[blk_indptr[i] + s] = (int)entry_val(table, slot_of(tmp_slot[q]));
+    if (s < (row_cnt[i] & kRowCntMask)) {
+      const int ts = tmp_slot[q];
+      if (ts != kSlotDone) blk_src[blk_indptr[i] + s] = (int)entry_val(table, slot_of(ts));
+    }
   }
 }
 
@@ -412,10 +417,11 @@ struct RelabelArgs {
   int fanout;
   const int* row_cnt;
   const long long* tmp_u;
-  const int* tmp_slot;
+  int* tmp_slot;  // read; the first appearances are marked kSlotDone
   HashEntry* table;
   long long* nodes;
   long long* blk_indptr;
+  int* blk_src;   // the first appearances' local ids are written here, the other edges' by the next kernel
   unsigned long long* status;  // one word per tile, filled with ones beforehand
   unsigned* ticket;            // filled with ones beforehand: the first ticket is 0xFFFFFFFF + 1 = 0
   unsigned long long* stat_part;  // [kStatPartWords * tiles] per tile, or nullptr
@@ -642,6 +648,12 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
     if (new_id[it] >= 0) {
       a.nodes[new_id[it]] = new_u[it];
       entry_set_val(a.table, (unsigned)slot[it], (unsigned)new_id[it]);
+      // this edge's local id is known right here: write it (the row's edges sit at its sampled slots
+      // 0 .. c-1, and s_c holds the row's inclusive edge count within the tile), and spare the edge-id pass
+      // the table look-up
+      const int r = it * kGroups + grp;
+      a.blk_src[ec + s_c[r] - (raw[it] & kRowCntMask) + gl] = (int)new_id[it];
+      a.tmp_slot[(row0 + r) * f + gl] = kSlotDone;
     }
 
   if (tid == 0) {
@@ -861,6 +873,7 @@ static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* c
     ra.table = ws.table;
     ra.nodes = nodes;
     ra.blk_indptr = reinterpret_cast<long long*>(out->blk_indptr[h]);
+    ra.blk_src = out->blk_src[h];
     ra.status = ws.status[h];
     ra.ticket = ws.ticket + h;
     ra.stat_part = stats ? ws.stat_part[h] : nullptr;
