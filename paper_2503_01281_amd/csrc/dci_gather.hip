@@ -125,8 +125,9 @@ __global__ __launch_bounds__(kGatherBlock) void k_gather(const long long* __rest
 // The selective gather of dci_gather_forward: every row's cache slot (or -1) is noted in rowref[i]; the
 // row itself is copied only if it lies below *n_dense_dev (the rows of F_{L-1}, which the dense layer reads
 // as a matrix) or misses (so that it crosses the host link once, not once per edge that uses it).
-// Even workgroups copy the rows of F_{L-1} like the plain gather (interleaved with the others so that the
-// two kinds of work run side by side instead of one after the other).  Odd workgroups go over the
+// Some workgroups copy the rows of F_{L-1} like the plain gather; the others (interleaved with them, so
+// that the two kinds of work run side by side instead of one after the other; the shares follow the bytes
+// each kind moves for this batch's sizes) go over the
 // rest with one lane per row - 64 dependent id -> remap chains in flight per wavefront instead of one per
 // lane group, because most of these rows are only looked up - and the rows among them that missed are then
 // moved by the whole wavefront, up to four rows' loads in flight at a time.
@@ -147,14 +148,27 @@ __global__ __launch_bounds__(kGatherBlock) void k_gather_select(const long long*
   long long n_dense = *n_dense_dev;
   if (n_dense > n) n_dense = n;
   GatherCounts cnt;
-  const int half = (int)gridDim.x >> 1, which = (int)blockIdx.x >> 1;  // the grid is even
-  if (((int)blockIdx.x & 1) == 0) {
-    copy_rows<V>(ids, n_dense, remap, cache, feat, F, lpr_log2, out, rowref, which, half, cnt);
+  // Workgroup b copies dense rows iff floor((b+1) nd / G) != floor(b nd / G): nd of the G workgroups, evenly
+  // spread.  nd follows the work: 8F bytes per dense row - but no less than 2 KB, since narrow rows are bound by
+  // the latency of their id -> slot -> row chain, not by their bytes - against about 160 bytes per looked-up row
+  // (id, a sector of the remap, the slot note).
+  const long long G = (long long)gridDim.x, b = (long long)blockIdx.x;
+  long long nd;
+  {
+    const double dense_bytes = (double)n_dense * (8.0 * F > 2048.0 ? 8.0 * F : 2048.0), look_bytes = (double)(n - n_dense) * 160.0;
+    nd = (long long)((double)G * dense_bytes / (dense_bytes + look_bytes + 1.0) + 0.5);
+    if (nd < 1) nd = 1;
+    if (nd > G - 1) nd = G - 1;
+  }
+  const long long before = b * nd / G;  // dense workgroups among 0 .. b-1
+  if ((b + 1) * nd / G != before) {
+    copy_rows<V>(ids, n_dense, remap, cache, feat, F, lpr_log2, out, rowref, (int)before, (int)nd, cnt);
   } else {
+    const long long q = b - before, quarter = G - nd;  // this workgroup's index among the look-up ones, and their number
     const int chunks = F / V, tail = F % V;
     const int lane = lane_id();
-    const long long first = n_dense + (long long)which * kGatherBlock;
-    const long long stride = (long long)half * kGatherBlock;
+    const long long first = n_dense + (long long)q * kGatherBlock;
+    const long long stride = (long long)quarter * kGatherBlock;
     for (long long base = first; base < n; base += stride) {
       const long long i = base + threadIdx.x;
       const bool valid = i < n;
@@ -271,12 +285,11 @@ int32_t gather_launch(dci_ctx* ctx, const dci_graph* g, const dci_cache* cache, 
     unsigned long long* st = stats ? reinterpret_cast<unsigned long long*>(partials_buf) : nullptr;
     if (rowref) {
       if (!n_dev || !n_dense_dev) return fail(ctx, DCI_ERR_INVALID_ARG, "selective gather needs device-side row counts");
-      // half of the grid for the dense rows, half for the look-ups (both halves walk their rows with a grid
-      // stride, so any size is correct)
-      int64_t half = blocks_for(n_dense_max, rows_per_block);
-      if (blocks_for(n_max, kGatherBlock) > half) half = blocks_for(n_max, kGatherBlock);
-      if (half > cap / 2) half = cap / 2;
-      blocks = 2 * half;
+      // workgroups for both kinds of work; the kernel shares them out from the batch's own sizes (both parts
+      // walk their rows with a grid stride, so any split is correct)
+      blocks = blocks_for(n_dense_max, rows_per_block) + blocks_for(n_max, kGatherBlock);
+      if (blocks > cap) blocks = cap;
+      if (blocks < 2) blocks = 2;
       if (V == 4)
         hipLaunchKernelGGL((k_gather_select<4>), dim3((int)blocks), dim3(kGatherBlock), 0, ctx->stream, ids_,
                            (long long)n_max, nd_, remap, fcache, g->feat, F, lpr_log2, out, st, rowref, dn_);

@@ -89,14 +89,20 @@ __global__ __launch_bounds__(kMeanBlock) void k_sage_mean(const long long* __res
     const float cnt = (float)(e1 - e0) + (mode == DCI_MODEL_GCN_AVG ? 1.f : 0.f);
     vec_t* dst = reinterpret_cast<vec_t*>(m + i * D);
     if (CPL > 0) {
+      // The launch picks CPL = ceil(chunks / lanes per row) exactly, so only a lane's last chunk can lie beyond
+      // the row; such a lane reads the row's last chunk instead (in bounds, discarded), which keeps the loop
+      // free of predicates.
       constexpr int N = CPL > 0 ? CPL : 1;
       constexpr int EU = N <= 2 ? 4 : 2;  // edges in flight: 8 to 16 loads per lane
+      const bool last_ok = cl + (N - 1) * lpr < chunks;
+      int col[N];
+#pragma unroll
+      for (int k = 0; k < N; ++k) col[k] = cl + k * lpr;
+      if (!last_ok) col[N - 1] = chunks - 1;
       vec_t acc[N];
 #pragma unroll
-      for (int k = 0; k < N; ++k) {
-        const int c = cl + k * lpr;
-        acc[k] = (mode == DCI_MODEL_GCN_AVG && c < chunks) ? reinterpret_cast<const vec_t*>(x + i * D)[c] : O::zero();
-      }
+      for (int k = 0; k < N; ++k)
+        acc[k] = mode == DCI_MODEL_GCN_AVG ? reinterpret_cast<const vec_t*>(x + i * D)[col[k]] : O::zero();
       long long e = e0;
       for (; e + EU <= e1; e += EU) {
         const vec_t* p[EU];
@@ -106,23 +112,20 @@ __global__ __launch_bounds__(kMeanBlock) void k_sage_mean(const long long* __res
 #pragma unroll
         for (int u = 0; u < EU; ++u)
 #pragma unroll
-          for (int k = 0; k < N; ++k)
-            if (cl + k * lpr < chunks) v[u][k] = p[u][cl + k * lpr];
+          for (int k = 0; k < N; ++k) v[u][k] = p[u][col[k]];
 #pragma unroll
         for (int u = 0; u < EU; ++u)
 #pragma unroll
-          for (int k = 0; k < N; ++k)
-            if (cl + k * lpr < chunks) O::add(acc[k], v[u][k]);
+          for (int k = 0; k < N; ++k) O::add(acc[k], v[u][k]);
       }
       for (; e < e1; ++e) {
         const vec_t* p = row(blk_src[e]);
 #pragma unroll
-        for (int k = 0; k < N; ++k)
-          if (cl + k * lpr < chunks) O::add(acc[k], p[cl + k * lpr]);
+        for (int k = 0; k < N; ++k) O::add(acc[k], p[col[k]]);
       }
 #pragma unroll
       for (int k = 0; k < N; ++k)
-        if (cl + k * lpr < chunks) dst[cl + k * lpr] = (mode == DCI_MODEL_SAGE_SUM || cnt == 0.f) ? acc[k] : O::div(acc[k], cnt);
+        if (k < N - 1 || last_ok) dst[col[k]] = (mode == DCI_MODEL_SAGE_SUM || cnt == 0.f) ? acc[k] : O::div(acc[k], cnt);
       continue;
     }
     for (int c = cl; c < chunks; c += lpr) {
@@ -955,11 +958,17 @@ static int32_t forward_in(dci_ctx* ctx, const dci_blocks* blocks, const float* x
                      x, D, lpr_log2, ws.m, model, (const int*)rowref, feat_cache)
 #define DCI_MEAN_BY_CPL(VV, RR)                         \
   do {                                                  \
-    if (cpl <= 1) DCI_MEAN_LAUNCH(VV, RR, 1);           \
-    else if (cpl <= 2) DCI_MEAN_LAUNCH(VV, RR, 2);      \
-    else if (cpl <= 4) DCI_MEAN_LAUNCH(VV, RR, 4);      \
-    else if (cpl <= 8) DCI_MEAN_LAUNCH(VV, RR, 8);      \
-    else DCI_MEAN_LAUNCH(VV, RR, 0);                    \
+    switch (cpl) {                                      \
+      case 1: DCI_MEAN_LAUNCH(VV, RR, 1); break;        \
+      case 2: DCI_MEAN_LAUNCH(VV, RR, 2); break;        \
+      case 3: DCI_MEAN_LAUNCH(VV, RR, 3); break;        \
+      case 4: DCI_MEAN_LAUNCH(VV, RR, 4); break;        \
+      case 5: DCI_MEAN_LAUNCH(VV, RR, 5); break;        \
+      case 6: DCI_MEAN_LAUNCH(VV, RR, 6); break;        \
+      case 7: DCI_MEAN_LAUNCH(VV, RR, 7); break;        \
+      case 8: DCI_MEAN_LAUNCH(VV, RR, 8); break;        \
+      default: DCI_MEAN_LAUNCH(VV, RR, 0); break;       \
+    }                                                   \
   } while (0)
     const int cpl = (chunks + (1 << lpr_log2) - 1) >> lpr_log2;  // chunks per lane
     if (ref) {
