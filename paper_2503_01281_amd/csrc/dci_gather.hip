@@ -130,7 +130,7 @@ __global__ __launch_bounds__(kGatherBlock) void k_gather(const long long* __rest
 // each kind moves for this batch's sizes) go over the
 // rest with one lane per row - 64 dependent id -> remap chains in flight per wavefront instead of one per
 // lane group, because most of these rows are only looked up - and the rows among them that missed are then
-// moved by the whole wavefront, up to four rows' loads in flight at a time.
+// listed in LDS and copied a lane group per row, two rows per group in flight.
 template <int V>
 __global__ __launch_bounds__(kGatherBlock) void k_gather_select(const long long* __restrict__ ids, long long n_max,
                                                                 const long long* __restrict__ n_dev,
@@ -164,12 +164,18 @@ __global__ __launch_bounds__(kGatherBlock) void k_gather_select(const long long*
   if ((b + 1) * nd / G != before) {
     copy_rows<V>(ids, n_dense, remap, cache, feat, F, lpr_log2, out, rowref, (int)before, (int)nd, cnt);
   } else {
-    const long long q = b - before, quarter = G - nd;  // this workgroup's index among the look-up ones, and their number
+    const long long q = b - before, n_look = G - nd;  // this workgroup's index among the look-up ones, and their number
+    // 256 rows per round: every lane looks one row up; the rows that missed are listed in LDS and then copied
+    // like the dense ones, a lane group per row, so that narrow rows keep all lanes busy.
+    __shared__ int s_list[kGatherBlock];
+    __shared__ int s_count;
     const int chunks = F / V, tail = F % V;
-    const int lane = lane_id();
-    const long long first = n_dense + (long long)q * kGatherBlock;
-    const long long stride = (long long)quarter * kGatherBlock;
-    for (long long base = first; base < n; base += stride) {
+    const int lpr = 1 << lpr_log2;
+    const int rows_per_round = kGatherBlock >> lpr_log2;
+    const int sub = (int)threadIdx.x >> lpr_log2, cl = (int)threadIdx.x & (lpr - 1);
+    for (long long base = n_dense + q * kGatherBlock; base < n; base += n_look * kGatherBlock) {
+      if (threadIdx.x == 0) s_count = 0;
+      __syncthreads();
       const long long i = base + threadIdx.x;
       const bool valid = i < n;
       const long long id = valid ? ids[i] : 0;
@@ -178,38 +184,33 @@ __global__ __launch_bounds__(kGatherBlock) void k_gather_select(const long long*
         rowref[i] = r;
         if (r >= 0) ++cnt.hits; else ++cnt.misses;
       }
-      const bool need = valid && r < 0;
-      if (need) ++cnt.copied;
-      const float* my_src = feat + id * F;
-      unsigned long long todo = __ballot(need);
-      const long long wave_row0 = i - lane;  // row of lane 0 of this wavefront
-      while (todo != 0ull) {
-        int j[4];
-        const float* src[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          j[u] = todo ? (int)__ffsll((long long)todo) - 1 : -1;
-          if (todo) todo &= todo - 1ull;
-          const int from = j[u] >= 0 ? j[u] : 0;
-          const unsigned long long p = (unsigned long long)reinterpret_cast<uintptr_t>(my_src);
-          const unsigned lo = (unsigned)__shfl((int)(unsigned)p, from, kWave), hi = (unsigned)__shfl((int)(unsigned)(p >> 32), from, kWave);
-          src[u] = reinterpret_cast<const float*>((uintptr_t)(((unsigned long long)hi << 32) | lo));
+      if (valid && r < 0) {
+        ++cnt.copied;
+        s_list[atomicAdd(&s_count, 1)] = (int)threadIdx.x;  // the order within the list does not matter
+      }
+      __syncthreads();
+      const int n_miss = s_count;
+      for (int k0 = sub; k0 < n_miss; k0 += 2 * rows_per_round) {
+        // two rows per lane group in flight
+        const int k1 = k0 + rows_per_round;
+        const long long ia = base + s_list[k0], ib = k1 < n_miss ? base + s_list[k1] : ia;
+        const float* sa = feat + ids[ia] * F;
+        const float* sb = feat + ids[ib] * F;
+        float* da = out + ia * F;
+        float* db = out + ib * F;
+        for (int c0 = cl; c0 < chunks; c0 += lpr) {
+          const reg_t va = reinterpret_cast<const mem_t*>(sa)[c0];
+          const reg_t vb = reinterpret_cast<const mem_t*>(sb)[c0];
+          reinterpret_cast<mem_t*>(da)[c0] = va;
+          if (k1 < n_miss) reinterpret_cast<mem_t*>(db)[c0] = vb;
         }
-        for (int c0 = lane; c0 < chunks; c0 += kWave) {
-          reg_t v[4];
-#pragma unroll
-          for (int u = 0; u < 4; ++u)
-            if (j[u] >= 0) v[u] = reinterpret_cast<const mem_t*>(src[u])[c0];
-#pragma unroll
-          for (int u = 0; u < 4; ++u)
-            if (j[u] >= 0) reinterpret_cast<mem_t*>(out + (wave_row0 + j[u]) * F)[c0] = v[u];
-        }
-        if (lane < tail) {
-#pragma unroll
-          for (int u = 0; u < 4; ++u)
-            if (j[u] >= 0) out[(wave_row0 + j[u]) * F + V * chunks + lane] = src[u][V * chunks + lane];
+        if (cl < tail) {
+          const float ta = sa[V * chunks + cl], tb = sb[V * chunks + cl];
+          da[V * chunks + cl] = ta;
+          if (k1 < n_miss) db[V * chunks + cl] = tb;
         }
       }
+      __syncthreads();  // the list is rewritten in the next round
     }
   }
   if (partials) store_partials(cnt, partials);
