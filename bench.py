@@ -195,6 +195,10 @@ def main() -> int:
             cache = dci.dci_fill_caches(ctx, g, fc, ac, w.budget_bytes, ts_used, tf_used, fill_flags, edge_count=ec)
         del ec
         t2 = time.time()
+        if args.adj_elements and indices_host is not indices:
+            # the element-granular fill reordered the lists in place (in HBM here): the oracle must see the same lists
+            for lo_ in range(0, w.num_edges, 1 << 27):
+                indices_host[lo_:lo_ + (1 << 27)].copy_(indices[lo_:lo_ + (1 << 27)])
         pre = dict(presample_s=round(t1 - t0, 4), fill_s=round(t2 - t1, 4), t_sample_ns=ts, t_feature_ns=tf,
                    split_times="measured" if not args.split_times else args.split_times,
                    cap_adj_bytes=int(cache.cap_adj_bytes), cap_feat_bytes=int(cache.cap_feat_bytes),
