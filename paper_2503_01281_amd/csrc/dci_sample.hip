@@ -15,9 +15,13 @@
 //   k_relabel_hop - a lane is the "first appearance" of its node iff the table still holds its own
 //                   padded position.  Counts them per row, prefix-sums edge counts and first
 //                   appearances over all rows (chained scan with decoupled look-back), appends the
-//                   first appearances to the frontier in (row, slot) order and publishes their
-//                   local ids in the table.
-//   k_write_src   - the last hop's edge ids, and the batch sizes for the host.
+//                   first appearances to the frontier in (row, slot) order, publishes their
+//                   local ids in the table and writes them as those edges' ids.
+//   k_write_src   - the last hop's remaining edge ids, the batch sizes for the host, and the totals of
+//                   the batch's statistics.
+// Should a tile of the scan ever give up waiting for its predecessors, the batch is voided: a status
+// word makes the batch's remaining kernels return at once, k_write_src zeroes the batch's sizes and
+// raises the context's host flag, and the next dci_sync reports it.
 // A table word holds the node id in its high half and, in its low half, either a final local id
 // (below 2^31) or 2^31 + the smallest padded position seen so far, so one atomic minimum serves
 // both "already in the frontier" and "who came first".

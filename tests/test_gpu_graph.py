@@ -13,7 +13,8 @@ import synth
 pytestmark = pytest.mark.gpu
 
 
-def test_step_replays_from_a_hip_graph(tiny):
+@pytest.mark.parametrize("variant", ["workspace", "static_scratch_and_rows_in_place"])
+def test_step_replays_from_a_hip_graph(tiny, variant):
     import paper_2503_01281_amd as dci
     from tests import gpu_util as gu
     w = tiny["w"]
@@ -35,9 +36,15 @@ def test_step_replays_from_a_hip_graph(tiny):
         batch_index = 5
 
         def step():
-            dci.dci_sample_khop(ctx, g, cache, seeds, batch_index, w.fanouts, w.rng_seed, blk)
-            dci.dci_gather_features(ctx, g, cache, blk.nodes, blk.cap_nodes[-1], x, n_dev=blk.n_input_dev())
-            dci.dci_sage_forward(ctx, blk, x, ws, wn, bs, logits)
+            if variant == "workspace":
+                dci.dci_sample_khop(ctx, g, cache, seeds, batch_index, w.fanouts, w.rng_seed, blk)
+                dci.dci_gather_features(ctx, g, cache, blk.nodes, blk.cap_nodes[-1], x, n_dev=blk.n_input_dev())
+                dci.dci_sage_forward(ctx, blk, x, ws, wn, bs, logits)
+            else:
+                # the sampler that allocates nothing (temporaries in the library's static device array), then the
+                # gather + forward that reads cached rows in place: x then holds only missed rows and those of F_{L-1}
+                dci.dci_sample_khop_static(ctx, g, cache, seeds, batch_index, w.fanouts, w.rng_seed, blk)
+                dci.dci_gather_forward(ctx, g, cache, blk, x, dci.DCI_MODEL_SAGE_MEAN, ws, wn, bs, logits)
 
         def snapshot():
             ctx.sync()
@@ -45,7 +52,7 @@ def test_step_replays_from_a_hip_graph(tiny):
             return got, x[:got["n_nodes"][-1]].cpu().numpy().copy(), logits.cpu().numpy().copy()
 
         def scribble():
-            blk.nodes.fill_(-1); blk.counts.fill_(-1); x.fill_(float("nan")); logits.fill_(float("nan"))
+            blk.nodes.fill_(-1); blk.counts.fill_(-1); x.fill_(0.5); logits.fill_(float("nan"))
             for t in blk.blk_src:
                 t.fill_(-1)
 
