@@ -368,19 +368,20 @@ def main() -> int:
     roof_key = {"write_src": "relabel"}.get(dominant, dominant)
 
     # ---- timed region: exactly K steps, one stream, only the dominant class bracketed
+    # (statistics are optional instrumentation and are left out here: the hit rates and the edge count of these
+    # same K batches come from the kernel pass)
     ctx.timing_enable([dominant])
-    stats_t = torch.zeros(dci.STATS_WORDS, dtype=torch.int64, device="cuda")
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     ev[0].record()
-    run(0, K, 1, stats_t)
+    run(0, K, 1, None)
     ev[1].record()
     torch.cuda.synchronize()
     wall_s = time.perf_counter() - t0
     dom_ms, dom_n = ctx.timing_read()[dominant]
     ctx.timing_enable([])
-    st = {k: int(v) for k, v in zip(dci.STAT.keys(), stats_t.cpu().numpy()[:len(dci.STAT)])}
+    st = sk
     edges = st["edges_sampled"]
     rows = st["feat_hits"] + st["feat_misses"]
     value = edges / wall_s
