@@ -165,14 +165,19 @@ int32_t dci_last_required(const dci_ctx* ctx, int64_t* cap_nodes, int64_t* cap_e
 /* Tuning options of a context.  None changes what is computed (the dense-layer kernels differ only
  * in the order of the floating-point sums).  DCI_ERR_INVALID_ARG for an unknown option or value.
  *   DCI_OPT_LINEAR_KERNEL  which dense-layer kernel dci_sage_forward / dci_gnn_forward launch:
- *       0  by shape (default): the wide kernel (128-column tiles, one workgroup per compute unit)
+ *       0  by shape (default): the kernel that keeps the weights in registers when the whole contraction
+ *          is at most 256 long (two operands of up to 128 columns, or GCN's one of up to 256), the input width
+ *          a multiple of 4, the output width a multiple of 256 and the layer at least 98304 rows tall by
+ *          capacity; else the wide kernel (128-column tiles, one workgroup per compute unit)
  *          when the layer is at least 16384 rows tall by capacity, its input width is even and
  *          at least 192, its output width is a multiple of 128 and the operands are suitably
  *          aligned; else a 64x64 tile kernel, fed by global->LDS loads where the output width is a multiple of 64, the
  *          input width even and the contraction not split, through registers otherwise
  *       1  always the 64x64 tile kernel that stages its operands through registers
  *       2  the wide kernel whenever width and alignment allow it, whatever the row count
- *       3  like 0 without the wide kernel */
+ *       3  like 0 without the wide and the weights-in-registers kernels
+ *       4  the weights-in-registers kernel whenever widths and alignment allow it, whatever the row count;
+ *          other layers as under 1 */
 #define DCI_OPT_LINEAR_KERNEL 1
 /*   DCI_OPT_LINEAR_SPLIT   upper limit on the workgroups that share one output tile of the 64x64 kernel
  *       (the contraction is split between them and a second kernel adds the partial sums in a fixed order):

@@ -184,7 +184,7 @@ int32_t dci_last_required(const dci_ctx* ctx, int64_t* cap_nodes, int64_t* cap_e
 int32_t dci_set_option(dci_ctx* ctx, int32_t option, int64_t value) {
   if (!ctx) return DCI_ERR_INVALID_ARG;
   if (option == DCI_OPT_LINEAR_KERNEL) {
-    if (value < 0 || value > 3) return dci::fail(ctx, DCI_ERR_INVALID_ARG, "DCI_OPT_LINEAR_KERNEL takes 0 .. 3, not %lld", (long long)value);
+    if (value < 0 || value > 4) return dci::fail(ctx, DCI_ERR_INVALID_ARG, "DCI_OPT_LINEAR_KERNEL takes 0 .. 4, not %lld", (long long)value);
     ctx->linear_kernel = (int)value;
     return DCI_OK;
   }

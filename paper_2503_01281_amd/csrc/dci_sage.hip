@@ -7,7 +7,9 @@
 //                        destination row, consecutive lanes on consecutive chunks of the row;
 //   a dense-layer kernel - y = x W_self + m W_neigh + b (+ ReLU) (GCN: y = m W + b): one contraction
 //                        over the concatenated axis on the matrix cores (v_mfma_f32_32x32x2f32, fp32 in,
-//                        fp32 accumulate).  Three of them, chosen by the layer's shape:
+//                        fp32 accumulate).  Four of them, chosen by the layer's shape:
+//       k_sage_linear_res   weights kept in registers, 32-row blocks streamed through LDS (tall layers
+//                           whose whole contraction is at most 256 long, 256-column tiles);
 //       k_sage_linear_wide  192x128 passes, one workgroup per compute unit, global->LDS loads
 //                           (tall layers with wide inputs);
 //       k_sage_linear_dma   64x64 tiles, global->LDS loads (output width a multiple of 64);
@@ -839,6 +841,211 @@ __global__ __launch_bounds__(kGemmThreads) void k_sage_linear_dma(LinearArgs a) 
 #undef DCI_D_STEP
 }
 
+// ---- weights resident in registers -------------------------------------------------------------
+// For layers whose whole contraction is at most 256 long (two operands of up to 128 columns each, or a
+// single one of up to 256) and whose output width is a multiple of 256.  With so short a contraction a
+// tiled kernel spends its time filling and draining its pipeline and re-reading the weights for every
+// tile; here each of the eight wavefronts of a workgroup owns 32 output columns and keeps its share of
+// the weights (contraction length x 32 values = up to 128 registers per lane) for the whole launch.
+// A workgroup (one per compute unit) walks 32-row blocks of the activations: a block's rows (both
+// operands side by side, at most 32 KB) arrive in LDS by 16-byte global->LDS loads two blocks ahead
+// (three buffers), every wavefront reads the whole block from LDS (16-byte fragment reads, same
+// xor-swizzled [slab][row][4 chunks] layout as the other kernels) and runs the contraction as one chain
+// of up to 128 matrix instructions into its 32x32 accumulator; the finished block is stored while the
+// next one is multiplied (two accumulator sets).  One barrier per block.
+// Needs: input width a multiple of 4, 16-byte aligned activation rows.
+constexpr int kResThreads = 512, kResCols = 256, kResMaxSlabs = 16, kResBufs = 3;
+constexpr int kResTileBytes = kResMaxSlabs * 32 * 64;  // 32 rows x 256 k x 4 B
+constexpr long long kResMinRows = 98304;               // by capacity; batches fill a quarter of it or so, and below about five row blocks per compute unit the start-up (every workgroup fetches all the weights) outweighs the gain
+
+struct FragR {
+  float4v a0, a1;  // t = 0, 1: four consecutive k of this lane's row
+};
+#define DCI_R_READ(f, OFF)                                                        \
+  asm volatile("ds_read_b128 %0, %2 offset:%4\n\tds_read_b128 %1, %3 offset:%4"  \
+               : "=&v"(f.a0), "=&v"(f.a1)                                         \
+               : "v"(la0), "v"(la1), "n"(OFF)                                     \
+               : "memory")
+#define DCI_R_WAIT(f, LG)                                                \
+  do {                                                                   \
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(LG) : "memory");          \
+    asm volatile("" : "+v"(f.a0), "+v"(f.a1)::"memory");                 \
+  } while (0)
+// slab S_ of the block: its fragments are in FC; the next slab's are requested into FN meanwhile.  NS (the
+// kernel's slab count) is a compile-time constant, so the conditions fold and the block is straight-line code.
+#define DCI_R_SLAB(S_, FC, FN, AC)                                                               \
+  if ((S_) < NS) {                                                                               \
+    if ((S_) + 1 < NS) {                                                                         \
+      DCI_R_READ(FN, (((S_) + 1) % kResMaxSlabs) * 2048);                                        \
+      DCI_R_WAIT(FC, 2);                                                                         \
+    } else {                                                                                     \
+      DCI_R_WAIT(FC, 0);                                                                         \
+    }                                                                                            \
+    __builtin_amdgcn_sched_barrier(0);                                                           \
+    AC = __builtin_amdgcn_mfma_f32_32x32x2f32(FC.a0.x, breg[8 * (S_) + 0], AC, 0, 0, 0);         \
+    AC = __builtin_amdgcn_mfma_f32_32x32x2f32(FC.a0.y, breg[8 * (S_) + 1], AC, 0, 0, 0);         \
+    AC = __builtin_amdgcn_mfma_f32_32x32x2f32(FC.a0.z, breg[8 * (S_) + 2], AC, 0, 0, 0);         \
+    AC = __builtin_amdgcn_mfma_f32_32x32x2f32(FC.a0.w, breg[8 * (S_) + 3], AC, 0, 0, 0);         \
+    AC = __builtin_amdgcn_mfma_f32_32x32x2f32(FC.a1.x, breg[8 * (S_) + 4], AC, 0, 0, 0);         \
+    AC = __builtin_amdgcn_mfma_f32_32x32x2f32(FC.a1.y, breg[8 * (S_) + 5], AC, 0, 0, 0);         \
+    AC = __builtin_amdgcn_mfma_f32_32x32x2f32(FC.a1.z, breg[8 * (S_) + 6], AC, 0, 0, 0);         \
+    AC = __builtin_amdgcn_mfma_f32_32x32x2f32(FC.a1.w, breg[8 * (S_) + 7], AC, 0, 0, 0);         \
+    __builtin_amdgcn_sched_barrier(0);                                                           \
+  }
+
+// NS: slabs of 16 the kernel multiplies, at least ceil(contraction length / 16); the weights and the LDS
+// chunks beyond the real length are zero, so a larger NS only costs time.
+template <int NS>
+__global__ __launch_bounds__(kResThreads, 1) void k_sage_linear_res(LinearArgs a, int g_n) {
+  static_assert(NS >= 1 && NS <= kResMaxSlabs, "slab count");
+  __shared__ __attribute__((aligned(1024))) char lds[kResBufs * kResTileBytes];
+  const long long M = a.counts[a.hop];
+  const int id = (int)blockIdx.x;
+  const int nt = id % a.n_tiles_n, slot = id / a.n_tiles_n;  // column tile, share of the row blocks
+  const long long n_rb = (M + 31) / 32;
+  if (slot >= n_rb) return;
+  const int n_my = (int)((n_rb - slot + g_n - 1) / g_n);  // blocks slot, slot + g_n, ...
+  const int tid = (int)threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int h = lane >> 5, ll = lane & 31;
+  const int K = a.K, N = a.N;
+  // The contraction runs over chunks of four k: first the chunks of the first operand, padded with a zero chunk
+  // to an even count, then those of the second operand likewise (so a pair of chunks - what one matrix step
+  // takes, one chunk per half of the wavefront - never straddles the operands), then zero chunks up to 4 NS.
+  const int n_ops = a.single ? 1 : 2;
+  const int kc_op = K / 4;                 // chunks of an operand that hold data
+  const int kpc = (kc_op + 1) & ~1;        // chunks per operand in the padded sequence
+  const float* A0 = a.single ? a.a_neigh : a.a_self;
+  const float* W0 = a.single ? a.w_neigh : a.w_self;
+
+  // Padding chunks are never loaded: they stay zero.
+  if (n_ops * kc_op != 4 * NS)
+    for (int i = tid; i < kResBufs * kResTileBytes / 16; i += kResThreads)
+      reinterpret_cast<float4*>(lds)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+
+  const int col = nt * kResCols + wave * 32 + ll;  // this lane's output column
+  const float bias = a.bias[col];
+
+  // Loads of a block: 2 per slab (16 rows each), numbered L = 2 slab + half; this wavefront issues
+  // L = wave, wave + 8, wave + 16, wave + 24.  Lane -> row 16 half + lane / 4, chunk (lane & 3) xor-ed with row bits.
+  const int rl = 16 * (wave & 1) + (lane >> 2);
+  const int c_a = (lane & 3) ^ ((lane >> 4) & 3);
+  const float* pb[4];
+  bool valid[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = 4 * ((wave + 8 * i) >> 1) + c_a;  // this lane's chunk in the padded sequence
+    const int op = c >= kpc ? 1 : 0;
+    const int kc = c - op * kpc;
+    valid[i] = op < n_ops && kc < kc_op;
+    pb[i] = (op ? a.a_neigh : A0) + 4 * kc;
+  }
+  auto issue = [&](int it_, int buf_) {
+    long long r = ((long long)slot + (long long)it_ * g_n) * 32 + rl;
+    if (r > M - 1) r = M - 1;  // rows past the end repeat the last row and are never stored
+    char* dst = lds + buf_ * kResTileBytes + wave * 1024;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (8 * i < 2 * NS && wave + 8 * i < 2 * NS && valid[i])
+        __builtin_amdgcn_global_load_lds((gptr_t)(pb[i] + r * K), (lptr_t)(dst + i * 8192), 16, 0, 0);
+  };
+  const unsigned lds0 = (unsigned)(size_t)(lptr_t)lds;
+  const unsigned la_row = lds0 + ll * 64 + ((h ^ ((ll >> 2) & 3)) * 16);
+  // Stores of a finished block: a uniform row base per accumulator register plus one lane offset (column, and
+  // the four rows that separate the wavefront's halves), so that the addresses cost no vector registers.
+  const unsigned lane_off = (unsigned)(4 * h * N + col);
+  auto store = [&](const floatx16& acc, int it_) {
+    const long long row0 = ((long long)slot + (long long)it_ * g_n) * 32;
+    float* yb = a.y + row0 * N;
+    if (row0 + 32 <= M) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float v = acc[r] + bias;
+        if (a.relu) v = v > 0.f ? v : 0.f;
+        (yb + (size_t)(8 * (r >> 2) + (r & 3)) * N)[lane_off] = v;
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float v = acc[r] + bias;
+        if (a.relu) v = v > 0.f ? v : 0.f;
+        if (row0 + 8 * (r >> 2) + 4 * h + (r & 3) < M) (yb + (size_t)(8 * (r >> 2) + (r & 3)) * N)[lane_off] = v;
+      }
+    }
+  };
+// One block: wait for its rows (requested two blocks ago, so they have long arrived; the wait also covers
+// the previous block's stores, issued most of a block ago), then multiply it.  Requesting the block after
+// next (into the buffer that every wavefront has finished reading) and storing the previous block are done
+// at the start by wavefronts 0..3 and half-way through the contraction by wavefronts 4..7: the two
+// wavefronts that share a SIMD then never leave the matrix pipe idle at the same time.
+#define DCI_R_SIDE(IT, PREV)                                             \
+  do {                                                                   \
+    if ((IT) + 2 < n_my) issue((IT) + 2, ((IT) + 2) % kResBufs);         \
+    if ((IT) > 0) store(PREV, (IT)-1);                                   \
+  } while (0)
+#define DCI_R_BLOCK(IT, ACC, PREV)                                       \
+  do {                                                                   \
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                     \
+    __builtin_amdgcn_s_barrier();                                        \
+    const unsigned la0 = la_row + ((IT) % kResBufs) * kResTileBytes;     \
+    const unsigned la1 = la0 ^ 32u;                                      \
+    FragR f0, f1;                                                        \
+    DCI_R_READ(f0, 0);                                                   \
+    if (wave < 4) DCI_R_SIDE(IT, PREV);                                  \
+    _Pragma("unroll") for (int r = 0; r < 16; ++r) ACC[r] = 0.f;         \
+    DCI_R_SLAB(0, f0, f1, ACC) DCI_R_SLAB(1, f1, f0, ACC) DCI_R_SLAB(2, f0, f1, ACC) DCI_R_SLAB(3, f1, f0, ACC)     \
+    DCI_R_SLAB(4, f0, f1, ACC) DCI_R_SLAB(5, f1, f0, ACC) DCI_R_SLAB(6, f0, f1, ACC) DCI_R_SLAB(7, f1, f0, ACC)     \
+    if (wave >= 4) DCI_R_SIDE(IT, PREV);                                 \
+    DCI_R_SLAB(8, f0, f1, ACC) DCI_R_SLAB(9, f1, f0, ACC) DCI_R_SLAB(10, f0, f1, ACC) DCI_R_SLAB(11, f1, f0, ACC)   \
+    DCI_R_SLAB(12, f0, f1, ACC) DCI_R_SLAB(13, f1, f0, ACC) DCI_R_SLAB(14, f0, f1, ACC) DCI_R_SLAB(15, f1, f0, ACC) \
+  } while (0)
+
+  __syncthreads();  // the zero fill is complete before the first rows arrive
+  issue(0, 0);
+  if (n_my > 1) issue(1, 1);
+
+  // This wavefront's weights.  Matrix step (T, j), T = 2 slab + t, takes chunk 2T of the padded sequence from
+  // lanes 0..31 and chunk 2T + 1 from lanes 32..63, element j of each: lane (column ll, half h) keeps
+  // W_op[4 (kc + h) + j][col], kc = 2T - op kpc.  Everything but the lane's byte offset is uniform, so a load
+  // is a scalar row base plus one vector offset; every load is issued (from a row that exists) and the lanes
+  // whose chunk is padding are zeroed afterwards.
+  const unsigned off_pair = lane_off * 4u, off_first = (unsigned)col * 4u;
+  float breg[8 * NS];
+#pragma unroll
+  for (int T = 0; T < 2 * NS; ++T) {
+    const int op = 2 * T >= kpc ? 1 : 0;
+    const int kc = 2 * T - op * kpc;                        // even
+    const bool first_ok = op < n_ops && kc < kc_op;         // the pair's first chunk holds data
+    const bool pair_ok = op < n_ops && kc + 1 < kc_op;      // and so does its second
+    const char* wrow = reinterpret_cast<const char*>(first_ok ? (op ? a.w_neigh : W0) + (size_t)(4 * kc) * N : W0);
+    const unsigned off = pair_ok ? off_pair : off_first;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) breg[4 * T + j] = *reinterpret_cast<const float*>(wrow + (size_t)j * N * 4 + off);
+  }
+  // (a second pass, so that no load waits for the one before it)
+#pragma unroll
+  for (int T = 0; T < 2 * NS; ++T) {
+    const int op = 2 * T >= kpc ? 1 : 0;
+    const int kc = 2 * T - op * kpc;
+    const bool first_ok = op < n_ops && kc < kc_op, pair_ok = op < n_ops && kc + 1 < kc_op;
+    if (!pair_ok) {  // uniform, and false for all but the last pair or two of an operand
+      const bool keep = first_ok && h == 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) breg[4 * T + j] = keep ? breg[4 * T + j] : 0.f;
+    }
+  }
+
+  floatx16 acc_e, acc_o;
+  for (int it = 0; it < n_my; it += 2) {
+    DCI_R_BLOCK(it, acc_e, acc_o);
+    if (it + 1 < n_my) DCI_R_BLOCK(it + 1, acc_o, acc_e);
+  }
+  if ((n_my - 1) & 1) store(acc_o, n_my - 1);
+  else store(acc_e, n_my - 1);
+#undef DCI_R_BLOCK
+#undef DCI_R_SIDE
+}
+
 struct SageWs {
   float* m;
   float* y[2];
@@ -1020,13 +1227,32 @@ static int32_t forward_in(dci_ctx* ctx, const dci_blocks* blocks, const float* x
     const int g_n = n_tiles_w > 0 ? (ctx->num_cus / 8 / n_tiles_w) * 8 : 0;
     const bool wide_ok = Do % kWideCols == 0 && D % 2 == 0 && g_n >= 8 && vb == 4 && aligned(x, 8) &&
                          aligned(ws.m, 8) && aligned(bias[l], 4);
-    const bool use_wide = wide_ok && (ctx->linear_kernel == 2 || (ctx->linear_kernel == 0 && cap >= kWideMinRows && D >= kWideMinWidth));
+    // weights in registers: short contractions (both operands together at most 256 long), 256-column tiles
+    const int n_tiles_r = Do / kResCols;
+    const int g_r = n_tiles_r > 0 ? ctx->num_cus / n_tiles_r : 0;
+    const int res_chunks = (gcn ? 1 : 2) * ((D / 4 + 1) & ~1);  // chunks of four k, each operand padded to an even count
+    const bool res_ok = Do % kResCols == 0 && D % 4 == 0 && res_chunks <= 4 * kResMaxSlabs && g_r >= 1 &&
+                        aligned(x, 16) && aligned(ws.m, 16);
+    const bool use_res = res_ok && (ctx->linear_kernel == 4 || (ctx->linear_kernel == 0 && cap >= kResMinRows));
+    const bool use_wide = !use_res && wide_ok && (ctx->linear_kernel == 2 || (ctx->linear_kernel == 0 && cap >= kWideMinRows && D >= kWideMinWidth));
     // 64x64 tiles fed by global->LDS loads: unsplit layers whose widths and alignment allow it
     const bool dma_ok = Do % TN == 0 && D % 2 == 0 && vb == 4 && va >= 2 && la.split == 1;
-    const bool use_dma = !use_wide && dma_ok && (ctx->linear_kernel == 0 || ctx->linear_kernel == 3);
+    const bool use_dma = !use_res && !use_wide && dma_ok && (ctx->linear_kernel == 0 || ctx->linear_kernel == 3);
     {
       Timed timed(ctx, l == 0 ? DCI_K_LINEAR_IN : DCI_K_LINEAR);
-      if (use_wide) {
+      if (use_res) {
+        la.n_tiles_n = n_tiles_r;
+        const int slabs = (res_chunks + 3) / 4;
+        const dim3 grid_r((unsigned)(g_r * n_tiles_r));
+        if (slabs <= 4)
+          hipLaunchKernelGGL(k_sage_linear_res<4>, grid_r, dim3(kResThreads), 0, ctx->stream, la, g_r);
+        else if (slabs <= 8)
+          hipLaunchKernelGGL(k_sage_linear_res<8>, grid_r, dim3(kResThreads), 0, ctx->stream, la, g_r);
+        else if (slabs <= 13)
+          hipLaunchKernelGGL(k_sage_linear_res<13>, grid_r, dim3(kResThreads), 0, ctx->stream, la, g_r);
+        else
+          hipLaunchKernelGGL(k_sage_linear_res<16>, grid_r, dim3(kResThreads), 0, ctx->stream, la, g_r);
+      } else if (use_wide) {
         la.n_tiles_n = n_tiles_w;
         if (l == 0)
           hipLaunchKernelGGL(k_sage_linear_wide<true>, dim3((unsigned)(g_n * n_tiles_w)), dim3(kWideThreads), 0,
@@ -1048,7 +1274,7 @@ static int32_t forward_in(dci_ctx* ctx, const dci_blocks* blocks, const float* x
         hipLaunchKernelGGL((k_sage_linear<1, 4>), grid, dim3(kGemmThreads), 0, ctx->stream, la);
       else
         hipLaunchKernelGGL((k_sage_linear<1, 1>), grid, dim3(kGemmThreads), 0, ctx->stream, la);
-      if (!use_wide && !use_dma && la.split > 1) {
+      if (!use_res && !use_wide && !use_dma && la.split > 1) {
         int64_t rb = (cap * Do + 255) / 256;
         if (rb > (int64_t)ctx->num_cus * 8) rb = (int64_t)ctx->num_cus * 8;
         hipLaunchKernelGGL(k_split_reduce, dim3((unsigned)rb), dim3(256), 0, ctx->stream, la);

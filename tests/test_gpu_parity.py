@@ -591,6 +591,8 @@ def test_dense_layer_kernels_on_random_shapes(env):
         model = int(rng.choice([0, 2]))
         option = int(rng.choice([0, 1, 2, 3]))
         split = int(rng.choice([0, 1]))
+        if case % 4 == 3:
+            option = 4   # weights in registers, where the shape allows it (else the default choice)
         blk = dci.Blocks(ctx, 10**6, M, (1,))
         blk.counts.zero_()
         blk.counts[0] = M
@@ -621,6 +623,53 @@ def test_dense_layer_kernels_on_random_shapes(env):
         assert np.isnan(got[M:]).all(), f"case {case}: rows beyond the batch were written"
 
 
+@pytest.mark.parametrize("model", [0, 2])
+@pytest.mark.parametrize("dims,fanouts,n_seeds", [((128, 256, 256), (3, 4), 70), ((100, 256, 47), (5, 5), 256),
+                                                  ((4, 256), (7,), 129), ((8, 512), (5,), 1), ((124, 256, 256), (5, 5), 300),
+                                                  ((64, 512, 256), (10, 25), 40)])
+def test_resident_weights_kernel_matches_oracle(env, model, dims, fanouts, n_seeds):
+    """The dense-layer kernel that keeps the weights in registers (kernel choice 4) forced on at small sizes:
+    contractions that fill all sixteen slabs (2 x 128), end inside a slab (2 x 100, 2 x 124, 2 x 4) or, for the
+    one-operand GCN layer, are half as long; one and two 256-column tiles; a single row and row counts that leave
+    the last 32-row block ragged; layers it cannot take (47 outputs, 512 inputs) fall back to the other kernels."""
+    _forward_case(env, dims, fanouts, n_seeds, model, option=4)
+
+
+def test_resident_weights_kernel_many_blocks(env):
+    """More 32-row blocks than workgroups (every workgroup walks several blocks, the three row buffers wrap, both
+    accumulator sets are stored) with a ragged last block, for both operand counts and a contraction that ends
+    inside a slab."""
+    dci, gu, ctx = env["dci"], env["gu"], env["ctx"]
+    rng = np.random.default_rng(5)
+    for M, K, N, model in ((40_001, 100, 256, 0), (33_000, 128, 256, 0), (24_577, 200, 512, 2)):
+        blk = dci.Blocks(ctx, 10**6, M, (1,))
+        blk.counts.zero_()
+        blk.counts[0] = M
+        blk.counts[1] = M
+        blk.blk_indptr[0].zero_()
+        x = rng.standard_normal((M, K), dtype=np.float32)
+        ws, wn, bs = synth.sage_weights((K, N), 300 + K)
+        want_blk = oracle.Blocks(n_nodes=np.array([M, M]), n_edges=np.array([0]), nodes=np.arange(M, dtype=np.int64),
+                                 blk_indptr=[np.zeros(M + 1, dtype=np.int64)], blk_src=[np.zeros(0, dtype=np.int32)],
+                                 src_global=[np.zeros(0, dtype=np.int64)], src_pos=[np.zeros(0, dtype=np.int64)])
+        want = oracle.gnn_forward(model, want_blk, x, ws, wn, bs)
+        x_dev = torch.zeros(blk.cap_nodes[1], K, dtype=torch.float32, device="cuda")
+        x_dev[:M] = torch.from_numpy(x).cuda()
+        logits = torch.full((blk.cap_nodes[0], N), float("nan"), dtype=torch.float32, device="cuda")
+        ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, 4)
+        try:
+            dci.dci_gnn_forward(ctx, blk, x_dev, model, [gu.dev(a) for a in ws], [gu.dev(a) for a in wn],
+                                [gu.dev(a) for a in bs], logits)
+            ctx.sync()
+        finally:
+            ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, 0)
+        got = logits.cpu().numpy()
+        tol = 1e-4 * max(1.0, float(np.abs(want).max()))
+        err = float(np.abs(got[:M].astype(np.float64) - want).max())
+        assert err <= tol, f"M={M} K={K} N={N} model={model}: {err} > {tol}"
+        assert np.isnan(got[M:]).all()
+
+
 @pytest.mark.parametrize("split", [1, 2, 0])
 def test_split_contraction_matches_oracle(env, split):
     """Few tiles: by default (0) the 64x64 kernel shares each tile between up to eight workgroups and a second
@@ -638,7 +687,7 @@ def test_split_contraction_matches_oracle(env, split):
 def test_set_option_rejects_bad_values(env):
     dci, ctx = env["dci"], env["ctx"]
     with pytest.raises(dci.DciError):
-        ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, 4)
+        ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, 5)
     with pytest.raises(dci.DciError):
         ctx.set_option(dci.DCI_OPT_LINEAR_SPLIT, 9)
     with pytest.raises(dci.DciError):
