@@ -73,10 +73,11 @@ def main() -> int:
                          "last node cached in part; pre-sampling then also counts per element")
     ap.add_argument("--model", default="sage-mean", choices=["sage-mean", "sage-sum", "gcn-avg"],
                     help="GNN of the forward pass (Table III); the headline configuration is sage-mean")
-    ap.add_argument("--linear-kernel", type=int, default=0, choices=[0, 1, 2, 3],
+    ap.add_argument("--linear-kernel", type=int, default=0, choices=[0, 1, 2, 3, 4],
                     help="dense-layer kernel of the single-stream regions: 0 by shape (default), 1 register-staged tile "
-                         "kernel, 2 wide kernel, 3 by shape without the wide kernel")
-    ap.add_argument("--pipelined-linear-kernel", type=int, default=1, choices=[0, 1, 2, 3],
+                         "kernel, 2 wide kernel, 3 by shape without the wide and the weights-in-registers kernels, "
+                         "4 weights in registers where the shape allows")
+    ap.add_argument("--pipelined-linear-kernel", type=int, default=1, choices=[0, 1, 2, 3, 4],
                     help="dense-layer kernel of the pipelined regions (the statically partitioned wide kernel loses "
                          "when other streams share the compute units)")
     ap.add_argument("--fused-input", type=int, default=1, choices=[0, 1],
@@ -86,7 +87,7 @@ def main() -> int:
     ap.add_argument("--cpu-batches", type=int, default=None, help="batches the single-thread CPU oracle is timed on")
     ap.add_argument("--lanes", type=int, default=4, help="batches in flight in the pipelined regions (0 or 1 = skip them)")
     ap.add_argument("--lanes-sweep", default=None, metavar="N,N,...",
-                    help="also time the pipelined region with these lane counts and dense-layer kernels 0 and 1 "
+                    help="also time the pipelined region with these lane counts and dense-layer kernels 0, 1, 3 and 4 "
                          "(extras.pipelined_sweep)")
     ap.add_argument("--roofline-kernel", default="auto",
                     help="kernel class of the top-level roofline (default: the one with the largest average launch in "
@@ -422,7 +423,7 @@ def main() -> int:
     if sweep:
         pipelined_sweep = []
         for nl in sweep:
-            for lk in (0, 1):
+            for lk in (0, 1, 3, 4):
                 for ln in lanes:
                     ln.ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, lk)
                 run(0, min(K, 2 * nl), nl)
