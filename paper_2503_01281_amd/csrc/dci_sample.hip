@@ -497,6 +497,7 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
 #pragma unroll
   for (int it = 0; it < kTileIters; ++it) val[it] = slot[it] >= 0 ? entry_val(a.table, (unsigned)slot[it]) : 0u;
   unsigned first_bits = 0;
+  long long new_u[kTileIters];
   unsigned long long hit_rows = 0, hit_edges = 0, host_lines = 0, bound_lines = 0;
 #pragma unroll
   for (int it = 0; it < kTileIters; ++it) {
@@ -506,6 +507,9 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
     const bool first = slot[it] >= 0 && val[it] == (kTentative | p);
     const unsigned long long bits = group_bits<G>(__ballot(first), grp_in_wave);
     if (first) first_bits |= 1u << it;
+    // the ids of the first appearances are only needed once the tile knows its offsets; asked for here, they
+    // arrive while the tile scans and looks back
+    new_u[it] = first ? a.tmp_u[(row0 + r) * f + gl] : 0;
     if (gl == 0) {
       s_c[r] = c;
       s_f[r] = __popcll(bits);
@@ -636,7 +640,7 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
   if (tid < TR && row0 + tid < n_rows) a.blk_indptr[row0 + tid + 1] = ec + s_c[tid];
 
   // first appearances take the next local ids, in (row, slot) order
-  long long new_id[kTileIters], new_u[kTileIters];
+  long long new_id[kTileIters];
 #pragma unroll
   for (int it = 0; it < kTileIters; ++it) {
     const int r = it * kGroups + grp;
@@ -644,9 +648,6 @@ __global__ __launch_bounds__(kBlock) void k_relabel_hop(RelabelArgs a) {
     const unsigned long long bits = group_bits<G>(__ballot(first), grp_in_wave);
     new_id[it] = first ? n_rows + ef + s_f[r] + __popcll(bits & ((1ull << gl) - 1ull)) : -1;
   }
-#pragma unroll
-  for (int it = 0; it < kTileIters; ++it)
-    new_u[it] = new_id[it] >= 0 ? a.tmp_u[(row0 + it * kGroups + grp) * f + gl] : 0;
 #pragma unroll
   for (int it = 0; it < kTileIters; ++it)
     if (new_id[it] >= 0) {
