@@ -338,6 +338,25 @@ def test_element_granular_cache_is_transparent_and_counts_hits_per_position(env)
                                             w.fanouts[h], w.rng_seed, pn, pd)
         hits += int(c4[2]); host += int(c4[3])
     assert host > 0
+    # host lines: a missed node costs the lines of its two list bounds and of the ids it reads; the node cached in
+    # part costs one line of bounds (where its host list starts) and the lines of the ids beyond its cached length
+    blines = ilines = slot_rows = all_rows = 0
+    for h in range(w.n_hops):
+        frontier = want.nodes[:want.n_nodes[h]]
+        bi = want.blk_indptr[h]
+        for i, v in enumerate(frontier):
+            v = int(v)
+            r = int(remap[v])
+            pos = want.src_pos[h][bi[i]:bi[i + 1]]
+            all_rows += 1
+            if r < 0:
+                blines += _host_lines(g.indptr.data_ptr(), [8 * v, 8 * (v + 1)])
+            else:
+                slot_rows += 1
+                pos = pos[pos >= int(cp[r + 1] - cp[r])]
+                blines += 1 if len(pos) else 0
+            if len(pos):
+                ilines += _host_lines(g.indices.data_ptr(), 8 * (int(tiny["indptr"][v]) + pos))
     for c_ in (cache, uploaded):
         blk = dci.Blocks(ctx, w.num_nodes, len(seeds), w.fanouts)
         stats = gu.new_stats()
@@ -345,6 +364,8 @@ def test_element_granular_cache_is_transparent_and_counts_hits_per_position(env)
         gu.assert_blocks_equal(gu.blocks_to_host(ctx, blk), want)
         st = gu.stats_dict(ctx, stats)
         assert (st["adj_edge_hits"], st["adj_edge_misses"]) == (hits, host)
+        assert (st["bytes_hbm"], st["bytes_host"]) == (16 * slot_rows + 8 * hits, 16 * (all_rows - slot_rows) + 8 * host)
+        assert (st["lines_bounds"], st["lines_ids"]) == (blines, ilines)
     # and the same blocks without any cache, from the reordered host lists alone
     blk = dci.Blocks(ctx, w.num_nodes, len(seeds), w.fanouts)
     dci.dci_sample_khop(ctx, g, None, gu.dev(seeds), 2, w.fanouts, w.rng_seed, blk)
