@@ -199,7 +199,7 @@ int32_t dci_last_required(const dci_ctx* ctx, int64_t* cap_nodes, int64_t* cap_e
 /*   DCI_OPT_FUSED_INPUT  how dci_infer_batches feeds the model on this context's lane: 0 (default)
  *       dci_gather_features then dci_gnn_forward, so that the lane's x holds every gathered row;
  *       1 dci_gather_forward (cached neighbour rows are read in place; x holds only the rows that
- *       missed and those of F_{L-1}).  The logits are the same up to nothing: the sums run in the same order. */
+ *       missed and those of F_{L-1}).  The logits are bit-identical either way: the sums run in the same order. */
 #define DCI_OPT_FUSED_INPUT 5
 /*   DCI_OPT_RELABEL_TILE_ITERS  rows per lane group in a tile of the frontier scan: 0 (default) chosen from
  *       the frontier's size, or 2, 4, 8.  Tuning only: the result does not depend on it. */
