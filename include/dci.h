@@ -132,7 +132,11 @@ enum {
                                   from the feature cache                                              */
   DCI_STAT_BYTES_HOST = 11,    /* the same quantities for what the graph arrays served (the miss path) */
   DCI_STAT_LINES_BOUNDS = 12,  /* sampling misses: 128-byte lines of graph->indptr that the list bounds of
-                                  the missed frontier nodes lie in (one or two per node), summed        */
+                                  the missed frontier nodes lie in (one or two per node), summed.  A node's
+                                  bounds cross the link once per batch, at the hop at which the node joins
+                                  the frontier: later hops, which sample it again, take them from a note
+                                  the sampler keeps in HBM for the batch (the byte counters above still
+                                  charge them to the tier that holds the node's list, hop by hop)        */
   DCI_STAT_LINES_IDS = 13,     /* sampling misses: distinct 128-byte lines of graph->indices read per
                                   frontier node, summed.  A host link charges a small read a whole
                                   request, so lines - not bytes - are what the miss path costs          */

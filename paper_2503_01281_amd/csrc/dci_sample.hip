@@ -9,7 +9,9 @@
 //                   one an element-granular fill may have cached in part), draw the positions (Floyd's subset algorithm
 //                   on Philox4x32-10, one lane per slot), read the neighbour ids, store them at the
 //                   padded position row*fanout + slot and register every id in the hash table with
-//                   an atomic minimum over that padded position.  At hop 0 the same kernel turns
+//                   an atomic minimum over that padded position.  A row's list bounds are noted for the
+//                   batch's later hops, which sample the same row again and then need neither the slot
+//                   look-up nor - for a miss - a second trip over the host link.  At hop 0 the same kernel turns
 //                   the seeds into F_0; at later hops its first workgroups write the previous
 //                   hop's edge ids, whose inputs are final by then.
 //   k_relabel_hop - a lane is the "first appearance" of its node iff the table still holds its own
@@ -164,6 +166,11 @@ struct HopArgs {
   int n_write_blocks;  // leading workgroups that only do the previous hop's edge ids
   const unsigned* batch_flag;  // != kBatchOk: an earlier kernel of this batch failed, do nothing
   int count_lines;             // statistics are on: count the host lines every row touches
+  // List bounds of the frontier's rows, kept for the batch's later hops (F_h is a prefix of F_{h+1}, and every
+  // hop samples all of its frontier): row i -> (start in the array that serves it, length | served-by-cache << 62),
+  // or a negative second word for the one node cached in part, whose bounds are looked up again.
+  long long* row_memo;
+  int last_hop;                // no later hop will read what this one would note
 };
 
 // blk_src of a finished hop: every edge reads the (by now final) local id of its source.
@@ -277,6 +284,7 @@ __global__ __launch_bounds__(kBlock) void k_write_src(const long long* counts, i
 template <int G, bool COUNT, bool INIT>
 __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
   const long long n_rows = INIT ? a.n_seeds : a.counts[a.hop];
+  const long long n_noted = INIT ? 0 : a.counts[a.hop - 1];  // rows below this were rows of the previous hop as well
   if (INIT) {
     if (blockIdx.x == 0 && threadIdx.x == 0) a.counts[0] = a.n_seeds;
   } else if (*a.batch_flag != kBatchOk) {
@@ -301,7 +309,7 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
     const bool row_ok = i < n_rows;
     long long v = 0, start = 0, d = 0, cached_len = 0;
     const long long* list = a.indices;
-    bool hit = false;
+    bool hit = false, noted = false;
     if (row_ok) {
       if (INIT) {
         v = a.seeds[i];
@@ -313,16 +321,32 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
       } else {
         v = a.nodes[i];
       }
-      const int r = a.adj_remap ? a.adj_remap[v] : -1;
-      hit = r >= 0;
-      if (hit) {
-        start = a.c_indptr[r];
-        cached_len = a.c_indptr[r + 1] - start;
-        d = v == a.partial_node ? a.partial_deg : cached_len;
-        list = a.c_indices;
-      } else {
-        start = a.indptr[v];
-        d = a.indptr[v + 1] - start;
+      if (!INIT && i < n_noted) {
+        const long long m = a.row_memo[2 * i + 1];
+        if (m >= 0) {
+          noted = true;
+          start = a.row_memo[2 * i];
+          hit = (m >> 62) != 0;
+          d = cached_len = m & ((1ll << 62) - 1);
+          if (hit) list = a.c_indices;
+        }
+      }
+      if (!noted) {
+        const int r = a.adj_remap ? a.adj_remap[v] : -1;
+        hit = r >= 0;
+        if (hit) {
+          start = a.c_indptr[r];
+          cached_len = a.c_indptr[r + 1] - start;
+          d = v == a.partial_node ? a.partial_deg : cached_len;
+          list = a.c_indices;
+        } else {
+          start = a.indptr[v];
+          d = a.indptr[v + 1] - start;
+        }
+        if (!a.last_hop && gl == 0) {
+          a.row_memo[2 * i] = start;
+          a.row_memo[2 * i + 1] = v == a.partial_node ? -1ll : (d | (hit ? (1ll << 62) : 0ll));
+        }
       }
     }
     const int c = d < (long long)f ? (int)d : f;
@@ -365,7 +389,7 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
         n_lines = __popcll(group_bits<G>(__ballot(leader), grp_in_wave));
       }
       if (row_ok && hit && n_host > 0) n_bound_lines = 1;  // the partly cached node: where its host list starts
-      if (row_ok && !hit) {
+      if (row_ok && !hit && !noted) {  // (a noted row's bounds came from the batch's own note in HBM)
         const uintptr_t b0 = reinterpret_cast<uintptr_t>(a.indptr + v), b1 = reinterpret_cast<uintptr_t>(a.indptr + v + 1);
         n_bound_lines = (b0 >> kHostLineLog2) == (b1 >> kHostLineLog2) ? 1 : 2;
       }
@@ -706,6 +730,7 @@ struct SampleWs {
   long long* tmp_u;
   int* tmp_slot[2];  // by hop parity: a hop's slots are still read while the next hop samples
   int* row_cnt[2];
+  long long* row_memo;     // [2 * rows]: list bounds of the frontier's rows, noted for the batch's later hops
   unsigned long long* stat_part[DCI_MAX_HOPS];  // per hop: two words per relabel tile
 };
 
@@ -760,6 +785,7 @@ static void carve_sample_ws(Arena& ar, const int64_t* cap_nodes, const int64_t* 
     ws->tmp_slot[k] = ar.take<int>((size_t)max_edges);
     ws->row_cnt[k] = ar.take<int>((size_t)max_rows);
   }
+  ws->row_memo = ar.take<long long>(2 * (size_t)max_rows);
   for (int32_t h = 0; h < n_hops; ++h)
     ws->stat_part[h] = ar.take<unsigned long long>(kStatPartWords * (size_t)tiles_for(cap_nodes[h], fanouts[h], kTileItersMin));
 }
@@ -868,6 +894,8 @@ static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* c
     ha.n_write_blocks = h > 0 ? grid_for_rows(ctx, out->cap_rows[h - 1] * fanouts[h - 1], kBlock * 4) : 0;
     ha.batch_flag = ws.batch_flag;
     ha.count_lines = stats ? 1 : 0;
+    ha.row_memo = ws.row_memo;
+    ha.last_hop = h == n_hops - 1 ? 1 : 0;
     RelabelArgs ra;
     ra.counts = counts;
     ra.hop = h;

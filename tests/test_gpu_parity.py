@@ -350,7 +350,8 @@ def test_element_granular_cache_is_transparent_and_counts_hits_per_position(env)
             pos = want.src_pos[h][bi[i]:bi[i + 1]]
             all_rows += 1
             if r < 0:
-                blines += _host_lines(g.indptr.data_ptr(), [8 * v, 8 * (v + 1)])
+                if h == 0 or i >= int(want.n_nodes[h - 1]):   # fetched once per batch, noted for the later hops
+                    blines += _host_lines(g.indptr.data_ptr(), [8 * v, 8 * (v + 1)])
             else:
                 slot_rows += 1
                 pos = pos[pos >= int(cp[r + 1] - cp[r])]
@@ -772,7 +773,8 @@ def _expected_sampler_traffic(want, fanouts, indptr, adj_remap, indptr_base, ind
     """(bytes_hbm, bytes_host, lines_bounds, lines_ids) of sampling the batch `want` through a node-granular adjacency
     cache, from the oracle's blocks and sampled positions: 16 bytes of list bounds per frontier node and
     8 bytes per neighbour id, charged to the tier that serves the node; lines = per missed node, the lines
-    of its two list bounds plus the distinct lines of the neighbour ids it reads."""
+    of its two list bounds (only at the hop at which the node joins the frontier: the sampler notes them for the
+    batch's later hops) plus the distinct lines of the neighbour ids it reads."""
     b_hbm = b_host = lines = blines = 0
     for h in range(len(fanouts)):
         frontier = want.nodes[:want.n_nodes[h]]
@@ -781,9 +783,11 @@ def _expected_sampler_traffic(want, fanouts, indptr, adj_remap, indptr_base, ind
         rows = np.diff(bi)
         b_hbm += 16 * int(hit.sum()) + 8 * int(rows[hit].sum())
         b_host += 16 * int((~hit).sum()) + 8 * int(rows[~hit].sum())
+        n_noted = int(want.n_nodes[h - 1]) if h > 0 else 0   # these rows' bounds were fetched at an earlier hop
         for i in np.flatnonzero(~hit):
             v = int(frontier[i])
-            blines += _host_lines(indptr_base, [8 * v, 8 * (v + 1)])
+            if i >= n_noted:
+                blines += _host_lines(indptr_base, [8 * v, 8 * (v + 1)])
             pos = want.src_pos[h][bi[i]:bi[i + 1]]
             if len(pos):
                 lines += _host_lines(indices_base, 8 * (int(indptr[v]) + pos))
