@@ -171,7 +171,6 @@ struct HopArgs {
   // or a negative second word for the one node cached in part, whose bounds are looked up again.
   long long* row_memo;
   int last_hop;                // no later hop will read what this one would note
-  long long cap_rows;          // rows this hop's buffers hold (the launch's bound on the frontier)
 };
 
 // blk_src of a finished hop: every edge reads the (by now final) local id of its source.
@@ -284,18 +283,6 @@ __global__ __launch_bounds__(kBlock) void k_write_src(const long long* counts, i
 // (write_block_sources), which only needs values that are already final.
 template <int G, bool COUNT, bool INIT>
 __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
-  // The first row of every lane group is asked for before the row count is known (the buffers hold cap_rows
-  // entries whatever the count): one memory round trip less on the kernel's chain of dependent accesses.  What
-  // arrives for a row beyond the count, or a note beyond the previous frontier, is not used.
-  long long v_first = 0, note0_first = 0, note1_first = -1;
-  {
-    const long long i0 = ((long long)blockIdx.x - (INIT ? 0 : a.n_write_blocks)) * (kBlock / G) + (long long)(threadIdx.x / G);
-    if (!INIT && i0 >= 0 && i0 < a.cap_rows) {
-      v_first = a.nodes[i0];
-      note0_first = a.row_memo[2 * i0];
-      note1_first = a.row_memo[2 * i0 + 1];
-    }
-  }
   const long long n_rows = INIT ? a.n_seeds : a.counts[a.hop];
   const long long n_noted = INIT ? 0 : a.counts[a.hop - 1];  // rows below this were rows of the previous hop as well
   if (INIT) {
@@ -320,7 +307,6 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
   for (long long base = (long long)block * kGroups; base < n_rows; base += (long long)n_blocks * kGroups) {
     const long long i = base + grp_in_block;
     const bool row_ok = i < n_rows;
-    const bool first_round = base == (long long)block * kGroups;
     long long v = 0, start = 0, d = 0, cached_len = 0;
     const long long* list = a.indices;
     bool hit = false, noted = false;
@@ -333,13 +319,13 @@ __global__ __launch_bounds__(kBlock) void k_sample_hop(HopArgs a) {
           (void)table_insert_min(a.table, a.entries, v, (unsigned)i, &ignored);
         }
       } else {
-        v = first_round ? v_first : a.nodes[i];
+        v = a.nodes[i];
       }
       if (!INIT && i < n_noted) {
-        const long long m = first_round ? note1_first : a.row_memo[2 * i + 1];
+        const long long m = a.row_memo[2 * i + 1];
         if (m >= 0) {
           noted = true;
-          start = first_round ? note0_first : a.row_memo[2 * i];
+          start = a.row_memo[2 * i];
           hit = (m >> 62) != 0;
           d = cached_len = m & ((1ll << 62) - 1);
           if (hit) list = a.c_indices;
@@ -910,7 +896,6 @@ static int32_t sample_batch(dci_ctx* ctx, const dci_graph* g, const dci_cache* c
     ha.count_lines = stats ? 1 : 0;
     ha.row_memo = ws.row_memo;
     ha.last_hop = h == n_hops - 1 ? 1 : 0;
-    ha.cap_rows = out->cap_rows[h];
     RelabelArgs ra;
     ra.counts = counts;
     ra.hop = h;
