@@ -83,6 +83,10 @@ def main() -> int:
     ap.add_argument("--fused-input", type=int, default=1, choices=[0, 1],
                     help="1 (default): the input layer reads cached neighbour rows in place (dci_gather_forward: only "
                          "missed rows and the rows of F_{L-1} are copied); 0: dci_gather_features then dci_gnn_forward")
+    ap.add_argument("--input-layer", type=int, default=0, choices=[0, 1, 2],
+                    help="first layer: 0 (default) one kernel that aggregates inside the weights-in-registers dense "
+                         "layer where that kernel would be chosen, 1 always aggregation kernel + dense kernel, "
+                         "2 the one-kernel form wherever the shape allows")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batches", type=int, default=None, help="batches the single-thread CPU oracle is timed on")
     ap.add_argument("--lanes", type=int, default=4, help="batches in flight in the pipelined regions (0 or 1 = skip them)")
@@ -168,6 +172,7 @@ def main() -> int:
     logits = torch.empty(w.num_seeds, w.classes, dtype=torch.float32, device="cuda")
     for ln in lanes:
         ln.ctx.set_option(dci.DCI_OPT_FUSED_INPUT, args.fused_input)
+        ln.ctx.set_option(dci.DCI_OPT_INPUT_LAYER, args.input_layer)
 
     # ---- one-off part: pre-sampling counts (timed per stage for Eq. (1)) and the dual-cache fill
     cache = None
@@ -345,13 +350,22 @@ def main() -> int:
         if l <= 1:
             if l == 1 and L > 2:       # the later layers share one class: add them up
                 mb = sum(4 * w.dims[j] * (int(hop_edges[L - 1 - j]) + int(hop_nodes[L - 1 - j])) for j in range(1, L))
+            fl = flops_layer[0] if l == 0 else float(flops_layer[1:].sum())
+            one_kernel = l == 0 and timing_all[cls_m][1] == 0 and timing_all[cls_l][1] > 0
+            if one_kernel:
+                # the input layer ran as one kernel (aggregation inside the dense layer): it answers to both bounds
+                rooflines[cls_l] = entry("k_sage_input_res (aggregation inside the dense layer)", cls_l,
+                                         {"hbm": mb / hbm_bw, "mfma": fl / (FP32_MFMA_PEAK_TFLOPS * 1e12)},
+                                         {"hbm": mb / GB, "mfma": fl / 1e12},
+                                         {"hbm": HBM_PEAK_GBPS, "mfma": FP32_MFMA_PEAK_TFLOPS}, unit_hbm,
+                                         bytes_per_step=round(mb / K), flops_per_step=round(fl / K))
+                continue
             rooflines[cls_m] = entry("k_sage_mean", cls_m, {"hbm": mb / hbm_bw}, {"hbm": mb / GB}, {"hbm": HBM_PEAK_GBPS},
                                      unit_hbm, bytes_per_step=round(mb / K))
-            fl = flops_layer[0] if l == 0 else float(flops_layer[1:].sum())
             rooflines[cls_l] = entry("dense layer (fp32 MFMA)", cls_l, {"mfma": fl / (FP32_MFMA_PEAK_TFLOPS * 1e12)},
                                      {"mfma": fl / 1e12}, {"mfma": FP32_MFMA_PEAK_TFLOPS}, unit_hbm,
                                      flops_per_step=round(fl / K))
-    if args.fused_input:
+    if args.fused_input and timing_all["mean_in"][1] > 0:
         # the pair against what the two separate steps are defined to move: every input row gathered (8F+12 B on a
         # hit) and every edge's row read once more for the aggregate
         full = (sk["feat_hits"] * (8 * F + 12) + sk["feat_misses"] * ((4 * F + 12) if feat.is_pinned() else (8 * F + 12))

@@ -208,6 +208,15 @@ int32_t dci_last_required(const dci_ctx* ctx, int64_t* cap_nodes, int64_t* cap_e
 /*   DCI_OPT_RELABEL_TILE_ITERS  rows per lane group in a tile of the frontier scan: 0 (default) chosen from
  *       the frontier's size, or 2, 4, 8.  Tuning only: the result does not depend on it. */
 #define DCI_OPT_RELABEL_TILE_ITERS 6
+/*   DCI_OPT_INPUT_LAYER  how the forward pass runs its first layer when that layer qualifies for the
+ *       weights-in-registers kernel (see DCI_OPT_LINEAR_KERNEL), has two operands of at most 128 columns and
+ *       the mean or sum aggregator: 0 (default) one kernel that aggregates inside the dense layer whenever the
+ *       default choice of dense kernel would be the weights-in-registers one and the two operands together are
+ *       at most 208 columns (13 slabs of 16) - beyond that the weights leave too few registers for the loads
+ *       in flight and the single kernel is no faster; 1 always the aggregation kernel followed by a dense
+ *       kernel; 2 the one-kernel form whenever widths and alignment allow it, whatever the row count.  The
+ *       result is bit-identical: every sum runs in the same order. */
+#define DCI_OPT_INPUT_LAYER 7
 int32_t dci_set_option(dci_ctx* ctx, int32_t option, int64_t value);
 
 /* Kernel timing, for benchmarks and profiles.  Kernel classes whose bit is set in class_mask are

@@ -437,6 +437,7 @@ DCI_OPT_RELABEL_SPIN_LIMIT = 3
 DCI_OPT_TEST_RELABEL_FIRST_TICKET = 4
 DCI_OPT_FUSED_INPUT = 5
 DCI_OPT_RELABEL_TILE_ITERS = 6
+DCI_OPT_INPUT_LAYER = 7
 
 
 def dci_sage_forward(ctx: Context, blocks: Blocks, x_in: torch.Tensor, w_self: Sequence[torch.Tensor],

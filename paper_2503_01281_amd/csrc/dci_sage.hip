@@ -7,7 +7,8 @@
 //                        destination row, consecutive lanes on consecutive chunks of the row;
 //   a dense-layer kernel - y = x W_self + m W_neigh + b (+ ReLU) (GCN: y = m W + b): one contraction
 //                        over the concatenated axis on the matrix cores (v_mfma_f32_32x32x2f32, fp32 in,
-//                        fp32 accumulate).  Four of them, chosen by the layer's shape:
+//                        fp32 accumulate).  Four of them, chosen by the layer's shape (and a fifth,
+//                        k_sage_input_res, that does the input layer's aggregation inside the first of them):
 //       k_sage_linear_res   weights kept in registers, 32-row blocks streamed through LDS (tall layers
 //                           whose whole contraction is at most 256 long, 256-column tiles);
 //       k_sage_linear_wide  192x128 passes, one workgroup per compute unit, global->LDS loads
@@ -875,12 +876,8 @@ struct FragR {
 // kernel's slab count) is a compile-time constant, so the conditions fold and the block is straight-line code.
 #define DCI_R_SLAB(S_, FC, FN, AC)                                                               \
   if ((S_) < NS) {                                                                               \
-    if ((S_) + 1 < NS) {                                                                         \
-      DCI_R_READ(FN, (((S_) + 1) % kResMaxSlabs) * 2048);                                        \
-      DCI_R_WAIT(FC, 2);                                                                         \
-    } else {                                                                                     \
-      DCI_R_WAIT(FC, 0);                                                                         \
-    }                                                                                            \
+    DCI_R_WAIT(FC, 0); /* asked for a slab ago; a wait for everything does not depend on what else is counted */ \
+    if ((S_) + 1 < NS) DCI_R_READ(FN, (((S_) + 1) % kResMaxSlabs) * 2048);                       \
     __builtin_amdgcn_sched_barrier(0);                                                           \
     AC = __builtin_amdgcn_mfma_f32_32x32x2f32(FC.a0.x, breg[8 * (S_) + 0], AC, 0, 0, 0);         \
     AC = __builtin_amdgcn_mfma_f32_32x32x2f32(FC.a0.y, breg[8 * (S_) + 1], AC, 0, 0, 0);         \
@@ -1046,6 +1043,292 @@ __global__ __launch_bounds__(kResThreads, 1) void k_sage_linear_res(LinearArgs a
 #undef DCI_R_SIDE
 }
 
+// ---- input layer in one kernel: aggregation inside the weights-in-registers dense layer ---------------
+// k_sage_linear_res reads, per 32-row block, the self rows and the aggregated rows side by side from LDS.
+// Here the aggregated half of a block is not loaded from a matrix that another kernel wrote: the workgroup
+// computes it itself, one block ahead, while its matrix instructions run - the matrix pipe leaves the issue
+// slots of a wavefront idle between dependent instructions, and the aggregation is loads plus a few additions.
+// Every wavefront aggregates four rows of the next block (rows 4w .. 4w+3): half h of the wavefront sums one
+// row, a lane of the half one 16-byte chunk of it, edge after edge in edge order (the order k_sage_mean uses,
+// so the two routes agree to the bit).  The loads run as a fixed pipeline of 32 "slots" per block (2 row pairs
+// x 16 edges): slot P is consumed eight slots after it was issued, so eight 16-byte loads per lane are in flight
+// all the time; slots of edges a row does not have load a dummy line and add zero, which keeps the number of
+// memory operations per block fixed (the wait before a block's barrier counts them).  Where a row's edges come
+// from (cache slot or staged row, via blk_src and rowref) is worked out three blocks ahead and kept in LDS.
+// Rows with more than 16 edges take the rest in a plain loop when the row is finished.
+// Needs what k_sage_linear_res needs, two operands of at most 128 columns, and the mean or sum aggregator.
+constexpr int kFuseSlots = 32, kFuseFan = 16, kFuseRing = 4;
+__device__ const float4 kFuseZeros[64] = {};  // what the slot of an edge that does not exist loads (one line per lane group, always zero)
+struct FuseNote {               // per wavefront and block, in LDS
+  unsigned long long base[64];  // lane 16 q + e: address of the source row of edge e of the wavefront's row q
+  long long lo[4];              // first edge of row q
+  int cnt[4];                   // edges of row q (0 for a row beyond the end)
+  int pad[4];
+};
+struct FuseArgs {
+  const long long* blk_indptr;
+  const int* blk_src;
+  const int* rowref;    // nullable: cache slot of a source, or -1
+  const float* cache;   // rows of cached sources
+  const float* x_src;   // rows of the other sources, by local id
+  int mode;             // DCI_MODEL_SAGE_MEAN or DCI_MODEL_SAGE_SUM
+};
+
+template <int NS>
+__global__ __launch_bounds__(kResThreads, 1) void k_sage_input_res(LinearArgs a, FuseArgs fa, int g_n) {
+  static_assert(NS >= 4 && NS <= kResMaxSlabs, "slab count");
+  // slots in flight per lane: eight where the registers allow it (the weights of the longest contraction take 128)
+  constexpr int kFuseAhead = NS > 13 ? 4 : 8;
+  __shared__ __attribute__((aligned(1024))) char lds[kResBufs * kResTileBytes];
+  __shared__ FuseNote notes[kFuseRing][kResThreads / kWave];
+  const long long M = a.counts[a.hop];
+  const int id = (int)blockIdx.x;
+  const int nt = id % a.n_tiles_n, slot = id / a.n_tiles_n;
+  const long long n_rb = (M + 31) / 32;
+  if (slot >= n_rb) return;
+  const int n_my = (int)((n_rb - slot + g_n - 1) / g_n);
+  const int tid = (int)threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int h = lane >> 5, ll = lane & 31;
+  const int K = a.K, N = a.N;
+  const int kc_op = K / 4;           // chunks of an operand that hold data (at most 32)
+  const int kpc = (kc_op + 1) & ~1;  // chunks per operand in the padded sequence
+
+  if (2 * kc_op != 4 * NS)
+    for (int i = tid; i < kResBufs * kResTileBytes / 16; i += kResThreads)
+      reinterpret_cast<float4*>(lds)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+
+  const int col = nt * kResCols + wave * 32 + ll;
+  const float bias = a.bias[col];
+
+  // global->LDS loads of the self rows (operand 0 only: the other half of a block is computed here); the
+  // addresses are formed when a block is requested rather than kept, registers being what this kernel is short of
+  const int rl = 16 * (wave & 1) + (lane >> 2);
+  const int c_a = (lane & 3) ^ ((lane >> 4) & 3);
+  auto issue = [&](int it_, int buf_) {
+    long long r = ((long long)slot + (long long)it_ * g_n) * 32 + rl;
+    if (r > M - 1) r = M - 1;
+    const float* prow = a.a_self + r * K + 4 * c_a;
+    char* dst = lds + buf_ * kResTileBytes + wave * 1024;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (8 * i < 2 * NS && wave + 8 * i < 2 * NS && 4 * ((wave + 8 * i) >> 1) + c_a < kc_op)
+        __builtin_amdgcn_global_load_lds((gptr_t)(prow + 16 * ((wave + 8 * i) >> 1)), (lptr_t)(dst + i * 8192), 16, 0, 0);
+  };
+  const unsigned lds0 = (unsigned)(size_t)(lptr_t)lds;
+  const unsigned la_row = lds0 + ll * 64 + ((h ^ ((ll >> 2) & 3)) * 16);
+  const unsigned lane_off = (unsigned)(4 * h * N + col);
+  auto store = [&](const floatx16& acc, int it_) {
+    const long long row0 = ((long long)slot + (long long)it_ * g_n) * 32;
+    float* yb = a.y + row0 * N;
+    if (row0 + 32 <= M) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float v = acc[r] + bias;
+        if (a.relu) v = v > 0.f ? v : 0.f;
+        (yb + (size_t)(8 * (r >> 2) + (r & 3)) * N)[lane_off] = v;
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float v = acc[r] + bias;
+        if (a.relu) v = v > 0.f ? v : 0.f;
+        if (row0 + 8 * (r >> 2) + 4 * h + (r & 3) < M) (yb + (size_t)(8 * (r >> 2) + (r & 3)) * N)[lane_off] = v;
+      }
+    }
+  };
+
+  // ---- where the edges' rows are: worked out per block in four steps, each waiting for the one before ----
+  struct Ix {
+    int lo, hi;  // edge numbers stay below 2^31 (the batch bounds are checked against that)
+    int s, rr;
+    bool on;
+  };
+  auto index_bounds = [&](Ix& ix, int t) {
+    const long long R = ((long long)slot + (long long)t * g_n) * 32 + 4 * wave + (lane >> 4);
+    const bool ok = t < n_my && R < M;
+    ix.lo = ok ? (int)fa.blk_indptr[R] : 0;
+    ix.hi = ok ? (int)fa.blk_indptr[R + 1] : 0;
+  };
+  auto index_source = [&](Ix& ix) {
+    ix.on = (lane & 15) < ix.hi - ix.lo;
+    ix.s = ix.on ? fa.blk_src[(long long)ix.lo + (lane & 15)] : 0;
+  };
+  auto index_slot = [&](Ix& ix) { ix.rr = (ix.on && fa.rowref) ? fa.rowref[ix.s] : -1; };
+  auto index_note = [&](const Ix& ix, int t) {
+    FuseNote& nb = notes[t & (kFuseRing - 1)][wave];
+    const float* p = ix.rr >= 0 ? fa.cache + (long long)ix.rr * K : fa.x_src + (long long)ix.s * K;
+    nb.base[lane] = ix.on ? (unsigned long long)reinterpret_cast<uintptr_t>(p) : 0ull;
+    if ((lane & 15) == 0) {
+      nb.lo[lane >> 4] = ix.lo;
+      nb.cnt[lane >> 4] = ix.hi - ix.lo;
+    }
+  };
+  Ix ixs = {0, 0, 0, -1, false};  // the block being worked out while the matrix instructions run
+
+  // ---- the slot pipeline ----
+  float4v land[kFuseAhead];
+  float4v agg = {0.f, 0.f, 0.f, 0.f};
+  const float4v zero4 = {0.f, 0.f, 0.f, 0.f};
+  const bool lane_on = ll < kc_op;
+  const float* const zeros = reinterpret_cast<const float*>(kFuseZeros) + 4 * lane;
+  auto slot_issue = [&](int t, int P) {  // P: 0 .. 31, a compile-time value at every call
+    const FuseNote& nb = notes[t & (kFuseRing - 1)][wave];
+    const int q = 2 * (P >> 4) + h, j = P & 15;
+    const bool on = lane_on && j < nb.cnt[q];
+    const float* p = on ? reinterpret_cast<const float*>((uintptr_t)nb.base[16 * q + j]) + 4 * ll : zeros;
+    land[P & (kFuseAhead - 1)] = *reinterpret_cast<const float4v*>(p);
+  };
+  auto row_done = [&](int t, int rp) {  // the two rows of row pair rp of block t are complete: write them to the block's buffer
+    const FuseNote& nb = notes[t & (kFuseRing - 1)][wave];
+    const int q = 2 * rp + h;
+    const int cnt = nb.cnt[q];
+    if (cnt > kFuseFan && lane_on) {  // the edges beyond the pipelined sixteen
+      const long long lo = nb.lo[q];
+      for (int e = kFuseFan; e < cnt; ++e) {
+        const int sidx = fa.blk_src[lo + e];
+        const int rr = fa.rowref ? fa.rowref[sidx] : -1;
+        const float* p = rr >= 0 ? fa.cache + (long long)rr * K : fa.x_src + (long long)sidx * K;
+        agg += *reinterpret_cast<const float4v*>(p + 4 * ll);
+      }
+    }
+    const float fc = (float)cnt;
+    const float4v r = (fa.mode == DCI_MODEL_SAGE_SUM || cnt == 0) ? agg : agg / fc;
+    if (lane_on) {
+      const int row = 4 * wave + q;
+      const int ck = kpc + ll;  // chunk of the second operand in the padded sequence
+      char* dst = lds + (t % kResBufs) * kResTileBytes + (ck >> 2) * 2048 + row * 64 + (((ck & 3) ^ ((row >> 2) & 3)) * 16);
+      *reinterpret_cast<float4v*>(dst) = r;
+    }
+    agg = zero4;
+  };
+  auto slot_take = [&](int t, int P) {
+    agg += land[P & (kFuseAhead - 1)];
+    if ((P & 15) == 15) row_done(t, P >> 4);
+  };
+// Slab S_ of the block that multiplies tile IT also handles slots kFuseSlots S_ / NS .. kFuseSlots (S_ + 1) / NS - 1 (two
+// or three): it takes them from tile IT + 1 and issues the slots eight further on (of tile IT + 1, or of tile IT + 2 once
+// past the end).  The slot work and the steps that find the sources of tile IT + 3 sit between the slab's matrix
+// instructions, whose dependent chain leaves the wavefront's issue slots free.
+#define DCI_F_SLOT(IT, S_, K_)                                                               \
+  do {                                                                                       \
+    constexpr int P_ = kFuseSlots * (S_) / NS + (K_);                                        \
+    if (P_ < kFuseSlots * ((S_) + 1) / NS) {                                                 \
+      slot_take((IT) + 1, P_);                                                               \
+      if (P_ + kFuseAhead < kFuseSlots) slot_issue((IT) + 1, P_ + kFuseAhead);               \
+      else slot_issue((IT) + 2, P_ + kFuseAhead - kFuseSlots);                               \
+    }                                                                                        \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
+  } while (0)
+#define DCI_F_MFMA(FC_, E_, Q_, AC)                                                          \
+  do {                                                                                       \
+    AC = __builtin_amdgcn_mfma_f32_32x32x2f32(FC_ E_, breg[Q_], AC, 0, 0, 0);                \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
+  } while (0)
+#define DCI_F_SLAB(IT, S_, FC, FN, AC)                                                       \
+  if ((S_) < NS) {                                                                           \
+    DCI_R_WAIT(FC, 0);                                                                       \
+    if ((S_) + 1 < NS) DCI_R_READ(FN, (((S_) + 1) % kResMaxSlabs) * 2048);                   \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
+    DCI_F_MFMA(FC, .a0.x, 8 * (S_) + 0, AC);                                                 \
+    DCI_F_SLOT(IT, S_, 0);                                                                   \
+    DCI_F_MFMA(FC, .a0.y, 8 * (S_) + 1, AC);                                                 \
+    DCI_F_MFMA(FC, .a0.z, 8 * (S_) + 2, AC);                                                 \
+    DCI_F_SLOT(IT, S_, 1);                                                                   \
+    DCI_F_MFMA(FC, .a0.w, 8 * (S_) + 3, AC);                                                 \
+    DCI_F_MFMA(FC, .a1.x, 8 * (S_) + 4, AC);                                                 \
+    DCI_F_SLOT(IT, S_, 2);                                                                   \
+    DCI_F_MFMA(FC, .a1.y, 8 * (S_) + 5, AC);                                                 \
+    if ((S_) == 0) index_bounds(ixs, (IT) + 3);                                              \
+    if ((S_) == NS / 4) index_source(ixs);                                                   \
+    if ((S_) == NS / 2) index_slot(ixs);                                                     \
+    if ((S_) == (3 * NS) / 4) index_note(ixs, (IT) + 3);                                     \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
+    DCI_F_MFMA(FC, .a1.z, 8 * (S_) + 6, AC);                                                 \
+    DCI_F_MFMA(FC, .a1.w, 8 * (S_) + 7, AC);                                                 \
+  }
+// At the start of a block the newest memory operations of the wavefront are the previous block's (at most 16) stores
+// and, before them, its eight slots in flight.  Every slot issues exactly one load, so the previous block issued at
+// least 32 operations, all of them after this block's self rows were requested (two blocks ago): waiting for all but
+// the newest 24 covers those rows whatever the stores were, and leaves the slots in flight.
+#define DCI_F_BLOCK(IT)                                                  \
+  do {                                                                   \
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(16 + kFuseAhead) : "memory"); \
+    __builtin_amdgcn_s_barrier();                                        \
+    const unsigned la0 = la_row + ((IT) % kResBufs) * kResTileBytes;     \
+    const unsigned la1 = la0 ^ 32u;                                      \
+    FragR f0, f1;                                                        \
+    DCI_R_READ(f0, 0);                                                   \
+    if (wave < 4 && (IT) + 2 < n_my) issue((IT) + 2, ((IT) + 2) % kResBufs); \
+    floatx16 acc;                                                        \
+    _Pragma("unroll") for (int r = 0; r < 16; ++r) acc[r] = 0.f;         \
+    DCI_F_SLAB(IT, 0, f0, f1, acc) DCI_F_SLAB(IT, 1, f1, f0, acc) DCI_F_SLAB(IT, 2, f0, f1, acc) DCI_F_SLAB(IT, 3, f1, f0, acc)     \
+    DCI_F_SLAB(IT, 4, f0, f1, acc) DCI_F_SLAB(IT, 5, f1, f0, acc) DCI_F_SLAB(IT, 6, f0, f1, acc) DCI_F_SLAB(IT, 7, f1, f0, acc)     \
+    if (wave >= 4 && (IT) + 2 < n_my) issue((IT) + 2, ((IT) + 2) % kResBufs); \
+    DCI_F_SLAB(IT, 8, f0, f1, acc) DCI_F_SLAB(IT, 9, f1, f0, acc) DCI_F_SLAB(IT, 10, f0, f1, acc) DCI_F_SLAB(IT, 11, f1, f0, acc)   \
+    DCI_F_SLAB(IT, 12, f0, f1, acc) DCI_F_SLAB(IT, 13, f1, f0, acc) DCI_F_SLAB(IT, 14, f0, f1, acc) DCI_F_SLAB(IT, 15, f1, f0, acc) \
+    store(acc, IT);                                                      \
+  } while (0)
+
+  __syncthreads();  // the zero fill is complete
+  issue(0, 0);
+  if (n_my > 1) issue(1, 1);
+
+  // before the first block: where the rows of blocks 0, 1 and 2 come from; the whole of block 0's aggregated
+  // half; the first eight slots of block 1 in flight
+  {
+    Ix p3[3];
+#pragma unroll
+    for (int t = 0; t < 3; ++t) index_bounds(p3[t], t);
+#pragma unroll
+    for (int t = 0; t < 3; ++t) index_source(p3[t]);
+#pragma unroll
+    for (int t = 0; t < 3; ++t) index_slot(p3[t]);
+#pragma unroll
+    for (int t = 0; t < 3; ++t) index_note(p3[t], t);
+  }
+#pragma unroll
+  for (int P = 0; P < kFuseAhead; ++P) slot_issue(0, P);
+#pragma unroll
+  for (int P = 0; P < kFuseSlots; ++P) {
+    slot_take(0, P);
+    if (P + kFuseAhead < kFuseSlots) slot_issue(0, P + kFuseAhead);
+    else slot_issue(1, P + kFuseAhead - kFuseSlots);
+  }
+  // this wavefront's weights (as in k_sage_linear_res), fetched after the first block's aggregation: together the two would not fit the registers
+  const unsigned off_pair = lane_off * 4u, off_first = (unsigned)col * 4u;
+  float breg[8 * NS];
+#pragma unroll
+  for (int T = 0; T < 2 * NS; ++T) {
+    const int op = 2 * T >= kpc ? 1 : 0;
+    const int kc = 2 * T - op * kpc;
+    const bool first_ok = kc < kc_op, pair_ok = kc + 1 < kc_op;
+    const char* wrow = reinterpret_cast<const char*>(first_ok ? (op ? a.w_neigh : a.w_self) + (size_t)(4 * kc) * N : a.w_self);
+    const unsigned off = pair_ok ? off_pair : off_first;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) breg[4 * T + j] = *reinterpret_cast<const float*>(wrow + (size_t)j * N * 4 + off);
+  }
+
+#pragma unroll
+  for (int T = 0; T < 2 * NS; ++T) {
+    const int op = 2 * T >= kpc ? 1 : 0;
+    const int kc = 2 * T - op * kpc;
+    const bool first_ok = kc < kc_op, pair_ok = kc + 1 < kc_op;
+    if (!pair_ok) {
+      const bool keep = first_ok && h == 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) breg[4 * T + j] = keep ? breg[4 * T + j] : 0.f;
+    }
+  }
+
+  for (int it = 0; it < n_my; ++it) DCI_F_BLOCK(it);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the slots still in flight belong to no block
+#undef DCI_F_BLOCK
+#undef DCI_F_SLAB
+#undef DCI_F_MFMA
+#undef DCI_F_SLOT
+}
+
 struct SageWs {
   float* m;
   float* y[2];
@@ -1144,6 +1427,63 @@ static int32_t forward_in(dci_ctx* ctx, const dci_blocks* blocks, const float* x
     const int D = dims[l], Do = dims[l + 1];
     const int64_t cap = blocks->cap_rows[h] > 0 ? blocks->cap_rows[h] : 1;
     float* y = l == n_layers - 1 ? logits : ws.y[l & 1];
+    // Input layer in one kernel (aggregation inside the weights-in-registers dense layer) where the layer qualifies
+    const bool ref_l = l == 0 && rowref != nullptr;
+    bool fuse_in = false;
+    if (l == 0 && !gcn && ctx->input_layer != 1 && (ctx->linear_kernel == 0 || ctx->linear_kernel == 4)) {
+      const int n_tiles_f = Do / kResCols;
+      const bool shape_ok = Do % kResCols == 0 && D % 4 == 0 && D <= 128 && n_tiles_f > 0 && ctx->num_cus / n_tiles_f >= 1 &&
+                            aligned(x, 16) && (!ref_l || aligned(feat_cache, 16));
+      // By default only where it was measured ahead of the two kernels: up to 13 slabs (large's 2 x 100 columns: 107 us
+      // against 60 + 64).  With all 16 slabs (huge's 2 x 128) the weights leave room for four slots in flight per
+      // lane, the loads no longer keep up, and the kernel takes as long as the two it replaces (160 us).
+      const int slabs_f = (2 * ((D / 4 + 1) & ~1) + 3) / 4;
+      fuse_in = shape_ok && (ctx->input_layer == 2 || (ctx->linear_kernel == 0 && cap >= kResMinRows && slabs_f <= 13));
+    }
+    if (fuse_in) {
+      LinearArgs la;
+      la.counts = counts;
+      la.hop = h;
+      la.a_self = x;
+      la.a_neigh = x;  // not read: the second operand is aggregated inside the kernel
+      la.w_self = w_self[l];
+      la.w_neigh = w_neigh[l];
+      la.single = 0;
+      la.bias = bias[l];
+      la.y = y;
+      la.K = D;
+      la.N = Do;
+      la.relu = l != n_layers - 1;
+      la.n_tiles_n = Do / kResCols;
+      la.split = 1;
+      la.n_tiles = 0;
+      la.part_rows = 0;
+      la.part = nullptr;
+      FuseArgs fa;
+      fa.blk_indptr = reinterpret_cast<const long long*>(blocks->blk_indptr[h]);
+      fa.blk_src = blocks->blk_src[h];
+      fa.rowref = ref_l ? rowref : nullptr;
+      fa.cache = feat_cache;
+      fa.x_src = x;
+      fa.mode = model;
+      const int g_f = ctx->num_cus / la.n_tiles_n;
+      const int slabs = (2 * ((D / 4 + 1) & ~1) + 3) / 4;
+      const dim3 grid_f((unsigned)(g_f * la.n_tiles_n));
+      {
+        Timed timed(ctx, DCI_K_LINEAR_IN);
+        if (slabs <= 4)
+          hipLaunchKernelGGL(k_sage_input_res<4>, grid_f, dim3(kResThreads), 0, ctx->stream, la, fa, g_f);
+        else if (slabs <= 8)
+          hipLaunchKernelGGL(k_sage_input_res<8>, grid_f, dim3(kResThreads), 0, ctx->stream, la, fa, g_f);
+        else if (slabs <= 13)
+          hipLaunchKernelGGL(k_sage_input_res<13>, grid_f, dim3(kResThreads), 0, ctx->stream, la, fa, g_f);
+        else
+          hipLaunchKernelGGL(k_sage_input_res<16>, grid_f, dim3(kResThreads), 0, ctx->stream, la, fa, g_f);
+      }
+      DCI_LAUNCH_CHECK(ctx);
+      x = y;
+      continue;
+    }
     // mean aggregation
     int V = 1;
     const bool cache_al16 = !(l == 0 && rowref) || aligned(feat_cache, 16), cache_al8 = !(l == 0 && rowref) || aligned(feat_cache, 8);

@@ -713,6 +713,8 @@ def test_set_option_rejects_bad_values(env):
     with pytest.raises(dci.DciError):
         ctx.set_option(dci.DCI_OPT_LINEAR_SPLIT, 9)
     with pytest.raises(dci.DciError):
+        ctx.set_option(dci.DCI_OPT_INPUT_LAYER, 3)
+    with pytest.raises(dci.DciError):
         ctx.set_option(99, 0)
 
 
@@ -919,6 +921,57 @@ def test_gather_forward_reads_cached_rows_in_place(env, F, model):
         dci.dci_gnn_forward(ctx, blk, x2, model, None if model == 2 else ws, wn, bs, logits2)
         ctx.sync()
         assert logits2.cpu().numpy().tobytes() == got.tobytes()
+
+
+@pytest.mark.parametrize("F,hidden,fanouts,model,n_seeds", [(128, 256, (5, 10), 0, 200), (100, 256, (5, 10), 1, 333),
+                                                            (64, 512, (3, 16), 0, 97), (4, 256, (2, 25), 0, 150),
+                                                            (124, 256, (4, 40), 1, 64), (128, 256, (7,), 0, 1)])
+def test_input_layer_in_one_kernel_matches_the_two_kernel_route(env, F, hidden, fanouts, model, n_seeds):
+    """The first layer as one kernel (aggregation inside the weights-in-registers dense layer, forced on at small sizes)
+    against the oracle, and bit for bit against the aggregation kernel followed by the same dense kernel: widths that fill
+    all sixteen slabs and that end inside one, one and two 256-column tiles, rows with more edges than the sixteen the
+    pipelined part takes (fan-outs 25 and 40), empty rows, a single seed, with a partly filled feature cache (rows read in
+    place through dci_gather_forward) and with none (dci_gnn_forward on gathered rows)."""
+    dci, gu, ctx, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "tiny", "w"))
+    N = w.num_nodes
+    feat = synth.features(N, F, 90 + F)
+    g = gu.make_graph(tiny["indptr"], tiny["indices"], feat)
+    dims = (F, hidden) if len(fanouts) == 1 else (F, hidden, 10)
+    ws_h, wn_h, b_h = synth.sage_weights(dims, 78)
+    ws, wn, bs = ([gu.dev(a) for a in arr] for arr in (ws_h, wn_h, b_h))
+    seeds = tiny["seeds"][100:100 + n_seeds]
+    want = oracle.sample_khop(tiny["indptr"], tiny["indices"], seeds, 9, fanouts, w.rng_seed)
+    want_x = oracle.gather(feat, want.nodes)
+    ref = oracle.gnn_forward(model, want, want_x, ws_h, wn_h, b_h)
+    rng = np.random.default_rng(F)
+    rows = rng.permutation(N)[:N // 2]
+    remap = np.full(N, -1, dtype=np.int32)
+    remap[rows] = np.arange(len(rows), dtype=np.int32)
+    cache = gu.upload_cache(np.full(N, -1), np.zeros(1, np.int64), np.zeros(0, np.int64), remap, feat[rows])
+    blk = dci.Blocks(ctx, N, len(seeds), fanouts)
+    dci.dci_sample_khop(ctx, g, cache, gu.dev(seeds), 9, fanouts, w.rng_seed, blk)
+    out = {}
+    for kind in (2, 1):
+        ctx.set_option(dci.DCI_OPT_INPUT_LAYER, kind)
+        ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, 4)   # the two-kernel route then ends in the same dense kernel
+        try:
+            x = torch.full((blk.cap_nodes[-1], F), -7.0, dtype=torch.float32, device="cuda")
+            l1 = torch.zeros(len(seeds), dims[-1], dtype=torch.float32, device="cuda")
+            dci.dci_gather_forward(ctx, g, cache, blk, x, model, ws, wn, bs, l1)
+            x2 = torch.empty_like(x)
+            l2 = torch.zeros_like(l1)
+            dci.dci_gather_features(ctx, g, cache, blk.nodes, blk.cap_nodes[-1], x2, n_dev=blk.n_input_dev())
+            dci.dci_gnn_forward(ctx, blk, x2, model, ws, wn, bs, l2)
+            ctx.sync()
+        finally:
+            ctx.set_option(dci.DCI_OPT_INPUT_LAYER, 0)
+            ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, 0)
+        out[kind] = (l1.cpu().numpy(), l2.cpu().numpy())
+        _logit_check(out[kind][0], ref)
+        _logit_check(out[kind][1], ref)
+    assert out[2][0].tobytes() == out[1][0].tobytes()
+    assert out[2][1].tobytes() == out[1][1].tobytes()
+    assert out[2][0].tobytes() == out[2][1].tobytes()
 
 
 def test_gather_forward_rejects_bad_arguments(env):
