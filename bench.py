@@ -83,10 +83,10 @@ def main() -> int:
     ap.add_argument("--fused-input", type=int, default=1, choices=[0, 1],
                     help="1 (default): the input layer reads cached neighbour rows in place (dci_gather_forward: only "
                          "missed rows and the rows of F_{L-1} are copied); 0: dci_gather_features then dci_gnn_forward")
-    ap.add_argument("--input-layer", type=int, default=0, choices=[0, 1, 2],
-                    help="first layer: 0 (default) one kernel that aggregates inside the weights-in-registers dense "
-                         "layer where that kernel would be chosen, 1 always aggregation kernel + dense kernel, "
-                         "2 the one-kernel form wherever the shape allows")
+    ap.add_argument("--input-layer", type=int, default=0, choices=[0, 1, 2, 3],
+                    help="first layer: 0 (default) one kernel (aggregation inside the dense layer) where the layer is "
+                         "large enough and its shape allows one of the two forms, 1 always aggregation kernel + dense kernel, "
+                         "2 / 3 the one-kernel form wherever the shape allows (weights in registers / 64-row tiles)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batches", type=int, default=None, help="batches the single-thread CPU oracle is timed on")
     ap.add_argument("--lanes", type=int, default=4, help="batches in flight in the pipelined regions (0 or 1 = skip them)")
@@ -354,7 +354,7 @@ def main() -> int:
             one_kernel = l == 0 and timing_all[cls_m][1] == 0 and timing_all[cls_l][1] > 0
             if one_kernel:
                 # the input layer ran as one kernel (aggregation inside the dense layer): it answers to both bounds
-                rooflines[cls_l] = entry("k_sage_input_res (aggregation inside the dense layer)", cls_l,
+                rooflines[cls_l] = entry("k_sage_input_res / k_sage_input_tile (aggregation inside the dense layer)", cls_l,
                                          {"hbm": mb / hbm_bw, "mfma": fl / (FP32_MFMA_PEAK_TFLOPS * 1e12)},
                                          {"hbm": mb / GB, "mfma": fl / 1e12},
                                          {"hbm": HBM_PEAK_GBPS, "mfma": FP32_MFMA_PEAK_TFLOPS}, unit_hbm,

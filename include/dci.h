@@ -208,14 +208,19 @@ int32_t dci_last_required(const dci_ctx* ctx, int64_t* cap_nodes, int64_t* cap_e
 /*   DCI_OPT_RELABEL_TILE_ITERS  rows per lane group in a tile of the frontier scan: 0 (default) chosen from
  *       the frontier's size, or 2, 4, 8.  Tuning only: the result does not depend on it. */
 #define DCI_OPT_RELABEL_TILE_ITERS 6
-/*   DCI_OPT_INPUT_LAYER  how the forward pass runs its first layer when that layer qualifies for the
- *       weights-in-registers kernel (see DCI_OPT_LINEAR_KERNEL), has two operands of at most 128 columns and
- *       the mean or sum aggregator: 0 (default) one kernel that aggregates inside the dense layer whenever the
- *       default choice of dense kernel would be the weights-in-registers one and the two operands together are
- *       at most 208 columns (13 slabs of 16) - beyond that the weights leave too few registers for the loads
- *       in flight and the single kernel is no faster; 1 always the aggregation kernel followed by a dense
- *       kernel; 2 the one-kernel form whenever widths and alignment allow it, whatever the row count.  The
- *       result is bit-identical: every sum runs in the same order. */
+/*   DCI_OPT_INPUT_LAYER  how the forward pass runs its first layer (two operands of at most 128 columns, mean or
+ *       sum aggregator).  There are two one-kernel forms that keep the aggregated rows out of device memory:
+ *       "registers" - the aggregation runs inside the weights-in-registers dense kernel (needs what that kernel
+ *       needs, see DCI_OPT_LINEAR_KERNEL) - and "tiles" - half of each workgroup aggregates 64 rows into LDS while
+ *       the other half multiplies the 64 rows before (needs a width that is a multiple of 16, at least 32, an
+ *       output width that is a multiple of 64, 16-byte aligned rows, weights, bias and output).
+ *       0 (default): for layers of at least 98,304 rows (capacity) the registers form if the two operands together
+ *       are at most 208 columns (13 slabs of 16: beyond that the weights leave too few registers for the loads in
+ *       flight), else the tiles form if the shape allows it, else two kernels;  1: always the aggregation kernel
+ *       followed by a dense kernel;  2: the registers form whenever widths and alignment allow it, whatever the
+ *       row count;  3: the tiles form likewise.  The registers form is bit-identical to the two-kernel route; the
+ *       tiles form is bit-identical to it where the contraction needs no padding (width a multiple of 16) and the
+ *       two-kernel route ends in the weights-in-registers kernel, and within rounding of it otherwise. */
 #define DCI_OPT_INPUT_LAYER 7
 int32_t dci_set_option(dci_ctx* ctx, int32_t option, int64_t value);
 

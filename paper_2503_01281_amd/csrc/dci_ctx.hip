@@ -200,7 +200,7 @@ int32_t dci_set_option(dci_ctx* ctx, int32_t option, int64_t value) {
     return DCI_OK;
   }
   if (option == DCI_OPT_INPUT_LAYER) {
-    if (value < 0 || value > 2) return dci::fail(ctx, DCI_ERR_INVALID_ARG, "DCI_OPT_INPUT_LAYER takes 0, 1 or 2, not %lld", (long long)value);
+    if (value < 0 || value > 3) return dci::fail(ctx, DCI_ERR_INVALID_ARG, "DCI_OPT_INPUT_LAYER takes 0 .. 3, not %lld", (long long)value);
     ctx->input_layer = (int)value;
     return DCI_OK;
   }

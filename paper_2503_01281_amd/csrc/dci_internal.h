@@ -33,7 +33,7 @@ struct dci_ctx {
   int64_t req_edges[DCI_MAX_HOPS] = {0};
   size_t req_workspace = 0;
   int relabel_tile_iters = 0;  // DCI_OPT_RELABEL_TILE_ITERS: 0 = by frontier size, else 2, 4 or 8 rows per lane group
-  int input_layer = 0;    // DCI_OPT_INPUT_LAYER: 0 by shape, 1 aggregation and dense layer as two kernels, 2 one kernel where the shape allows
+  int input_layer = 0;    // DCI_OPT_INPUT_LAYER: 0 by shape, 1 aggregation and dense layer as two kernels, 2 / 3 one kernel where the shape allows (weights in registers / 64-row tiles)
   int fused_input = 0;    // DCI_OPT_FUSED_INPUT: dci_infer_batches lets the first layer read cached rows in place
   int linear_split = 0;   // DCI_OPT_LINEAR_SPLIT: 0 = by shape, n = at most n workgroups per tile
   int linear_kernel = 0;  // DCI_OPT_LINEAR_KERNEL: 0 by shape, 1 tile kernel, 2 wide kernel where the shape allows

@@ -7,8 +7,9 @@
 //                        destination row, consecutive lanes on consecutive chunks of the row;
 //   a dense-layer kernel - y = x W_self + m W_neigh + b (+ ReLU) (GCN: y = m W + b): one contraction
 //                        over the concatenated axis on the matrix cores (v_mfma_f32_32x32x2f32, fp32 in,
-//                        fp32 accumulate).  Four of them, chosen by the layer's shape (and a fifth,
-//                        k_sage_input_res, that does the input layer's aggregation inside the first of them):
+//                        fp32 accumulate).  Four of them, chosen by the layer's shape (and two more,
+//                        k_sage_input_res and k_sage_input_tile, that do the input layer's aggregation themselves
+//                        and keep the aggregated rows out of device memory):
 //       k_sage_linear_res   weights kept in registers, 32-row blocks streamed through LDS (tall layers
 //                           whose whole contraction is at most 256 long, 256-column tiles);
 //       k_sage_linear_wide  192x128 passes, one workgroup per compute unit, global->LDS loads
@@ -373,6 +374,12 @@ typedef float float2v __attribute__((ext_vector_type(2)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
+// A 16-byte load through a pointer that is known to be global memory.  An address that went through an integer (a
+// shuffle, a note in LDS) has lost its address space; loaded through a generic pointer it would count against the
+// LDS counter as well as the memory counter, and every wait for an LDS read would wait for it too.
+typedef __attribute__((address_space(1))) const float4v* gf4ptr_t;
+typedef __attribute__((address_space(1))) const float* gfptr_t;
+__device__ __forceinline__ float4v load_global_f4(const float* p) { return *(gf4ptr_t)(p); }
 
 constexpr long long kWideMinRows = 16384;  // below this capacity the 64x64 kernel (with its split contraction) fills the chip better
 constexpr int kWideMinWidth = 192;  // narrower inputs spend the kernel in its pipeline fill and drain (measured cross-over with the 64x64 kernel)
@@ -1058,7 +1065,7 @@ __global__ __launch_bounds__(kResThreads, 1) void k_sage_linear_res(LinearArgs a
 // Rows with more than 16 edges take the rest in a plain loop when the row is finished.
 // Needs what k_sage_linear_res needs, two operands of at most 128 columns, and the mean or sum aggregator.
 constexpr int kFuseSlots = 32, kFuseFan = 16, kFuseRing = 4;
-__device__ const float4 kFuseZeros[64] = {};  // what the slot of an edge that does not exist loads (one line per lane group, always zero)
+__device__ float4 kFuseZeros[64] = {};  // what the slot of an edge that does not exist loads (one line per lane group, always zero)
 struct FuseNote {               // per wavefront and block, in LDS
   unsigned long long base[64];  // lane 16 q + e: address of the source row of edge e of the wavefront's row q
   long long lo[4];              // first edge of row q
@@ -1177,7 +1184,7 @@ __global__ __launch_bounds__(kResThreads, 1) void k_sage_input_res(LinearArgs a,
     const int q = 2 * (P >> 4) + h, j = P & 15;
     const bool on = lane_on && j < nb.cnt[q];
     const float* p = on ? reinterpret_cast<const float*>((uintptr_t)nb.base[16 * q + j]) + 4 * ll : zeros;
-    land[P & (kFuseAhead - 1)] = *reinterpret_cast<const float4v*>(p);
+    land[P & (kFuseAhead - 1)] = load_global_f4(p);
   };
   auto row_done = [&](int t, int rp) {  // the two rows of row pair rp of block t are complete: write them to the block's buffer
     const FuseNote& nb = notes[t & (kFuseRing - 1)][wave];
@@ -1189,7 +1196,7 @@ __global__ __launch_bounds__(kResThreads, 1) void k_sage_input_res(LinearArgs a,
         const int sidx = fa.blk_src[lo + e];
         const int rr = fa.rowref ? fa.rowref[sidx] : -1;
         const float* p = rr >= 0 ? fa.cache + (long long)rr * K : fa.x_src + (long long)sidx * K;
-        agg += *reinterpret_cast<const float4v*>(p + 4 * ll);
+        agg += load_global_f4(p + 4 * ll);
       }
     }
     const float fc = (float)cnt;
@@ -1329,6 +1336,313 @@ __global__ __launch_bounds__(kResThreads, 1) void k_sage_input_res(LinearArgs a,
 #undef DCI_F_SLOT
 }
 
+// ---- input layer in one kernel, 64-row tiles: some wavefronts aggregate while the others multiply -------
+// The other way to keep the aggregated rows out of HBM.  A workgroup (one per compute unit, eight wavefronts)
+// walks 64-row tiles.  A tile's left operand - its self rows and its aggregated rows side by side, 64 rows x 2K,
+// at most 64 KB - is built in LDS in the [slab][row][4 chunks] layout of k_sage_linear_dma by wavefronts 4 - 7:
+// the self rows arrive by global->LDS loads; the aggregated rows they sum themselves (a half-wavefront per row, a
+// lane per 16-byte chunk, edge after edge in edge order as k_sage_mean does).  These wavefronts keep no weights or
+// accumulators, so their registers hold loads in flight: two row pairs of sixteen 16-byte loads per lane.
+// Meanwhile wavefronts 0 - 3 multiply the tile built one step earlier (two such buffers) with the weights, one
+// pass of 128 output columns after the other (32 per wavefront): every output element is one running sum over k in
+// ascending order, as in k_sage_linear_res (so the one-kernel route and the two-kernel route that ends in that kernel
+// agree to the bit), and every wavefront loads the weight values it needs straight into registers, several slabs ahead,
+// so that the multiplying wavefronts never wait for each other and the whole workgroup meets at one barrier per tile.
+// Needs two operands of K columns, 32 <= K <= 128, K a multiple of 16, an output width that is a multiple of 64,
+// 16-byte aligned rows and weights.
+constexpr int kTileInThreads = 512, kTileInMaxSlabs = 16, kTileInFan = 16, kTileInAhead = 4;
+constexpr int kTileInSlabBytes = TM * TK * 4;
+constexpr int kTileInBufBytes = kTileInMaxSlabs * kTileInSlabBytes;  // 64 KB
+constexpr int kTileInOutBytes = TM * 32 * 4;                         // a wavefront's 64 x 32 results on their way out
+constexpr int kTileInLds = 2 * kTileInBufBytes + 4 * kTileInOutBytes;  // 160 KB
+
+struct FragA {
+  float4v a0, a1;  // rows 0 - 31 of the tile: four consecutive k of this lane's row, t = 0, 1
+  float4v c0, c1;  // rows 32 - 63
+};
+#define DCI_T_READ(f, SLAB)                                                                            \
+  asm volatile("ds_read_b128 %0, %4 offset:%6\n\tds_read_b128 %1, %5 offset:%6\n\t"                   \
+               "ds_read_b128 %2, %4 offset:%7\n\tds_read_b128 %3, %5 offset:%7"                        \
+               : "=&v"(f.a0), "=&v"(f.a1), "=&v"(f.c0), "=&v"(f.c1)                                    \
+               : "v"(la0), "v"(la1), "n"((SLAB)*kTileInSlabBytes), "n"((SLAB)*kTileInSlabBytes + 2048) \
+               : "memory")
+#define DCI_T_WAIT(f)                                                              \
+  do {                                                                             \
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                             \
+    asm volatile("" : "+v"(f.a0), "+v"(f.a1), "+v"(f.c0), "+v"(f.c1)::"memory");   \
+  } while (0)
+
+template <int SF>
+__global__ __launch_bounds__(kTileInThreads, 1) void k_sage_input_tile(LinearArgs a, FuseArgs fa) {
+  static_assert(SF >= 2 && 2 * SF <= kTileInMaxSlabs, "slabs per operand");
+  __shared__ __attribute__((aligned(1024))) char lds[kTileInLds];
+  const long long M = a.counts[a.hop];
+  const long long n_tiles = (M + TM - 1) / TM;
+  if ((long long)blockIdx.x >= n_tiles) return;
+  const int n_my = (int)((n_tiles - blockIdx.x + gridDim.x - 1) / gridDim.x);  // tiles blockIdx.x, + gridDim.x, ...
+  const int tid = (int)threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int h = lane >> 5, ll = lane & 31;
+  const int K = a.K, N = a.N;
+  constexpr int Sf = SF;  // slabs per operand (K = 16 SF); a tile's slabs: 0 .. Sf-1 self rows, Sf .. 2 Sf-1 aggregated rows
+  constexpr int n = 2 * Sf;
+
+  if (wave >= 4) {
+    // ================= building tiles =================
+    const int pw = wave - 4;
+    const long long* const zeros_ll = reinterpret_cast<const long long*>(kFuseZeros);
+    const int* const zeros_i = reinterpret_cast<const int*>(kFuseZeros);
+    const float* const zeros_f = reinterpret_cast<const float*>(kFuseZeros) + 4 * lane;
+    const bool lane_on = ll < K / 4;
+    const float4v zero4 = {0.f, 0.f, 0.f, 0.f};
+    const int c_a = (lane & 3) ^ ((lane >> 4) & 3);
+    for (int it = 0; it < n_my; ++it) {
+      {
+        char* const buf = lds + (it & 1) * kTileInBufBytes;
+        const long long row0 = ((long long)blockIdx.x + (long long)it * gridDim.x) * TM;
+        // self rows: this wave's sixteen rows of every slab (lane -> row, chunk of four k; chunk position xor-ed with row bits)
+        {
+          long long r_l = row0 + 16 * pw + (lane >> 2);
+          if (r_l > M - 1) r_l = M - 1;
+          const float* pa = a.a_self + r_l * K + 4 * c_a;
+#pragma unroll
+          for (int s = 0; s < Sf; ++s)
+            __builtin_amdgcn_global_load_lds((gptr_t)(pa + TK * s), (lptr_t)(buf + s * kTileInSlabBytes + 1024 * pw), 16, 0, 0);
+        }
+        // aggregated rows 16 pw .. 16 pw + 15 of the tile, two at a time (one per half of the wavefront).  Every load below
+        // is issued by every lane, from a line of zeros where there is nothing to read: straight-line code, so that
+        // the loads of two row pairs are in flight together and only the oldest are waited for.
+        constexpr int RP = 8;
+        int lo[RP], cn[RP];
+#pragma unroll
+        for (int rp = 0; rp < RP; ++rp) {
+          const long long R = row0 + 16 * pw + 2 * rp + h;
+          const long long* pb = R < M ? fa.blk_indptr + R : zeros_ll;
+          const long long e0 = pb[0], e1 = pb[1];
+          lo[rp] = (int)e0;  // edge numbers stay below 2^31 (the batch bounds are checked against that)
+          cn[rp] = (int)(e1 - e0);
+        }
+        // lane e < 16 of a half: where the row of edge e of the half's row is
+        int sidx[RP];
+        bool on[RP];
+#pragma unroll
+        for (int rp = 0; rp < RP; ++rp) {
+          on[rp] = ll < kTileInFan && ll < cn[rp];
+          sidx[rp] = *(on[rp] ? fa.blk_src + ((long long)lo[rp] + ll) : zeros_i);
+        }
+        const float* bp[RP];
+        if (fa.rowref) {
+#pragma unroll
+          for (int rp = 0; rp < RP; ++rp) {
+            const int rr = *(on[rp] ? fa.rowref + sidx[rp] : zeros_i);
+            bp[rp] = (on[rp] && rr >= 0) ? fa.cache + (long long)rr * K : fa.x_src + (long long)sidx[rp] * K;
+          }
+        } else {
+#pragma unroll
+          for (int rp = 0; rp < RP; ++rp) bp[rp] = fa.x_src + (long long)sidx[rp] * K;
+        }
+        float4v land[2][kTileInFan];
+        auto request = [&](int rp, float4v* v, int j0, int j1) {  // slots j0 .. j1-1 of the row pair
+#pragma unroll
+          for (int j = 0; j < kTileInFan; ++j) {
+            if (j < j0 || j >= j1) continue;
+            const unsigned long long pj = __shfl((unsigned long long)reinterpret_cast<uintptr_t>(bp[rp]), (lane & 32) + j, kWave);
+            const float* p = (lane_on && j < cn[rp]) ? reinterpret_cast<const float*>((uintptr_t)pj) + 4 * ll : zeros_f;
+            v[j] = load_global_f4(p);
+          }
+        };
+        auto finish = [&](int rp, const float4v* v) {
+          float4v agg = zero4;
+#pragma unroll
+          for (int j = 0; j < kTileInFan; ++j) agg += v[j];  // slots beyond the row's edges hold zero
+          const int cnt = cn[rp];
+          if (cnt > kTileInFan && lane_on) {
+            for (int e = kTileInFan; e < cnt; ++e) {
+              const int s = fa.blk_src[(long long)lo[rp] + e];
+              const int rr = fa.rowref ? fa.rowref[s] : -1;
+              const float* p = rr >= 0 ? fa.cache + (long long)rr * K : fa.x_src + (long long)s * K;
+              agg += load_global_f4(p + 4 * ll);
+            }
+          }
+          const float fc = (float)cnt;
+          const float4v r = (fa.mode == DCI_MODEL_SAGE_SUM || cnt == 0) ? agg : agg / fc;
+          if (lane_on) {
+            const int row = 16 * pw + 2 * rp + h;
+            char* dst = buf + (Sf + (ll >> 2)) * kTileInSlabBytes + row * 64 + (((ll & 3) ^ ((row >> 2) & 3)) * 16);
+            *reinterpret_cast<float4v*>(dst) = r;
+          }
+        };
+        // the next row pair's first kTileInAhead slots are requested before the current one is summed, the rest after:
+        // 16 + kTileInAhead loads per lane in flight at most.  (Deeper queues only add to the latency that the other
+        // wavefronts' weight loads see behind them.)
+        request(0, land[0], 0, kTileInFan);
+#pragma unroll
+        for (int rp = 0; rp < RP; rp += 2) {
+          request(rp + 1, land[1], 0, kTileInAhead);
+          finish(rp, land[0]);
+          request(rp + 1, land[1], kTileInAhead, kTileInFan);
+          if (rp + 2 < RP) request(rp + 2, land[0], 0, kTileInAhead);
+          finish(rp + 1, land[1]);
+          if (rp + 2 < RP) request(rp + 2, land[0], kTileInAhead, kTileInFan);
+        }
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // the self rows have landed, the aggregated rows are written
+      }
+      __builtin_amdgcn_s_barrier();  // tile `it` is complete; the other wavefronts are done with the buffer of tile it - 1
+    }
+    return;
+  }
+
+  // ================= multiplying tiles =================
+  // Wavefront w multiplies all 64 rows of the tile with 32 columns of the weights (columns 128 p + 32 w + 0..31 in pass
+  // p over the output's columns): a weight value it loads serves two matrix instructions (rows 0 - 31 and 32 - 63).
+  const unsigned lds0 = (unsigned)(size_t)(lptr_t)lds;
+  const int cw = 32 * wave;
+  // The weights go straight to registers: per slab and lane the eight values B[k][column] of its column, k = 4 h + 0..3
+  // and 8 + 4 h + 0..3 (a load covers two k rows x 32 consecutive columns).  D register sets in rotation hold the slabs
+  // to come; a slab is requested P = D - 2 steps before its turn into the set that was multiplied two steps ago (see
+  // the note on fragment registers below; a global load is far slower than the two matrix instructions that can be
+  // waiting).  D divides the slabs of a pass, so that a slab's set is the same in every pass and all register indices
+  // are compile-time values.
+  constexpr int D = n <= 8 ? n : n / 2, P = D - 2;
+  static_assert(n % D == 0 && P >= 2, "rotation of the weight registers");
+  const unsigned lane_off = (unsigned)(4 * h * N + ll);
+  float bq[D][8];
+  // q_s, q_c: the next slab to request (the wavefront streams n_my * passes * n slabs: tile after tile, pass after
+  // pass; the weights do not depend on the tile).  A wavefront whose columns lie beyond the output's width in the
+  // last pass (N = 64 mod 128) loads columns 0 - 31 instead and stores nothing.
+  const int n_pass = (N + 127) / 128;
+  int q_s = 0, q_c = 0;
+#define DCI_T_LOADB(SET)                                                                                       \
+  do {                                                                                                         \
+    const int qc_ = q_c + cw < N ? q_c + cw : 0;                                                               \
+    const float* w_ = (q_s >= Sf ? a.w_neigh + (size_t)(q_s - Sf) * TK * N : a.w_self + (size_t)q_s * TK * N) + qc_; \
+    gfptr_t wp_ = (gfptr_t)(w_ + lane_off); /* one pointer stepped from k row to k row: eight addresses would cost 16 registers */ \
+    _Pragma("unroll") for (int j_ = 0; j_ < 8; ++j_) {                                                        \
+      asm volatile("" : "+v"(wp_));                                                                            \
+      bq[SET][j_] = *wp_;                                                                                      \
+      wp_ += j_ == 3 ? 5 * (size_t)N : (size_t)N;                                                              \
+    }                                                                                                          \
+    if (++q_s == n) {                                                                                          \
+      q_s = 0;                                                                                                 \
+      q_c += 128;                                                                                              \
+      if (q_c >= N) q_c = 0;                                                                                   \
+    }                                                                                                          \
+  } while (0)
+// Per output element one running sum over k in ascending order, as in k_sage_linear_res; the two row blocks alternate,
+// so that a matrix instruction never waits for the one just before it.
+#define DCI_T_MFMA(f, SET)                                                                 \
+  do {                                                                                     \
+    __builtin_amdgcn_sched_barrier(0);                                                     \
+    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a0.x, bq[SET][0], acc0, 0, 0, 0);        \
+    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.c0.x, bq[SET][0], acc1, 0, 0, 0);        \
+    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a0.y, bq[SET][1], acc0, 0, 0, 0);        \
+    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.c0.y, bq[SET][1], acc1, 0, 0, 0);        \
+    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a0.z, bq[SET][2], acc0, 0, 0, 0);        \
+    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.c0.z, bq[SET][2], acc1, 0, 0, 0);        \
+    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a0.w, bq[SET][3], acc0, 0, 0, 0);        \
+    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.c0.w, bq[SET][3], acc1, 0, 0, 0);        \
+    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a1.x, bq[SET][4], acc0, 0, 0, 0);        \
+    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.c1.x, bq[SET][4], acc1, 0, 0, 0);        \
+    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a1.y, bq[SET][5], acc0, 0, 0, 0);        \
+    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.c1.y, bq[SET][5], acc1, 0, 0, 0);        \
+    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a1.z, bq[SET][6], acc0, 0, 0, 0);        \
+    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.c1.z, bq[SET][6], acc1, 0, 0, 0);        \
+    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a1.w, bq[SET][7], acc0, 0, 0, 0);        \
+    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(f.c1.w, bq[SET][7], acc1, 0, 0, 0);        \
+    __builtin_amdgcn_sched_barrier(0);                                                     \
+  } while (0)
+// Slab I of a pass, its row fragments in FC: request the weights of the slab P steps on (of the next pass or the next
+// tile past the end of this one; LAST: the very last pass, where there is nothing further), read the next slab's row
+// fragments if it belongs to this pass (the next pass reads its first ones itself: after a barrier they come from
+// the other buffer), multiply.
+#define DCI_T_STEP(FC, FN, FP, I, LAST)                                                \
+  if ((I) < n) {                                                                       \
+    DCI_T_WAIT(FC);                                                                    \
+    if (!(LAST) || (I) + P < n) DCI_T_LOADB(((I) + P) % D);                            \
+    if ((I) + 1 < n) DCI_T_READ(FN, ((I) + 1) % kTileInMaxSlabs);                      \
+    DCI_T_MFMA(FC, (I) % D);                                                           \
+    asm volatile("" : "+v"(FP.a0), "+v"(FP.a1), "+v"(FP.c0), "+v"(FP.c1));             \
+  }
+// Three sets of fragment registers in rotation: a step's reads land where the matrix instructions of two steps before
+// read, never in registers that instructions still waiting for the matrix pipe may have to read (each matrix instruction
+// depends on an earlier one of the step in between, so those of two steps before are complete).  The empty statement
+// after a step's matrix instructions keeps the previous step's set alive, so that the three really are three sets of
+// registers.  A pass starts in f0 (whatever used f0 last is complete by then: the sums have been stored); its first read
+// stands inside the pass's code, after the branch that selects it, because nothing - not even a register copy that the
+// compiler places at a branch - may touch the registers between a read and its wait: the compiler takes the read's
+// results for present as soon as the statement that issues it is over.
+#define DCI_T_PASS(LAST)                                                                                          \
+  do {                                                                                                            \
+    DCI_T_READ(f0, 0);                                                                                            \
+    DCI_T_STEP(f0, f1, f2, 0, LAST) DCI_T_STEP(f1, f2, f0, 1, LAST) DCI_T_STEP(f2, f0, f1, 2, LAST)               \
+    DCI_T_STEP(f0, f1, f2, 3, LAST) DCI_T_STEP(f1, f2, f0, 4, LAST) DCI_T_STEP(f2, f0, f1, 5, LAST)               \
+    DCI_T_STEP(f0, f1, f2, 6, LAST) DCI_T_STEP(f1, f2, f0, 7, LAST) DCI_T_STEP(f2, f0, f1, 8, LAST)               \
+    DCI_T_STEP(f0, f1, f2, 9, LAST) DCI_T_STEP(f1, f2, f0, 10, LAST) DCI_T_STEP(f2, f0, f1, 11, LAST)             \
+    DCI_T_STEP(f0, f1, f2, 12, LAST) DCI_T_STEP(f1, f2, f0, 13, LAST) DCI_T_STEP(f2, f0, f1, 14, LAST)            \
+    DCI_T_STEP(f0, f1, f2, 15, LAST)                                                                              \
+  } while (0)
+
+  FragA f0 = {}, f1 = {}, f2 = {};
+#pragma unroll
+  for (int i = 0; i < P; ++i) DCI_T_LOADB(i);  // slabs 0 .. P-1 of the first pass
+  for (int it = 0; it < n_my; ++it) {
+    const long long row0 = ((long long)blockIdx.x + (long long)it * gridDim.x) * TM;
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wavefront's reads of the previous tile's buffer are complete
+    __builtin_amdgcn_s_barrier();                        // tile `it` is in its buffer
+    const unsigned la0 = lds0 + (it & 1) * kTileInBufBytes + ll * 64 + ((h ^ ((ll >> 2) & 3)) * 16);
+    const unsigned la1 = la0 ^ 32u;
+    for (int pass = 0; pass < n_pass; ++pass) {
+      floatx16 acc0, acc1;  // rows 0 - 31 and 32 - 63
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        acc0[r] = 0.f;
+        acc1[r] = 0.f;
+      }
+      if (it == n_my - 1 && pass == n_pass - 1) DCI_T_PASS(true);
+      else DCI_T_PASS(false);
+      // Out through the wavefront's own 8 KB of LDS, so that a lane stores 16 bytes of a row: eight stores per pass
+      // instead of 32.  The wavefront's memory operations retire in order, so a wait for a weight load also waits for
+      // every store before it; 32 stores between the loads would fill the counter and hold the next pass up for as
+      // long as the stores take.
+      if (pass * 128 + cw < N) {
+        float* const ob = reinterpret_cast<float*>(lds + 2 * kTileInBufBytes + wave * kTileInOutBytes);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = 8 * (r >> 2) + 4 * h + (r & 3);
+          ob[row * 32 + ll] = acc0[r];
+          ob[(row + 32) * 32 + ll] = acc1[r];
+        }
+        const int c4 = 4 * (lane & 7);
+        const int colb = pass * 128 + cw + c4;
+        const float4v b4 = *reinterpret_cast<const float4v*>(a.bias + colb);
+        typedef __attribute__((address_space(1))) float4v* gy4ptr_t;
+        __attribute__((address_space(1))) float* yp = (__attribute__((address_space(1))) float*)(a.y + (row0 + (lane >> 3)) * N + colb);
+        asm volatile("" : "+v"(yp));  // keeps the compiler from holding eight row addresses in registers from tile start on
+        const size_t N8 = (size_t)N * 8;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int row = 8 * i + (lane >> 3);
+          float4v v = *reinterpret_cast<const float4v*>(ob + row * 32 + c4) + b4;
+          if (a.relu) {
+            v.x = v.x > 0.f ? v.x : 0.f;
+            v.y = v.y > 0.f ? v.y : 0.f;
+            v.z = v.z > 0.f ? v.z : 0.f;
+            v.w = v.w > 0.f ? v.w : 0.f;
+          }
+          if (row0 + row < M) *(gy4ptr_t)(yp) = v;
+          yp += N8;
+        }
+      }
+    }
+  }
+#undef DCI_T_PASS
+#undef DCI_T_STEP
+#undef DCI_T_MFMA
+#undef DCI_T_LOADB
+}
+#undef DCI_T_READ
+#undef DCI_T_WAIT
+
 struct SageWs {
   float* m;
   float* y[2];
@@ -1439,6 +1753,57 @@ static int32_t forward_in(dci_ctx* ctx, const dci_blocks* blocks, const float* x
       // lane, the loads no longer keep up, and the kernel takes as long as the two it replaces (160 us).
       const int slabs_f = (2 * ((D / 4 + 1) & ~1) + 3) / 4;
       fuse_in = shape_ok && (ctx->input_layer == 2 || (ctx->linear_kernel == 0 && cap >= kResMinRows && slabs_f <= 13));
+    }
+    // The 64-row-tile form of the same: aggregate into LDS, then multiply (k_sage_input_tile)
+    bool tile_in = false;
+    if (l == 0 && !gcn && !fuse_in && (ctx->input_layer == 3 || ctx->input_layer == 0) && (ctx->linear_kernel == 0 || ctx->linear_kernel == 4)) {
+      const bool shape_ok = Do % TN == 0 && D % TK == 0 && D >= 2 * TK && D <= 128 && aligned(x, 16) && (!ref_l || aligned(feat_cache, 16)) &&
+                            aligned(w_self[l], 16) && aligned(w_neigh[l], 16) && aligned(y, 16) && aligned(bias[l], 16) && (cap + TM - 1) / TM < ((int64_t)1 << 31);
+      tile_in = shape_ok && (ctx->input_layer == 3 || (ctx->linear_kernel == 0 && cap >= kResMinRows));
+    }
+    if (tile_in) {
+      LinearArgs la;
+      la.counts = counts;
+      la.hop = h;
+      la.a_self = x;
+      la.a_neigh = x;  // not read: the second operand is aggregated inside the kernel
+      la.w_self = w_self[l];
+      la.w_neigh = w_neigh[l];
+      la.single = 0;
+      la.bias = bias[l];
+      la.y = y;
+      la.K = D;
+      la.N = Do;
+      la.relu = l != n_layers - 1;
+      la.n_tiles_n = Do / TN;
+      la.split = 1;
+      la.n_tiles = 0;
+      la.part_rows = 0;
+      la.part = nullptr;
+      FuseArgs fa;
+      fa.blk_indptr = reinterpret_cast<const long long*>(blocks->blk_indptr[h]);
+      fa.blk_src = blocks->blk_src[h];
+      fa.rowref = ref_l ? rowref : nullptr;
+      fa.cache = feat_cache;
+      fa.x_src = x;
+      fa.mode = model;
+      {
+        Timed timed(ctx, DCI_K_LINEAR_IN);
+        const int64_t tiles_cap = (cap + TM - 1) / TM;
+        const dim3 grid_t((unsigned)(tiles_cap < ctx->num_cus ? tiles_cap : ctx->num_cus));
+        switch (D / TK) {
+          case 2: hipLaunchKernelGGL(k_sage_input_tile<2>, grid_t, dim3(kTileInThreads), 0, ctx->stream, la, fa); break;
+          case 3: hipLaunchKernelGGL(k_sage_input_tile<3>, grid_t, dim3(kTileInThreads), 0, ctx->stream, la, fa); break;
+          case 4: hipLaunchKernelGGL(k_sage_input_tile<4>, grid_t, dim3(kTileInThreads), 0, ctx->stream, la, fa); break;
+          case 5: hipLaunchKernelGGL(k_sage_input_tile<5>, grid_t, dim3(kTileInThreads), 0, ctx->stream, la, fa); break;
+          case 6: hipLaunchKernelGGL(k_sage_input_tile<6>, grid_t, dim3(kTileInThreads), 0, ctx->stream, la, fa); break;
+          case 7: hipLaunchKernelGGL(k_sage_input_tile<7>, grid_t, dim3(kTileInThreads), 0, ctx->stream, la, fa); break;
+          default: hipLaunchKernelGGL(k_sage_input_tile<8>, grid_t, dim3(kTileInThreads), 0, ctx->stream, la, fa); break;
+        }
+      }
+      DCI_LAUNCH_CHECK(ctx);
+      x = y;
+      continue;
     }
     if (fuse_in) {
       LinearArgs la;

@@ -713,7 +713,7 @@ def test_set_option_rejects_bad_values(env):
     with pytest.raises(dci.DciError):
         ctx.set_option(dci.DCI_OPT_LINEAR_SPLIT, 9)
     with pytest.raises(dci.DciError):
-        ctx.set_option(dci.DCI_OPT_INPUT_LAYER, 3)
+        ctx.set_option(dci.DCI_OPT_INPUT_LAYER, 4)
     with pytest.raises(dci.DciError):
         ctx.set_option(99, 0)
 
@@ -972,6 +972,59 @@ def test_input_layer_in_one_kernel_matches_the_two_kernel_route(env, F, hidden, 
     assert out[2][0].tobytes() == out[1][0].tobytes()
     assert out[2][1].tobytes() == out[1][1].tobytes()
     assert out[2][0].tobytes() == out[2][1].tobytes()
+
+
+@pytest.mark.parametrize("F,hidden,fanouts,model,n_seeds", [(128, 256, (5, 10), 0, 200), (112, 320, (5, 10), 1, 333),
+                                                            (64, 512, (3, 16), 0, 97), (32, 64, (2, 25), 0, 150),
+                                                            (48, 192, (4, 40), 1, 64), (128, 256, (7,), 0, 1)])
+def test_input_layer_in_one_kernel_of_64_row_tiles(env, F, hidden, fanouts, model, n_seeds):
+    """The first layer as one kernel in its other form (half of a workgroup aggregates 64 rows into LDS while the other
+    half multiplies the 64 before), forced on at small sizes: against the oracle, and - where the output width allows
+    that kernel - bit for bit against the aggregation kernel followed by the weights-in-registers dense kernel, whose
+    order of summation it shares.  Two to eight slabs per operand, output widths that end inside a pass of 128 columns,
+    rows with more edges than the sixteen loaded at once, empty rows, a last tile of one row, cached rows read in place
+    and gathered rows."""
+    dci, gu, ctx, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "tiny", "w"))
+    N = w.num_nodes
+    feat = synth.features(N, F, 190 + F)
+    g = gu.make_graph(tiny["indptr"], tiny["indices"], feat)
+    dims = (F, hidden) if len(fanouts) == 1 else (F, hidden, 10)
+    ws_h, wn_h, b_h = synth.sage_weights(dims, 79)
+    ws, wn, bs = ([gu.dev(a) for a in arr] for arr in (ws_h, wn_h, b_h))
+    seeds = tiny["seeds"][50:50 + n_seeds]
+    want = oracle.sample_khop(tiny["indptr"], tiny["indices"], seeds, 11, fanouts, w.rng_seed)
+    want_x = oracle.gather(feat, want.nodes)
+    ref = oracle.gnn_forward(model, want, want_x, ws_h, wn_h, b_h)
+    rng = np.random.default_rng(F + 1)
+    rows = rng.permutation(N)[:N // 2]
+    remap = np.full(N, -1, dtype=np.int32)
+    remap[rows] = np.arange(len(rows), dtype=np.int32)
+    cache = gu.upload_cache(np.full(N, -1), np.zeros(1, np.int64), np.zeros(0, np.int64), remap, feat[rows])
+    blk = dci.Blocks(ctx, N, len(seeds), fanouts)
+    dci.dci_sample_khop(ctx, g, cache, gu.dev(seeds), 11, fanouts, w.rng_seed, blk)
+    out = {}
+    for kind in (3, 1):
+        ctx.set_option(dci.DCI_OPT_INPUT_LAYER, kind)
+        ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, 4)
+        try:
+            x = torch.full((blk.cap_nodes[-1], F), -7.0, dtype=torch.float32, device="cuda")
+            l1 = torch.zeros(len(seeds), dims[-1], dtype=torch.float32, device="cuda")
+            dci.dci_gather_forward(ctx, g, cache, blk, x, model, ws, wn, bs, l1)
+            x2 = torch.empty_like(x)
+            l2 = torch.zeros_like(l1)
+            dci.dci_gather_features(ctx, g, cache, blk.nodes, blk.cap_nodes[-1], x2, n_dev=blk.n_input_dev())
+            dci.dci_gnn_forward(ctx, blk, x2, model, ws, wn, bs, l2)
+            ctx.sync()
+        finally:
+            ctx.set_option(dci.DCI_OPT_INPUT_LAYER, 0)
+            ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, 0)
+        out[kind] = (l1.cpu().numpy(), l2.cpu().numpy())
+        _logit_check(out[kind][0], ref)
+        _logit_check(out[kind][1], ref)
+    assert out[3][0].tobytes() == out[3][1].tobytes()
+    if hidden % 256 == 0:
+        assert out[3][0].tobytes() == out[1][0].tobytes()
+        assert out[3][1].tobytes() == out[1][1].tobytes()
 
 
 def test_gather_forward_rejects_bad_arguments(env):
