@@ -1378,8 +1378,19 @@ __global__ __launch_bounds__(kTileInThreads, 1) void k_sage_input_tile(LinearArg
   __shared__ __attribute__((aligned(1024))) char lds[kTileInLds];
   const long long M = a.counts[a.hop];
   const long long n_tiles = (M + TM - 1) / TM;
-  if ((long long)blockIdx.x >= n_tiles) return;
-  const int n_my = (int)((n_tiles - blockIdx.x + gridDim.x - 1) / gridDim.x);  // tiles blockIdx.x, + gridDim.x, ...
+  // Tiles blockIdx.x, + gridDim.x, ... in rounds.  The tiles of a last round that fills at most half of the workgroups
+  // are taken by two workgroups each: both build the tile, each multiplies half of the passes over the output's
+  // columns (the workgroups would otherwise idle for a whole tile while the others finish).
+  const int n_pass = (a.N + 127) / 128;
+  const int n_full = (int)(n_tiles / gridDim.x);
+  const int rem = (int)(n_tiles - (long long)n_full * gridDim.x);
+  const bool halves = n_pass >= 2 && rem > 0 && 2 * rem <= (int)gridDim.x;
+  const bool has_last = halves ? (int)blockIdx.x < 2 * rem : (int)blockIdx.x < rem;
+  const int n_my = n_full + (has_last ? 1 : 0);
+  if (n_my == 0) return;
+  const long long last_tile = (long long)n_full * gridDim.x + (halves ? (int)blockIdx.x >> 1 : (int)blockIdx.x);
+  const int last_p0 = halves && (blockIdx.x & 1) ? n_pass / 2 : 0;
+  const int last_p1 = halves && !(blockIdx.x & 1) ? n_pass / 2 : n_pass;
   const int tid = (int)threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int h = lane >> 5, ll = lane & 31;
@@ -1399,7 +1410,7 @@ __global__ __launch_bounds__(kTileInThreads, 1) void k_sage_input_tile(LinearArg
     for (int it = 0; it < n_my; ++it) {
       {
         char* const buf = lds + (it & 1) * kTileInBufBytes;
-        const long long row0 = ((long long)blockIdx.x + (long long)it * gridDim.x) * TM;
+        const long long row0 = (it < n_full ? (long long)blockIdx.x + (long long)it * gridDim.x : last_tile) * TM;
         // self rows: this wave's sixteen rows of every slab (lane -> row, chunk of four k; chunk position xor-ed with row bits)
         {
           long long r_l = row0 + 16 * pw + (lane >> 2);
@@ -1507,11 +1518,10 @@ __global__ __launch_bounds__(kTileInThreads, 1) void k_sage_input_tile(LinearArg
   static_assert(n % D == 0 && P >= 2, "rotation of the weight registers");
   const unsigned lane_off = (unsigned)(4 * h * N + ll);
   float bq[D][8];
-  // q_s, q_c: the next slab to request (the wavefront streams n_my * passes * n slabs: tile after tile, pass after
-  // pass; the weights do not depend on the tile).  A wavefront whose columns lie beyond the output's width in the
+  // q_s, q_c, q_it: the next slab to request, its pass's first column and its tile's number here (the wavefront
+  // streams its tiles' passes one after the other; the weights depend on the pass only).  A wavefront whose columns lie beyond the output's width in the
   // last pass (N = 64 mod 128) loads columns 0 - 31 instead and stores nothing.
-  const int n_pass = (N + 127) / 128;
-  int q_s = 0, q_c = 0;
+  int q_s = 0, q_it = 0, q_c = 128 * (n_full > 0 ? 0 : last_p0);
 #define DCI_T_LOADB(SET)                                                                                       \
   do {                                                                                                         \
     const int qc_ = q_c + cw < N ? q_c + cw : 0;                                                               \
@@ -1525,7 +1535,10 @@ __global__ __launch_bounds__(kTileInThreads, 1) void k_sage_input_tile(LinearArg
     if (++q_s == n) {                                                                                          \
       q_s = 0;                                                                                                 \
       q_c += 128;                                                                                              \
-      if (q_c >= N) q_c = 0;                                                                                   \
+      if (q_c >= 128 * (q_it < n_full ? n_pass : last_p1)) { /* on to the next tile's first pass */            \
+        ++q_it;                                                                                                \
+        q_c = 128 * (q_it < n_full ? 0 : last_p0);                                                             \
+      }                                                                                                        \
     }                                                                                                          \
   } while (0)
 // Per output element one running sum over k in ascending order, as in k_sage_linear_res; the two row blocks alternate,
@@ -1586,19 +1599,20 @@ __global__ __launch_bounds__(kTileInThreads, 1) void k_sage_input_tile(LinearArg
 #pragma unroll
   for (int i = 0; i < P; ++i) DCI_T_LOADB(i);  // slabs 0 .. P-1 of the first pass
   for (int it = 0; it < n_my; ++it) {
-    const long long row0 = ((long long)blockIdx.x + (long long)it * gridDim.x) * TM;
+    const long long row0 = (it < n_full ? (long long)blockIdx.x + (long long)it * gridDim.x : last_tile) * TM;
+    const int p0 = it < n_full ? 0 : last_p0, p1 = it < n_full ? n_pass : last_p1;
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wavefront's reads of the previous tile's buffer are complete
     __builtin_amdgcn_s_barrier();                        // tile `it` is in its buffer
     const unsigned la0 = lds0 + (it & 1) * kTileInBufBytes + ll * 64 + ((h ^ ((ll >> 2) & 3)) * 16);
     const unsigned la1 = la0 ^ 32u;
-    for (int pass = 0; pass < n_pass; ++pass) {
+    for (int pass = p0; pass < p1; ++pass) {
       floatx16 acc0, acc1;  // rows 0 - 31 and 32 - 63
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         acc0[r] = 0.f;
         acc1[r] = 0.f;
       }
-      if (it == n_my - 1 && pass == n_pass - 1) DCI_T_PASS(true);
+      if (it == n_my - 1 && pass == p1 - 1) DCI_T_PASS(true);
       else DCI_T_PASS(false);
       // Out through the wavefront's own 8 KB of LDS, so that a lane stores 16 bytes of a row: eight stores per pass
       // instead of 32.  The wavefront's memory operations retire in order, so a wait for a weight load also waits for

@@ -974,16 +974,18 @@ def test_input_layer_in_one_kernel_matches_the_two_kernel_route(env, F, hidden, 
     assert out[2][0].tobytes() == out[2][1].tobytes()
 
 
-@pytest.mark.parametrize("F,hidden,fanouts,model,n_seeds", [(128, 256, (5, 10), 0, 200), (112, 320, (5, 10), 1, 333),
-                                                            (64, 512, (3, 16), 0, 97), (32, 64, (2, 25), 0, 150),
-                                                            (48, 192, (4, 40), 1, 64), (128, 256, (7,), 0, 1)])
-def test_input_layer_in_one_kernel_of_64_row_tiles(env, F, hidden, fanouts, model, n_seeds):
+@pytest.mark.parametrize("F,hidden,fanouts,model,n_seeds,room", [(128, 256, (5, 10), 0, 200, 1), (112, 320, (5, 10), 1, 333, 1),
+                                                                 (64, 512, (3, 16), 0, 97, 1), (32, 64, (2, 25), 0, 150, 1),
+                                                                 (48, 192, (4, 40), 1, 64, 1), (128, 256, (7,), 0, 1, 1),
+                                                                 (128, 256, (5, 10), 0, 200, 3), (64, 384, (3, 16), 0, 97, 4)])
+def test_input_layer_in_one_kernel_of_64_row_tiles(env, F, hidden, fanouts, model, n_seeds, room):
     """The first layer as one kernel in its other form (half of a workgroup aggregates 64 rows into LDS while the other
     half multiplies the 64 before), forced on at small sizes: against the oracle, and - where the output width allows
     that kernel - bit for bit against the aggregation kernel followed by the weights-in-registers dense kernel, whose
     order of summation it shares.  Two to eight slabs per operand, output widths that end inside a pass of 128 columns,
     rows with more edges than the sixteen loaded at once, empty rows, a last tile of one row, cached rows read in place
-    and gathered rows."""
+    and gathered rows; with `room` > 1 the batch's buffers are sized for `room` times as many seeds, so that the launch has
+    more than twice as many workgroups as tiles and two workgroups share every tile (one half of the passes each)."""
     dci, gu, ctx, tiny, w = (env[k] for k in ("dci", "gu", "ctx", "tiny", "w"))
     N = w.num_nodes
     feat = synth.features(N, F, 190 + F)
@@ -1000,7 +1002,7 @@ def test_input_layer_in_one_kernel_of_64_row_tiles(env, F, hidden, fanouts, mode
     remap = np.full(N, -1, dtype=np.int32)
     remap[rows] = np.arange(len(rows), dtype=np.int32)
     cache = gu.upload_cache(np.full(N, -1), np.zeros(1, np.int64), np.zeros(0, np.int64), remap, feat[rows])
-    blk = dci.Blocks(ctx, N, len(seeds), fanouts)
+    blk = dci.Blocks(ctx, N, room * len(seeds), fanouts)
     dci.dci_sample_khop(ctx, g, cache, gu.dev(seeds), 11, fanouts, w.rng_seed, blk)
     out = {}
     for kind in (3, 1):
@@ -1008,7 +1010,7 @@ def test_input_layer_in_one_kernel_of_64_row_tiles(env, F, hidden, fanouts, mode
         ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, 4)
         try:
             x = torch.full((blk.cap_nodes[-1], F), -7.0, dtype=torch.float32, device="cuda")
-            l1 = torch.zeros(len(seeds), dims[-1], dtype=torch.float32, device="cuda")
+            l1 = torch.zeros(room * len(seeds), dims[-1], dtype=torch.float32, device="cuda")
             dci.dci_gather_forward(ctx, g, cache, blk, x, model, ws, wn, bs, l1)
             x2 = torch.empty_like(x)
             l2 = torch.zeros_like(l1)
@@ -1018,7 +1020,7 @@ def test_input_layer_in_one_kernel_of_64_row_tiles(env, F, hidden, fanouts, mode
         finally:
             ctx.set_option(dci.DCI_OPT_INPUT_LAYER, 0)
             ctx.set_option(dci.DCI_OPT_LINEAR_KERNEL, 0)
-        out[kind] = (l1.cpu().numpy(), l2.cpu().numpy())
+        out[kind] = (l1.cpu().numpy()[:len(seeds)], l2.cpu().numpy()[:len(seeds)])
         _logit_check(out[kind][0], ref)
         _logit_check(out[kind][1], ref)
     assert out[3][0].tobytes() == out[3][1].tobytes()
