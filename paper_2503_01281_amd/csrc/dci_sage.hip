@@ -1342,14 +1342,15 @@ __global__ __launch_bounds__(kResThreads, 1) void k_sage_input_res(LinearArgs a,
 // at most 64 KB - is built in LDS in the [slab][row][4 chunks] layout of k_sage_linear_dma by wavefronts 4 - 7:
 // the self rows arrive by global->LDS loads; the aggregated rows they sum themselves (a half-wavefront per row, a
 // lane per 16-byte chunk, edge after edge in edge order as k_sage_mean does).  These wavefronts keep no weights or
-// accumulators, so their registers hold loads in flight: two row pairs of sixteen 16-byte loads per lane.
+// accumulators, so their registers hold loads in flight: a row pair's sixteen 16-byte loads per lane and the first
+// few of the next one's.
 // Meanwhile wavefronts 0 - 3 multiply the tile built one step earlier (two such buffers) with the weights, one
 // pass of 128 output columns after the other (32 per wavefront): every output element is one running sum over k in
 // ascending order, as in k_sage_linear_res (so the one-kernel route and the two-kernel route that ends in that kernel
 // agree to the bit), and every wavefront loads the weight values it needs straight into registers, several slabs ahead,
 // so that the multiplying wavefronts never wait for each other and the whole workgroup meets at one barrier per tile.
 // Needs two operands of K columns, 32 <= K <= 128, K a multiple of 16, an output width that is a multiple of 64,
-// 16-byte aligned rows and weights.
+// 16-byte aligned rows, weights, bias and output.
 constexpr int kTileInThreads = 512, kTileInMaxSlabs = 16, kTileInFan = 16, kTileInAhead = 4;
 constexpr int kTileInSlabBytes = TM * TK * 4;
 constexpr int kTileInBufBytes = kTileInMaxSlabs * kTileInSlabBytes;  // 64 KB
