@@ -22,6 +22,8 @@
 // grids are sized for the capacities and surplus workgroups leave at once.
 #include "dci_internal.h"
 
+#include <type_traits>
+
 namespace dci {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -1399,14 +1401,97 @@ __global__ __launch_bounds__(kTileInThreads, 1) void k_sage_input_tile(LinearArg
   constexpr int Sf = SF;  // slabs per operand (K = 16 SF); a tile's slabs: 0 .. Sf-1 self rows, Sf .. 2 Sf-1 aggregated rows
   constexpr int n = 2 * Sf;
 
+  // ---- the aggregated rows of a tile: row pairs RP0 .. RP1-1 of the sixteen rows 16 pw .. 16 pw + 15, two rows at a time
+  // (one per half of the wavefront).  Every load is issued by every lane, from a line of zeros where there is nothing to
+  // read: straight-line code, so that the loads of two row pairs are in flight together and only the oldest are waited for.
+  const long long* const zeros_ll = reinterpret_cast<const long long*>(kFuseZeros);
+  const int* const zeros_i = reinterpret_cast<const int*>(kFuseZeros);
+  const float* const zeros_f = reinterpret_cast<const float*>(kFuseZeros) + 4 * lane;
+  const bool lane_on = ll < K / 4;
+  const float4v zero4 = {0.f, 0.f, 0.f, 0.f};
+  auto aggregate = [&](char* const buf, const long long row0, const int pw, auto rp0_c, auto rp1_c) {
+    constexpr int RP0 = decltype(rp0_c)::value, RP = decltype(rp1_c)::value - RP0;
+    int lo[RP], cn[RP];
+#pragma unroll
+    for (int rp = 0; rp < RP; ++rp) {
+      const long long R = row0 + 16 * pw + 2 * (RP0 + rp) + h;
+      const long long* pb = R < M ? fa.blk_indptr + R : zeros_ll;
+      const long long e0 = pb[0], e1 = pb[1];
+      lo[rp] = (int)e0;  // edge numbers stay below 2^31 (the batch bounds are checked against that)
+      cn[rp] = (int)(e1 - e0);
+    }
+    // lane e < 16 of a half: where the row of edge e of the half's row is
+    int sidx[RP];
+    bool on[RP];
+#pragma unroll
+    for (int rp = 0; rp < RP; ++rp) {
+      on[rp] = ll < kTileInFan && ll < cn[rp];
+      sidx[rp] = *(on[rp] ? fa.blk_src + ((long long)lo[rp] + ll) : zeros_i);
+    }
+    const float* bp[RP];
+    if (fa.rowref) {
+#pragma unroll
+      for (int rp = 0; rp < RP; ++rp) {
+        const int rr = *(on[rp] ? fa.rowref + sidx[rp] : zeros_i);
+        bp[rp] = (on[rp] && rr >= 0) ? fa.cache + (long long)rr * K : fa.x_src + (long long)sidx[rp] * K;
+      }
+    } else {
+#pragma unroll
+      for (int rp = 0; rp < RP; ++rp) bp[rp] = fa.x_src + (long long)sidx[rp] * K;
+    }
+    float4v land[2][kTileInFan];
+    auto request = [&](int rp, float4v* v, int j0, int j1) {  // slots j0 .. j1-1 of the row pair
+#pragma unroll
+      for (int j = 0; j < kTileInFan; ++j) {
+        if (j < j0 || j >= j1) continue;
+        const unsigned long long pj = __shfl((unsigned long long)reinterpret_cast<uintptr_t>(bp[rp]), (lane & 32) + j, kWave);
+        const float* p = (lane_on && j < cn[rp]) ? reinterpret_cast<const float*>((uintptr_t)pj) + 4 * ll : zeros_f;
+        v[j] = load_global_f4(p);
+      }
+    };
+    auto finish = [&](int rp, const float4v* v) {
+      float4v agg = zero4;
+#pragma unroll
+      for (int j = 0; j < kTileInFan; ++j) agg += v[j];  // slots beyond the row's edges hold zero
+      const int cnt = cn[rp];
+      if (cnt > kTileInFan && lane_on) {
+        for (int e = kTileInFan; e < cnt; ++e) {
+          const int s = fa.blk_src[(long long)lo[rp] + e];
+          const int rr = fa.rowref ? fa.rowref[s] : -1;
+          const float* p = rr >= 0 ? fa.cache + (long long)rr * K : fa.x_src + (long long)s * K;
+          agg += load_global_f4(p + 4 * ll);
+        }
+      }
+      const float fc = (float)cnt;
+      const float4v r = (fa.mode == DCI_MODEL_SAGE_SUM || cnt == 0) ? agg : agg / fc;
+      if (lane_on) {
+        const int row = 16 * pw + 2 * (RP0 + rp) + h;
+        char* dst = buf + (Sf + (ll >> 2)) * kTileInSlabBytes + row * 64 + (((ll & 3) ^ ((row >> 2) & 3)) * 16);
+        *reinterpret_cast<float4v*>(dst) = r;
+      }
+    };
+    // the next row pair's first kTileInAhead slots are requested before the current one is summed, the rest after:
+    // 16 + kTileInAhead loads per lane in flight at most.  (Deeper queues only add to the latency that the other
+    // wavefronts' weight loads see behind them.)
+    request(0, land[0], 0, kTileInFan);
+#pragma unroll
+    for (int rp = 0; rp < RP; rp += 2) {
+      request(rp + 1, land[1], 0, kTileInAhead);
+      finish(rp, land[0]);
+      request(rp + 1, land[1], kTileInAhead, kTileInFan);
+      if (rp + 2 < RP) request(rp + 2, land[0], 0, kTileInAhead);
+      finish(rp + 1, land[1]);
+      if (rp + 2 < RP) request(rp + 2, land[0], kTileInAhead, kTileInFan);
+    }
+  };
+  using rp_c0 = std::integral_constant<int, 0>;
+  using rp_c4 = std::integral_constant<int, 4>;
+  using rp_c8 = std::integral_constant<int, 8>;
+  const long long row0_first = (n_full > 0 ? (long long)blockIdx.x : last_tile) * TM;
+
   if (wave >= 4) {
     // ================= building tiles =================
     const int pw = wave - 4;
-    const long long* const zeros_ll = reinterpret_cast<const long long*>(kFuseZeros);
-    const int* const zeros_i = reinterpret_cast<const int*>(kFuseZeros);
-    const float* const zeros_f = reinterpret_cast<const float*>(kFuseZeros) + 4 * lane;
-    const bool lane_on = ll < K / 4;
-    const float4v zero4 = {0.f, 0.f, 0.f, 0.f};
     const int c_a = (lane & 3) ^ ((lane >> 4) & 3);
     for (int it = 0; it < n_my; ++it) {
       {
@@ -1421,82 +1506,9 @@ __global__ __launch_bounds__(kTileInThreads, 1) void k_sage_input_tile(LinearArg
           for (int s = 0; s < Sf; ++s)
             __builtin_amdgcn_global_load_lds((gptr_t)(pa + TK * s), (lptr_t)(buf + s * kTileInSlabBytes + 1024 * pw), 16, 0, 0);
         }
-        // aggregated rows 16 pw .. 16 pw + 15 of the tile, two at a time (one per half of the wavefront).  Every load below
-        // is issued by every lane, from a line of zeros where there is nothing to read: straight-line code, so that
-        // the loads of two row pairs are in flight together and only the oldest are waited for.
-        constexpr int RP = 8;
-        int lo[RP], cn[RP];
-#pragma unroll
-        for (int rp = 0; rp < RP; ++rp) {
-          const long long R = row0 + 16 * pw + 2 * rp + h;
-          const long long* pb = R < M ? fa.blk_indptr + R : zeros_ll;
-          const long long e0 = pb[0], e1 = pb[1];
-          lo[rp] = (int)e0;  // edge numbers stay below 2^31 (the batch bounds are checked against that)
-          cn[rp] = (int)(e1 - e0);
-        }
-        // lane e < 16 of a half: where the row of edge e of the half's row is
-        int sidx[RP];
-        bool on[RP];
-#pragma unroll
-        for (int rp = 0; rp < RP; ++rp) {
-          on[rp] = ll < kTileInFan && ll < cn[rp];
-          sidx[rp] = *(on[rp] ? fa.blk_src + ((long long)lo[rp] + ll) : zeros_i);
-        }
-        const float* bp[RP];
-        if (fa.rowref) {
-#pragma unroll
-          for (int rp = 0; rp < RP; ++rp) {
-            const int rr = *(on[rp] ? fa.rowref + sidx[rp] : zeros_i);
-            bp[rp] = (on[rp] && rr >= 0) ? fa.cache + (long long)rr * K : fa.x_src + (long long)sidx[rp] * K;
-          }
-        } else {
-#pragma unroll
-          for (int rp = 0; rp < RP; ++rp) bp[rp] = fa.x_src + (long long)sidx[rp] * K;
-        }
-        float4v land[2][kTileInFan];
-        auto request = [&](int rp, float4v* v, int j0, int j1) {  // slots j0 .. j1-1 of the row pair
-#pragma unroll
-          for (int j = 0; j < kTileInFan; ++j) {
-            if (j < j0 || j >= j1) continue;
-            const unsigned long long pj = __shfl((unsigned long long)reinterpret_cast<uintptr_t>(bp[rp]), (lane & 32) + j, kWave);
-            const float* p = (lane_on && j < cn[rp]) ? reinterpret_cast<const float*>((uintptr_t)pj) + 4 * ll : zeros_f;
-            v[j] = load_global_f4(p);
-          }
-        };
-        auto finish = [&](int rp, const float4v* v) {
-          float4v agg = zero4;
-#pragma unroll
-          for (int j = 0; j < kTileInFan; ++j) agg += v[j];  // slots beyond the row's edges hold zero
-          const int cnt = cn[rp];
-          if (cnt > kTileInFan && lane_on) {
-            for (int e = kTileInFan; e < cnt; ++e) {
-              const int s = fa.blk_src[(long long)lo[rp] + e];
-              const int rr = fa.rowref ? fa.rowref[s] : -1;
-              const float* p = rr >= 0 ? fa.cache + (long long)rr * K : fa.x_src + (long long)s * K;
-              agg += load_global_f4(p + 4 * ll);
-            }
-          }
-          const float fc = (float)cnt;
-          const float4v r = (fa.mode == DCI_MODEL_SAGE_SUM || cnt == 0) ? agg : agg / fc;
-          if (lane_on) {
-            const int row = 16 * pw + 2 * rp + h;
-            char* dst = buf + (Sf + (ll >> 2)) * kTileInSlabBytes + row * 64 + (((ll & 3) ^ ((row >> 2) & 3)) * 16);
-            *reinterpret_cast<float4v*>(dst) = r;
-          }
-        };
-        // the next row pair's first kTileInAhead slots are requested before the current one is summed, the rest after:
-        // 16 + kTileInAhead loads per lane in flight at most.  (Deeper queues only add to the latency that the other
-        // wavefronts' weight loads see behind them.)
-        request(0, land[0], 0, kTileInFan);
-#pragma unroll
-        for (int rp = 0; rp < RP; rp += 2) {
-          request(rp + 1, land[1], 0, kTileInAhead);
-          finish(rp, land[0]);
-          request(rp + 1, land[1], kTileInAhead, kTileInFan);
-          if (rp + 2 < RP) request(rp + 2, land[0], 0, kTileInAhead);
-          finish(rp + 1, land[1]);
-          if (rp + 2 < RP) request(rp + 2, land[0], kTileInAhead, kTileInFan);
-        }
+        // the first tile's rows are shared with the multiplying wavefronts, which have nothing to multiply yet
+        if (it == 0) aggregate(buf, row0, pw, rp_c0{}, rp_c4{});
+        else aggregate(buf, row0, pw, rp_c0{}, rp_c8{});
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // the self rows have landed, the aggregated rows are written
       }
       __builtin_amdgcn_s_barrier();  // tile `it` is complete; the other wavefronts are done with the buffer of tile it - 1
@@ -1596,6 +1608,10 @@ __global__ __launch_bounds__(kTileInThreads, 1) void k_sage_input_tile(LinearArg
     DCI_T_STEP(f0, f1, f2, 15, LAST)                                                                              \
   } while (0)
 
+  // Nothing to multiply yet: this wavefront sums the second half of the rows of the first tile that wavefront 4 + wave
+  // is building (its registers are free for the loads until the weights come in).
+  aggregate(lds, row0_first, wave, rp_c4{}, rp_c8{});
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // those rows are written before the first barrier below
   FragA f0 = {}, f1 = {}, f2 = {};
 #pragma unroll
   for (int i = 0; i < P; ++i) DCI_T_LOADB(i);  // slabs 0 .. P-1 of the first pass
@@ -1613,13 +1629,18 @@ __global__ __launch_bounds__(kTileInThreads, 1) void k_sage_input_tile(LinearArg
         acc0[r] = 0.f;
         acc1[r] = 0.f;
       }
+      // the pass's bias values, asked for now: at the end of the pass they would be a memory round trip on the critical path
+      const int c4 = 4 * (lane & 7);
+      const bool cols_ok = pass * 128 + cw < N;
+      const int colb = cols_ok ? pass * 128 + cw + c4 : c4;
+      const float4v b4 = *reinterpret_cast<const float4v*>(a.bias + colb);
       if (it == n_my - 1 && pass == p1 - 1) DCI_T_PASS(true);
       else DCI_T_PASS(false);
       // Out through the wavefront's own 8 KB of LDS, so that a lane stores 16 bytes of a row: eight stores per pass
       // instead of 32.  The wavefront's memory operations retire in order, so a wait for a weight load also waits for
       // every store before it; 32 stores between the loads would fill the counter and hold the next pass up for as
       // long as the stores take.
-      if (pass * 128 + cw < N) {
+      if (cols_ok) {
         float* const ob = reinterpret_cast<float*>(lds + 2 * kTileInBufBytes + wave * kTileInOutBytes);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -1627,9 +1648,6 @@ __global__ __launch_bounds__(kTileInThreads, 1) void k_sage_input_tile(LinearArg
           ob[row * 32 + ll] = acc0[r];
           ob[(row + 32) * 32 + ll] = acc1[r];
         }
-        const int c4 = 4 * (lane & 7);
-        const int colb = pass * 128 + cw + c4;
-        const float4v b4 = *reinterpret_cast<const float4v*>(a.bias + colb);
         typedef __attribute__((address_space(1))) float4v* gy4ptr_t;
         __attribute__((address_space(1))) float* yp = (__attribute__((address_space(1))) float*)(a.y + (row0 + (lane >> 3)) * N + colb);
         asm volatile("" : "+v"(yp));  // keeps the compiler from holding eight row addresses in registers from tile start on
